@@ -1,0 +1,111 @@
+"""The pins must have teeth: plant one plausible mistake at a time in a copy of
+the oracle's C source (on the CPU, never in the HIP path), rebuild it, and
+check that at least one pin test fails for every mutant."""
+import ctypes
+import os
+import subprocess
+
+import pytest
+
+import oracle
+import test_oracle_adam as t_adam
+import test_oracle_cast as t_cast
+import test_oracle_layout as t_layout
+import test_oracle_reduce as t_reduce
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+MUTANTS = [
+    ("floor_instead_of_ceil", "int64_t S = (N + W - 1) / W;", "int64_t S = N / W;"),
+    ("offsets_inclusive", "off[i] = acc;\n        acc += n;", "acc += n;\n        off[i] = acc;"),
+    ("pad_value_one", "flat[k] = 0.0f;", "flat[k] = 1.0f;"),
+    ("chunk_ignores_rank", "shard[k] = flat[(int64_t)w * S + k];", "shard[k] = flat[k];"),
+    ("cast_truncates", "(u + 0x7FFFu + lsb) >> 16", "u >> 16"),
+    ("cast_half_up", "(u + 0x7FFFu + lsb) >> 16", "(u + 0x8000u) >> 16"),
+    ("cast_half_down", "(u + 0x7FFFu + lsb) >> 16", "(u + 0x7FFFu) >> 16"),
+    ("cast_nan_not_special", "(u & 0x007FFFFFu) != 0u)", "(u & 0x007FFFFFu) != 0u && 0)"),
+    ("gather_reversed", "flat_lp + (int64_t)w * S);", "flat_lp + (int64_t)(W - 1 - w) * S);"),
+    ("reduce_acc_from_zero", "float acc = slices[0][k] / pre;", "float acc = 0.0f + slices[0][k] / pre;"),
+    ("reduce_reverse_order",
+     "float acc = slices[0][k] / pre;\n        for (int32_t w = 1; w < W; ++w) acc = acc + slices[w][k] / pre;",
+     "float acc = slices[W - 1][k] / pre;\n        for (int32_t w = W - 2; w >= 0; --w) acc = acc + slices[w][k] / pre;"),
+    ("reduce_reciprocal_post", "out[k] = acc / post;", "out[k] = acc * (1.0f / post);"),
+    ("reduce_no_post", "out[k] = acc / post;", "out[k] = acc;"),
+    ("reduce_pre_after_sum",
+     "float acc = slices[0][k] / pre;\n        for (int32_t w = 1; w < W; ++w) acc = acc + slices[w][k] / pre;\n        out[k] = acc / post;",
+     "float acc = slices[0][k];\n        for (int32_t w = 1; w < W; ++w) acc = acc + slices[w][k];\n        out[k] = acc / pre / post;"),
+    ("scatter_wrong_slice", "sl[w] = gradbufs[w] + (int64_t)r * S;", "sl[w] = gradbufs[w] + (int64_t)(r ? r - 1 : 0) * S;"),
+    ("bf16_upcast_shift", "(uint32_t)h << 16", "(uint32_t)h << 15"),
+    ("adam_eps_inside_sqrt", "sqrtf(vk) / sqrt_bc2 + eps;", "sqrtf(vk + eps) / sqrt_bc2;"),
+    ("adam_no_bias_correction2", "float sqrt_bc2 = sqrtf(bc2);", "float sqrt_bc2 = 1.0f;"),
+    ("adam_no_bias_correction1", "float step_size = lr / bc1;", "float step_size = lr;"),
+    ("adam_v_not_squared", "one_m_b2 * gk * gk;", "one_m_b2 * gk;"),
+    ("adam_betas_swapped", "float mk = beta1 * m[k] + one_m_b1 * gk;", "float mk = beta2 * m[k] + one_m_b2 * gk;"),
+    ("adam_ascent", "p[k] = p[k] - step_size", "p[k] = p[k] + step_size"),
+    ("adam_state_not_stored", "        m[k] = mk;\n", ""),
+]
+
+
+def _pins():
+    pins = [
+        lambda: t_layout.test_fig3_worked_example(GOLDEN),
+        t_layout.test_layout_special_cases,
+        t_layout.test_config_sizes_table,
+        t_layout.test_flatten_is_row_major_and_order_sensitive,
+        lambda: t_layout.test_padding_closed_form_and_bound(3),
+        lambda: t_layout.test_flatten_matches_concatenate_and_views_invert(3),
+        lambda: t_layout.test_unshard_bf16_is_cast_of_parameters(3),
+        t_cast.test_hand_vectors,
+        t_cast.test_nan_stays_quiet_nan_with_sign,
+        t_cast.test_nearest_neighbour_in_exact_arithmetic,
+        lambda: t_reduce.test_brute_force_sum_then_slice_tiny(4, 2.0, 2.0),
+        lambda: t_reduce.test_brute_force_sum_then_slice_tiny(12, 4.0, 3.0),
+        lambda: t_reduce.test_brute_force_sum_then_slice_tiny(3, 3.0, 1.0),
+        t_reduce.test_pre_divide_happens_before_the_sum,
+        t_reduce.test_minus_zero_survives,
+        t_reduce.test_order_witness_sequential_rank_order,
+        t_reduce.test_integer_gradients_give_exact_mean,
+        t_reduce.test_pre_and_post_are_true_divisions,
+        t_reduce.test_bf16_inputs_upcast_exactly,
+        t_adam.test_closed_form_first_step_from_zero_state,
+        lambda: t_adam.test_single_step_matches_torch_adam_float64(5),
+        t_adam.test_checkpoint_resume,
+        t_adam.test_ten_steps_track_torch_adam,
+    ]
+    return pins
+
+
+def _load(path):
+    lib = ctypes.CDLL(path)
+    lib.orc_bf16_rne.restype = ctypes.c_uint16
+    lib.orc_bf16_rne.argtypes = [ctypes.c_uint32]
+    lib.orc_num_threads.restype = ctypes.c_int
+    return lib
+
+
+def _killed() -> bool:
+    for pin in _pins():
+        try:
+            pin()
+        except (AssertionError, ValueError):
+            return True
+    return False
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_mutant_is_caught(name, old, new, tmp_path, monkeypatch):
+    src = open(os.path.join(os.path.dirname(oracle.__file__), "fsdp_oracle.c")).read()
+    assert src.count(old) >= 1, f"mutation site for {name} not found"
+    mutated = src.replace(old, new)
+    c = tmp_path / f"{name}.c"
+    so = tmp_path / f"{name}.so"
+    c.write_text(mutated)
+    subprocess.check_call(["gcc", *[f for f in oracle.CFLAGS if not f.startswith("-W")], str(c), "-o", str(so), "-lm"])
+    oracle.lib()                                    # make sure the real one is loaded first
+    monkeypatch.setattr(oracle, "_lib", _load(str(so)))
+    assert _killed(), f"no pin noticed the planted mistake '{name}'"
+
+
+def test_unmutated_oracle_passes_every_pin():
+    for pin in _pins():
+        pin()
