@@ -1,0 +1,249 @@
+#!/usr/bin/env python3
+"""Benchmark of the FlatParameter data path on one MI355X.
+
+A step is one pass of the hot path over every FSDP unit of the workload, in
+order: unshard (fp32 shards -> bf16 flat buffer, all W ranks' shards), then the
+rank-0 share of the reduce-scatter over W simulated ranks' gradient buffers and
+the sharded Adam step.  Inputs are synthetic, seeded, and resident in HBM before
+the timed region starts.
+
+Prints ONE JSON line:  metric = effective HBM GB/s (algorithmic bytes of
+unshard + reduce-scatter + Adam, summed over the units, per second).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=1, help="index into BASELINE.json configs (default 1)")
+    ap.add_argument("--max-units", type=int, default=0, help="limit the number of units (0 = all)")
+    ap.add_argument("--mode", choices=["fused", "separate"], default="fused",
+                    help="fused: reduce-scatter + Adam in one launch; separate: the two entry points")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
+                    help="rocprofv3 --pmc derived HBM bytes per launch (written by hand from profiles/)")
+    return ap.parse_args()
+
+
+class UnitState:
+    """Device buffers of one FSDP unit (caller-owned, as the library expects)."""
+
+    def __init__(self, F, wl, unit, index, torch, workloads):
+        W = wl.world_size
+        self.name = unit.name
+        self.lay = F.fsdp_layout_init(unit.shapes, W)
+        S, P, N = self.lay.shard, self.lay.padded, self.lay.numel
+        self.S, self.P, self.N, self.W = S, P, N, W
+        self.gbytes = 4 if wl.grad_dtype == "f32" else 2
+        params = workloads.gen_params(unit, index, device="cuda")
+        self.shard_base = torch.empty(W * S, dtype=torch.float32, device="cuda")
+        self.shards = [self.shard_base[w * S:(w + 1) * S] for w in range(W)]
+        F.fsdp_flatten_shard(self.lay, params, self.shards)
+        del params
+        gdt = torch.float32 if wl.grad_dtype == "f32" else torch.bfloat16
+        self.grads = []
+        for w in range(W):
+            g = torch.empty(P, dtype=gdt, device="cuda")
+            workloads.gen_rank_grad(P, N, w, index, wl.grad_dtype, device="cuda", outlier_frac=wl.outlier_frac,
+                                    outlier_scale=wl.outlier_scale, out=g)
+            self.grads.append(g)
+        self.m = torch.zeros(S, dtype=torch.float32, device="cuda")
+        self.v = torch.zeros(S, dtype=torch.float32, device="cuda")
+        self.gshard = torch.empty(S, dtype=torch.float32, device="cuda")
+        self.shard_tab = F.PtrArray(self.shards)
+        self.grad_tab = F.PtrArray(self.grads)
+        # algorithmic bytes (fixed numerators, whatever the kernels really touch)
+        self.b_unshard = 6 * P
+        self.b_reduce = self.gbytes * P + 4 * S
+        self.b_adam = 28 * S
+        self.b_total = self.b_unshard + self.b_reduce + self.b_adam
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build simulates all W ranks on ONE GPU; --gpus must be 1 "
+              "(no multi-GPU figure exists for it)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads
+    from paper_2304_11277_amd import build as fbuild
+    fbuild.build_lib(force=False)
+    import paper_2304_11277_amd as F
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = workloads.config(args.config)
+    units = list(wl.units)
+    if args.max_units:
+        units = units[:args.max_units]
+    pre, post = F.fsdp_default_divide_factors(wl.world_size)
+    t0 = time.time()
+    states = [UnitState(F, wl, u, i, torch, workloads) for i, u in enumerate(units)]
+    flat = torch.empty(max(s.P for s in states), dtype=torch.bfloat16, device="cuda")   # transient, reused
+    torch.cuda.synchronize()
+    log(f"[bench] {wl.name}: {len(states)} units, W={wl.world_size}, grads {wl.grad_dtype}, "
+        f"setup {time.time() - t0:.1f}s, HBM in use {torch.cuda.memory_allocated() / 2**30:.2f} GiB")
+    hp = (wl.lr, wl.beta1, wl.beta2, wl.eps)
+    rank = 0
+
+    def unshard(s):
+        F.fsdp_unshard(s.lay, s.shard_tab, flat[:s.P])
+
+    def reduce_adam(s, t):
+        if args.mode == "fused":
+            F.fsdp_reduce_scatter_adam_fused(s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m, s.v, t,
+                                             *hp, None)
+        else:
+            F.fsdp_reduce_scatter_local(s.lay, s.grad_tab, rank, pre, post, s.gshard)
+            F.fsdp_shard_adam_step(s.lay, s.shards[rank], s.gshard, s.m, s.v, t, *hp)
+
+    def step(t):
+        for s in states:
+            unshard(s)
+            reduce_adam(s, t)
+
+    use_graph = not args.no_graph
+    graph = None
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        step(1)                      # first-touch / module load outside any capture
+        torch.cuda.synchronize()
+        if use_graph:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                step(2)
+        run = (lambda t: graph.replay()) if use_graph else step
+
+        for i in range(args.warmup):
+            run(3 + i)
+        torch.cuda.synchronize()
+        tb = time.perf_counter()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(args.steps):
+            run(3 + args.warmup + i)
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - tb) * 1e3
+        dev_ms = e0.elapsed_time(e1)
+    ms_per_step = wall_ms / args.steps
+    step_bytes = sum(s.b_total for s in states)
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    log(f"[bench] {args.steps} steps: wall {wall_ms:.3f} ms, device {dev_ms:.3f} ms, "
+        f"{ms_per_step * 1e3:.1f} us/step, {value:.1f} GB/s effective ({100 * value / HBM_PEAK_GBPS:.1f}% of peak)")
+
+    # ---- per-kernel durations (HIP events on the launch stream) -> roofline of the dominant kernel
+    roofline = None
+    per_kernel = {}
+    if not args.no_kernel_timing:
+        reps = 20
+        kinds = {"unshard": (lambda s: unshard(s), lambda s: s.b_unshard),
+                 "reduce_adam": (lambda s: reduce_adam(s, 2), lambda s: s.b_reduce + s.b_adam)}
+        with torch.cuda.stream(stream):
+            for kind, (fn, nbytes) in kinds.items():
+                tot_us = 0.0
+                for s in states:
+                    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                           for _ in range(reps)]
+                    fn(s)
+                    for a, b in evs:
+                        a.record()
+                        fn(s)
+                        b.record()
+                    torch.cuda.synchronize()
+                    us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+                    tot_us += sum(us) / len(us)
+                nb = sum(nbytes(s) for s in states)
+                per_kernel[kind] = {"launches_per_step": len(states) * (2 if kind == "reduce_adam" and args.mode == "separate" else 1),
+                                    "avg_us": tot_us / len(states), "alg_bytes_per_launch": nb / len(states),
+                                    "GBps": nb / (tot_us * 1e-6) / 1e9}
+        dom = max(per_kernel, key=lambda k: per_kernel[k]["avg_us"])
+        traffic = None
+        try:
+            with open(args.traffic_json) as fh:
+                traffic = json.load(fh).get(f"{wl.name}:{args.mode}:{dom}")
+        except (OSError, ValueError):
+            pass
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": round(per_kernel[dom]["GBps"], 1),
+                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(per_kernel[dom]["GBps"] / HBM_PEAK_GBPS, 4),
+                    "traffic": traffic, "avg_launch_us": round(per_kernel[dom]["avg_us"], 2),
+                    "alg_bytes_per_launch": per_kernel[dom]["alg_bytes_per_launch"]}
+        for k, v in per_kernel.items():
+            log(f"[bench] kernel {k}: avg {v['avg_us']:.2f} us/launch, {v['GBps']:.1f} GB/s algorithmic")
+
+    # ---- the CPU oracle on the host cores, same three operations, bounded sample
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(states, wl, pre, post, rank, hp, torch)
+
+    out = {
+        "metric": "effective HBM GB/s per FSDP unit pass: unshard + reduce-scatter + Adam",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "units": len(states), "world_size": wl.world_size,
+                   "grad_dtype": wl.grad_dtype, "unshard_dtype": "bf16", "rank": rank, "mode": args.mode,
+                   "hip_graph": use_graph, "alg_bytes_per_step": step_bytes},
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": per_kernel,
+    }
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(states, wl, pre, post, rank, hp, torch):
+    """Time the oracle (as it stands) on the host: unshard + rank share of the
+    reduce-scatter + Adam for a bounded sample of the workload's units."""
+    import numpy as np
+    import oracle
+    budget_s = 20.0
+    done_bytes = 0
+    spent = 0.0
+    n_units = 0
+    for s in states:
+        h_shards = [x.cpu().numpy() for x in s.shards]
+        S = s.S
+        if wl.grad_dtype == "f32":
+            h_slices = [g[rank * S:(rank + 1) * S].cpu().numpy() for g in s.grads]
+        else:
+            h_slices = [g[rank * S:(rank + 1) * S].cpu().view(torch.int16).numpy().view(np.uint16) for g in s.grads]
+        h_m, h_v = s.m.cpu().numpy(), s.v.cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.unshard_bf16(h_shards)
+        g = oracle.reduce_slices(h_slices, pre, post)
+        oracle.adam_f32(h_shards[rank], g, h_m, h_v, 1, *hp)
+        spent += time.perf_counter() - t0
+        done_bytes += s.b_total
+        n_units += 1
+        if spent > budget_s:
+            break
+    return {"value": round(done_bytes / spent / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "sample": f"first {n_units} of {len(states)} units of {wl.name}, one pass, "
+                                        f"{spent:.2f} s of oracle time"}
+
+
+if __name__ == "__main__":
+    main()

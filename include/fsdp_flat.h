@@ -1,0 +1,148 @@
+/*
+ * fsdp_flat.h -- C ABI of libfsdp_flat: the per-rank FlatParameter data path of
+ * Fully Sharded Data Parallel (arXiv 2304.11277) for AMD MI355X (gfx950).
+ *
+ * Notation (Sec. 3.2.1): a unit has p parameters with numels n_i,
+ * off_i = sum_{j<i} n_j, N = off_p; W is the sharding factor (full sharding:
+ * the world size); S = ceil(N / W) is the shard size, P = S * W the padded
+ * FlatParameter size, pad = P - N (at most W - 1).
+ *
+ * Conventions shared by every entry point
+ *  - Return value: FSDP_OK (0) or a negative fsdp_status_t.  All argument
+ *    checks happen on the host before anything is launched; on error nothing
+ *    has been launched and no output is written.
+ *  - "dev" pointers are device (HBM) addresses; pointer *tables* (param_ptrs,
+ *    shard_ptrs, grad_ptrs) are HOST arrays of device addresses and are read
+ *    during the call only.  The caller owns every device buffer; the library
+ *    owns only fsdp_layout_t (host memory).
+ *  - Compute calls are asynchronous on hip_stream (a hipStream_t passed as
+ *    void*; NULL = the default stream) of the current device.  They never
+ *    synchronise, never allocate and may be captured in a HIP graph.
+ *  - Device buffers need only element alignment (4 B for fp32, 2 B for bf16),
+ *    so contiguous shards base + w * S with odd S are legal.  Buffers of
+ *    different roles must not overlap.
+ *  - bf16 is the upper half of an IEEE binary32 pattern (uint16_t).
+ *  - A layout is immutable after init; calls that share a layout may run
+ *    concurrently from several host threads and on several streams.
+ */
+#ifndef FSDP_FLAT_H
+#define FSDP_FLAT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fsdp_layout fsdp_layout_t;   /* opaque, library-owned, host memory */
+
+typedef enum { FSDP_F32 = 0, FSDP_BF16 = 1 } fsdp_dtype_t;
+
+typedef enum {
+    FSDP_OK = 0,
+    FSDP_ERR_INVALID_ARG = -1,  /* non-positive count, negative dim, N == 0, bad factor / hyper-parameter,
+                                   misaligned device pointer */
+    FSDP_ERR_NULL_PTR = -2,     /* a required pointer (or table entry) is NULL */
+    FSDP_ERR_OVERFLOW = -3,     /* a numel or 4 * P does not fit in int64 */
+    FSDP_ERR_OOM = -4,          /* host allocation failed */
+    FSDP_ERR_BAD_DTYPE = -5,    /* dtype enum out of range */
+    FSDP_ERR_RANK_RANGE = -6,   /* rank or parameter index out of range */
+    FSDP_ERR_HIP = -7           /* a kernel launch failed; see fsdp_last_hip_error() */
+} fsdp_status_t;
+
+/* Maximum number of rank pointers one kernel launch takes; larger W is split
+ * into several launches by the library (results are unchanged). */
+#define FSDP_MAX_RANKS_PER_LAUNCH 64
+
+/* ---- layout (Sec. 3.2.1: flatten-concat-pad-chunk) -------------------------
+ * dims:  host, all parameters' dims concatenated in parameter order.
+ * ndims: host [num_params]; 0 = scalar (numel 1); a zero dim = numel 0 (legal).
+ * Computes off_i (exclusive prefix sum), N, S, P, pad.  Host only; touches no
+ * device.  *out must be released with fsdp_layout_destroy. */
+int fsdp_layout_init(const int64_t* dims, const int32_t* ndims, int32_t num_params,
+                     int32_t world_size, fsdp_layout_t** out);
+void fsdp_layout_destroy(fsdp_layout_t* layout);           /* NULL is a no-op */
+
+/* Queries (host only).  Any out pointer may be NULL to skip that field. */
+int fsdp_layout_info(const fsdp_layout_t* layout, int64_t* numel /*N*/, int64_t* padded /*P*/,
+                     int64_t* shard /*S*/, int64_t* pad, int32_t* num_params, int32_t* world_size);
+int fsdp_layout_param(const fsdp_layout_t* layout, int32_t i, int64_t* offset /*off_i*/,
+                      int64_t* numel /*n_i*/);
+
+/* Sec. 3.2.3: the original parameters are views into the unsharded
+ * FlatParameter.  *out = flat_base + off_i * sizeof(dtype); zero bytes move. */
+int fsdp_view_ptr(const fsdp_layout_t* layout, void* flat_base, fsdp_dtype_t dtype, int32_t i,
+                  void** out);
+
+/* Convention of this library (the paper's eq. (1) is a plain sum): split the
+ * data-parallel mean's divisor W as pre * post, pre being the smallest power of
+ * two that divides W with pre * pre >= W or, if there is none, the largest power
+ * of two dividing W.  W=8 -> (4,2), 12 -> (4,3), 16 -> (4,4), 64 -> (8,8),
+ * 6 -> (2,3), odd W -> (1,W).  A power-of-two pre makes the pre-divide exact. */
+int fsdp_default_divide_factors(int32_t world_size, float* pre, float* post);
+
+/* ---- Sec. 3.2.1: build the sharded FlatParameter ---------------------------
+ * param_ptrs: host [p] of dev fp32 arrays, parameter i holding n_i elements in
+ *             row-major order (entries with n_i == 0 are ignored, may be NULL).
+ * shard_ptrs: host [W] of dev fp32 arrays of S elements each (written).
+ * shard_w[k] = flat[w * S + k] where flat = concat_i(param_i) followed by pad
+ * zeros (+0.0f).  Every element of every shard is written exactly once. */
+int fsdp_flatten_shard(const fsdp_layout_t* layout, const void* const* param_ptrs,
+                       float* const* shard_ptrs, void* hip_stream);
+
+/* ---- Sec. 3 / 3.2.1 unshard (AllGather with even inputs into one tensor),
+ * fused with Sec. 4.4's full-to-low precision cast of each local shard -------
+ * shard_ptrs: host [W] of dev fp32 shards, S elements each (read).
+ * flat_out:   dev, P elements of out_dtype (written, pad included).
+ * FSDP_BF16: flat_out[w * S + k] = bf16_rne(shard_w[k]) -- round to nearest,
+ * ties to even; NaN keeps sign and top payload bits and is made quiet;
+ * denormals are rounded, not flushed.  FSDP_F32: plain gather copy. */
+int fsdp_unshard(const fsdp_layout_t* layout, const float* const* shard_ptrs, void* flat_out,
+                 fsdp_dtype_t out_dtype, void* hip_stream);
+
+/* ---- Sec. 3 / Sec. 3.2.2 eq. (1): ReduceScatter, this rank's share ----------
+ * grad_ptrs: host [W] of dev unsharded gradient buffers (P elements of
+ *            grad_dtype each); only elements [rank * S, (rank + 1) * S) of each
+ *            are read.
+ * grad_shard_out: dev fp32 [S] (written).
+ * out[k] = ((x_0 / pre) + (x_1 / pre) + ... + (x_{W-1} / pre)) / post with
+ * x_w = (float) grad_w[rank * S + k] (bf16 upcast is exact); strictly in rank
+ * order, one binary32 division and addition per rank, no fused multiply-add,
+ * accumulator initialised from rank 0's term.  pre, post: finite and > 0. */
+int fsdp_reduce_scatter_local(const fsdp_layout_t* layout, const void* const* grad_ptrs,
+                              fsdp_dtype_t grad_dtype, int32_t rank, float pre_div, float post_div,
+                              float* grad_shard_out, void* hip_stream);
+
+/* ---- Sec. 3 / Sec. 5.4: optimizer step on the sharded state (Adam) ---------
+ * p_shard, exp_avg, exp_avg_sq: dev fp32 [S], updated in place; g_shard: dev
+ * fp32 [S], read.  step >= 1 is the step count after increment.
+ * m = b1 m + (1 - b1) g;  v = b2 v + (1 - b2) g g;
+ * p = p - (lr / (1 - b1^step)) * (m / (sqrt(v) / sqrt(1 - b2^step) + eps)).
+ * binary32 element arithmetic, bias corrections evaluated in binary64 on the
+ * host.  Requires lr finite, 0 <= b1, b2 < 1, eps >= 0. */
+int fsdp_shard_adam_step(const fsdp_layout_t* layout, float* p_shard, const float* g_shard,
+                         float* exp_avg, float* exp_avg_sq, int64_t step, float lr, float beta1,
+                         float beta2, float eps, void* hip_stream);
+
+/* ---- fused reduce-scatter + Adam (same results as the two calls above) -----
+ * The reduced gradient stays in registers.  grad_shard_out (dev fp32 [S]) and
+ * p_lp_out (dev bf16 [S], receives bf16_rne of the updated p_shard, i.e. the
+ * next unshard's local cast) may each be NULL to skip that output.  With
+ * W > FSDP_MAX_RANKS_PER_LAUNCH, grad_shard_out is required (it carries the
+ * partial sum between launches). */
+int fsdp_reduce_scatter_adam_fused(const fsdp_layout_t* layout, const void* const* grad_ptrs,
+                                   fsdp_dtype_t grad_dtype, int32_t rank, float pre_div,
+                                   float post_div, float* grad_shard_out, float* p_shard,
+                                   float* exp_avg, float* exp_avg_sq, int64_t step, float lr,
+                                   float beta1, float beta2, float eps, void* p_lp_out,
+                                   void* hip_stream);
+
+/* Last hipError_t seen by this thread inside the library (0 if none). */
+int fsdp_last_hip_error(void);
+/* Static string for a fsdp_status_t. */
+const char* fsdp_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FSDP_FLAT_H */

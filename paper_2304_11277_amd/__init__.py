@@ -1,0 +1,24 @@
+"""MI355X-native FlatParameter data path of FSDP (arXiv 2304.11277).
+
+The product is the C-ABI library libfsdp_flat (HIP, gfx950); this package is a
+thin ctypes binding with the same entry-point names.  PyTorch supplies device
+memory and streams only.
+"""
+from .binding import (  # noqa: F401
+    FSDP_BF16,
+    FSDP_F32,
+    FsdpError,
+    Layout,
+    PtrArray,
+    fsdp_default_divide_factors,
+    fsdp_flatten_shard,
+    fsdp_layout_init,
+    fsdp_reduce_scatter_adam_fused,
+    fsdp_reduce_scatter_local,
+    fsdp_shard_adam_step,
+    fsdp_unshard,
+    fsdp_view_ptr,
+    fsdp_views,
+    lib,
+    library_path,
+)

@@ -1,0 +1,283 @@
+"""ctypes binding of libfsdp_flat: argument marshalling only.
+
+Every function here has the name and argument order of the C entry point it
+wraps (include/fsdp_flat.h).  Tensors are checked (device, dtype, contiguity,
+size) and reduced to raw device addresses; all work happens in the library's
+HIP kernels.  There is no CPU fallback: if the library is not built, loading
+fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+FSDP_F32 = 0
+FSDP_BF16 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libfsdp_flat.so")
+
+_STATUS = {
+    0: "ok", -1: "invalid argument", -2: "null pointer", -3: "size overflows int64",
+    -4: "host allocation failed", -5: "bad dtype", -6: "rank or parameter index out of range",
+    -7: "HIP launch error",
+}
+
+
+class FsdpError(RuntimeError):
+    def __init__(self, fn: str, status: int, hip_error: int = 0):
+        self.status = status
+        self.hip_error = hip_error
+        msg = f"{fn} failed: {status} ({_STATUS.get(status, 'unknown')})"
+        if status == -7:
+            msg += f", hipError_t={hip_error}"
+        super().__init__(msg)
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+_lib = None
+
+_i32, _i64, _f32, _vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_void_p
+_pp = ctypes.POINTER(ctypes.c_void_p)
+
+_SIGNATURES = {
+    "fsdp_layout_init": [ctypes.POINTER(_i64), ctypes.POINTER(_i32), _i32, _i32, ctypes.POINTER(_vp)],
+    "fsdp_layout_info": [_vp, ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.POINTER(_i64),
+                         ctypes.POINTER(_i64), ctypes.POINTER(_i32), ctypes.POINTER(_i32)],
+    "fsdp_layout_param": [_vp, _i32, ctypes.POINTER(_i64), ctypes.POINTER(_i64)],
+    "fsdp_view_ptr": [_vp, _vp, ctypes.c_int, _i32, ctypes.POINTER(_vp)],
+    "fsdp_default_divide_factors": [_i32, ctypes.POINTER(_f32), ctypes.POINTER(_f32)],
+    "fsdp_flatten_shard": [_vp, _pp, _pp, _vp],
+    "fsdp_unshard": [_vp, _pp, _vp, ctypes.c_int, _vp],
+    "fsdp_reduce_scatter_local": [_vp, _pp, ctypes.c_int, _i32, _f32, _f32, _vp, _vp],
+    "fsdp_shard_adam_step": [_vp, _vp, _vp, _vp, _vp, _i64, _f32, _f32, _f32, _f32, _vp],
+    "fsdp_reduce_scatter_adam_fused": [_vp, _pp, ctypes.c_int, _i32, _f32, _f32, _vp, _vp, _vp, _vp, _i64,
+                                       _f32, _f32, _f32, _f32, _vp, _vp],
+    "fsdp_last_hip_error": [],
+}
+
+
+def lib() -> ctypes.CDLL:
+    """Load libfsdp_flat.so (built in-tree by paper_2304_11277_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                f"{_LIB_PATH} is not built; run `python -m paper_2304_11277_amd.build` "
+                "(there is no fallback path)")
+        l = ctypes.CDLL(_LIB_PATH)
+        for name, argtypes in _SIGNATURES.items():
+            fn = getattr(l, name)
+            fn.argtypes = argtypes
+            fn.restype = ctypes.c_int
+        l.fsdp_layout_destroy.argtypes = [_vp]
+        l.fsdp_layout_destroy.restype = None
+        l.fsdp_status_string.argtypes = [ctypes.c_int]
+        l.fsdp_status_string.restype = ctypes.c_char_p
+        _lib = l
+    return _lib
+
+
+def _check(fn: str, status: int) -> None:
+    if status != 0:
+        raise FsdpError(fn, status, lib().fsdp_last_hip_error() if status == -7 else 0)
+
+
+class PtrArray:
+    """A host array of device addresses, marshalled once and reusable across
+    calls (keeps the tensors alive)."""
+
+    def __init__(self, tensors: Sequence[torch.Tensor], allow_empty: bool = False):
+        self.tensors = list(tensors)
+        addrs = [(t.data_ptr() if t.numel() or not allow_empty else 0) for t in self.tensors]
+        self.array = (ctypes.c_void_p * max(1, len(addrs)))(*addrs)
+        self.n = len(addrs)
+
+
+def _stream_handle(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, torch.cuda.Stream):
+        return ctypes.c_void_p(stream.cuda_stream)
+    return ctypes.c_void_p(int(stream))
+
+
+def _dev_tensor(t: torch.Tensor, dtype, min_numel: int, what: str) -> int:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{what}: expected a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{what}: expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what}: must be contiguous")
+    if t.numel() < min_numel:
+        raise ValueError(f"{what}: needs at least {min_numel} elements, has {t.numel()}")
+    return t.data_ptr()
+
+
+def _ptr_table(ts, dtype, min_numel: int, n_expected: int, what: str, allow_empty=False) -> PtrArray:
+    if isinstance(ts, PtrArray):
+        if ts.n != n_expected:
+            raise ValueError(f"{what}: expected {n_expected} entries, got {ts.n}")
+        return ts
+    ts = list(ts)
+    if len(ts) != n_expected:
+        raise ValueError(f"{what}: expected {n_expected} entries, got {len(ts)}")
+    for i, t in enumerate(ts):
+        need = min_numel[i] if isinstance(min_numel, (list, tuple)) else min_numel
+        if allow_empty and need == 0:
+            continue
+        _dev_tensor(t, dtype, need, f"{what}[{i}]")
+    return PtrArray(ts, allow_empty=allow_empty)
+
+
+class Layout:
+    """Owner of a fsdp_layout_t handle (the FlatParamHandle's bookkeeping,
+    Sec. 4.2): offsets, N, S, P, pad."""
+
+    def __init__(self, handle: int, shapes: Sequence[Tuple[int, ...]]):
+        self._h = ctypes.c_void_p(handle)
+        self.shapes = [tuple(int(d) for d in s) for s in shapes]
+        N, P, S, pad = _i64(), _i64(), _i64(), _i64()
+        p, W = _i32(), _i32()
+        _check("fsdp_layout_info", lib().fsdp_layout_info(self._h, ctypes.byref(N), ctypes.byref(P), ctypes.byref(S),
+                                                         ctypes.byref(pad), ctypes.byref(p), ctypes.byref(W)))
+        self.numel, self.padded, self.shard, self.pad = N.value, P.value, S.value, pad.value
+        self.num_params, self.world_size = p.value, W.value
+        self.offsets: List[int] = []
+        self.numels: List[int] = []
+        for i in range(self.num_params):
+            o, n = _i64(), _i64()
+            _check("fsdp_layout_param", lib().fsdp_layout_param(self._h, i, ctypes.byref(o), ctypes.byref(n)))
+            self.offsets.append(o.value)
+            self.numels.append(n.value)
+
+    @property
+    def handle(self) -> ctypes.c_void_p:
+        if self._h is None:
+            raise ValueError("layout was destroyed")
+        return self._h
+
+    def close(self) -> None:
+        if self._h is not None:
+            lib().fsdp_layout_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def fsdp_layout_init(shapes: Sequence[Sequence[int]], world_size: int) -> Layout:
+    shapes = [tuple(int(d) for d in s) for s in shapes]
+    flat = [d for s in shapes for d in s]
+    dims = (_i64 * max(1, len(flat)))(*flat)
+    ndims = (_i32 * max(1, len(shapes)))(*[len(s) for s in shapes])
+    out = _vp()
+    _check("fsdp_layout_init", lib().fsdp_layout_init(dims, ndims, len(shapes), int(world_size), ctypes.byref(out)))
+    return Layout(out.value, shapes)
+
+
+def fsdp_default_divide_factors(world_size: int) -> Tuple[float, float]:
+    pre, post = _f32(), _f32()
+    _check("fsdp_default_divide_factors",
+           lib().fsdp_default_divide_factors(int(world_size), ctypes.byref(pre), ctypes.byref(post)))
+    return pre.value, post.value
+
+
+def _flat_dtype(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return FSDP_F32
+    if t.dtype == torch.bfloat16:
+        return FSDP_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def fsdp_view_ptr(layout: Layout, flat_base: torch.Tensor, i: int) -> int:
+    """Device address of parameter i inside the unsharded flat buffer."""
+    out = _vp()
+    _check("fsdp_view_ptr", lib().fsdp_view_ptr(layout.handle, _vp(flat_base.data_ptr()), _flat_dtype(flat_base),
+                                                int(i), ctypes.byref(out)))
+    return out.value or 0
+
+
+def fsdp_views(layout: Layout, flat: torch.Tensor) -> List[torch.Tensor]:
+    """Zero-copy per-parameter tensors over the unsharded flat buffer
+    (Sec. 3.2.3); their addresses are the ones fsdp_view_ptr returns."""
+    views = []
+    for i, shp in enumerate(layout.shapes):
+        v = flat[layout.offsets[i]:layout.offsets[i] + layout.numels[i]].view(shp)
+        if v.numel() and v.data_ptr() != fsdp_view_ptr(layout, flat, i):
+            raise AssertionError("view address mismatch")
+        views.append(v)
+    return views
+
+
+def fsdp_flatten_shard(layout: Layout, param_ptrs, shard_ptrs, stream=None) -> None:
+    params = _ptr_table(param_ptrs, torch.float32, layout.numels, layout.num_params, "param_ptrs", allow_empty=True)
+    shards = _ptr_table(shard_ptrs, torch.float32, layout.shard, layout.world_size, "shard_ptrs")
+    _check("fsdp_flatten_shard", lib().fsdp_flatten_shard(layout.handle, params.array, shards.array,
+                                                         _stream_handle(stream)))
+
+
+def fsdp_unshard(layout: Layout, shard_ptrs, flat_out: torch.Tensor, stream=None) -> None:
+    shards = _ptr_table(shard_ptrs, torch.float32, layout.shard, layout.world_size, "shard_ptrs")
+    dt = _flat_dtype(flat_out)
+    _dev_tensor(flat_out, flat_out.dtype, layout.padded, "flat_out")
+    _check("fsdp_unshard", lib().fsdp_unshard(layout.handle, shards.array, _vp(flat_out.data_ptr()), dt,
+                                              _stream_handle(stream)))
+
+
+def _grad_table(layout: Layout, grad_ptrs) -> Tuple[PtrArray, int]:
+    if isinstance(grad_ptrs, PtrArray):
+        gdt = grad_ptrs.tensors[0].dtype
+    else:
+        grad_ptrs = list(grad_ptrs)
+        gdt = grad_ptrs[0].dtype
+    if gdt not in (torch.float32, torch.bfloat16):
+        raise TypeError(f"grad dtype {gdt} not supported")
+    tab = _ptr_table(grad_ptrs, gdt, layout.padded, layout.world_size, "grad_ptrs")
+    return tab, (FSDP_F32 if gdt == torch.float32 else FSDP_BF16)
+
+
+def fsdp_reduce_scatter_local(layout: Layout, grad_ptrs, rank: int, pre_div: float, post_div: float,
+                              grad_shard_out: torch.Tensor, stream=None) -> None:
+    tab, gdt = _grad_table(layout, grad_ptrs)
+    _dev_tensor(grad_shard_out, torch.float32, layout.shard, "grad_shard_out")
+    _check("fsdp_reduce_scatter_local",
+           lib().fsdp_reduce_scatter_local(layout.handle, tab.array, gdt, int(rank), float(pre_div), float(post_div),
+                                           _vp(grad_shard_out.data_ptr()), _stream_handle(stream)))
+
+
+def fsdp_shard_adam_step(layout: Layout, p_shard, g_shard, exp_avg, exp_avg_sq, step: int, lr: float, beta1: float,
+                         beta2: float, eps: float, stream=None) -> None:
+    S = layout.shard
+    ptrs = [_dev_tensor(t, torch.float32, S, n) for t, n in
+            ((p_shard, "p_shard"), (g_shard, "g_shard"), (exp_avg, "exp_avg"), (exp_avg_sq, "exp_avg_sq"))]
+    _check("fsdp_shard_adam_step",
+           lib().fsdp_shard_adam_step(layout.handle, *[_vp(x) for x in ptrs], int(step), float(lr), float(beta1),
+                                      float(beta2), float(eps), _stream_handle(stream)))
+
+
+def fsdp_reduce_scatter_adam_fused(layout: Layout, grad_ptrs, rank: int, pre_div: float, post_div: float,
+                                   grad_shard_out: Optional[torch.Tensor], p_shard, exp_avg, exp_avg_sq, step: int,
+                                   lr: float, beta1: float, beta2: float, eps: float,
+                                   p_lp_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    tab, gdt = _grad_table(layout, grad_ptrs)
+    S = layout.shard
+    g_out = _dev_tensor(grad_shard_out, torch.float32, S, "grad_shard_out") if grad_shard_out is not None else None
+    lp = _dev_tensor(p_lp_out, torch.bfloat16, S, "p_lp_out") if p_lp_out is not None else None
+    ptrs = [_dev_tensor(t, torch.float32, S, n) for t, n in
+            ((p_shard, "p_shard"), (exp_avg, "exp_avg"), (exp_avg_sq, "exp_avg_sq"))]
+    _check("fsdp_reduce_scatter_adam_fused",
+           lib().fsdp_reduce_scatter_adam_fused(layout.handle, tab.array, gdt, int(rank), float(pre_div),
+                                                float(post_div), _vp(g_out), *[_vp(x) for x in ptrs], int(step),
+                                                float(lr), float(beta1), float(beta2), float(eps), _vp(lp),
+                                                _stream_handle(stream)))

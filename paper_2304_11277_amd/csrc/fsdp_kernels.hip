@@ -1,0 +1,795 @@
+// HIP kernels and launchers of libfsdp_flat for gfx950 (MI355X, CDNA4).
+//
+// Every step of the FlatParameter data path (arXiv 2304.11277, Sec. 3.2.1,
+// 3.2.3, 4.4, eq. (1), Sec. 5.4) is a streaming pass over HBM, so the kernels
+// share one shape: each lane moves 16-byte vectors, a 256-lane workgroup owns
+// a contiguous tile, the destination side is always 16-byte aligned (ragged
+// heads and tails are peeled off and handled element-wise) and sources that
+// are only element-aligned are read through under-aligned vector types.
+// Nothing here is a contraction, so there is no MFMA.
+//
+// Build flags that matter for bit-exactness: -ffp-contract=off (no fused
+// multiply-add), IEEE-correct fp32 divide and sqrt (hipcc's default), fp32
+// denormals kept (gfx950's default).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "fsdp_internal.h"
+
+namespace {
+
+constexpr int kBlock = 256;                           // 4 wavefronts of 64 lanes
+constexpr int kMaxRanks = FSDP_MAX_RANKS_PER_LAUNCH;  // rank pointers per kernarg table
+constexpr int kMaxSegs = 24;                          // parameter segments per pack launch
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+// Same vectors with element alignment only: the compiler may still emit one
+// wide access (gfx9 global memory accepts it), never assumes more than this.
+typedef f32x4 f32x4_a4 __attribute__((aligned(4)));
+typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
+typedef u32x2 u32x2_a2 __attribute__((aligned(2)));
+
+struct PtrTable {
+    const void* p[kMaxRanks];
+};
+struct MutPtrTable {
+    float* p[kMaxRanks];
+};
+struct SegTable {
+    const float* src[kMaxSegs];   // nullptr = zero fill (the pad)
+    int64_t off[kMaxSegs + 1];    // flat offsets, off[i+1] - off[i] = segment length
+};
+
+__device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
+__device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
+
+// fp32 -> bf16, round to nearest, ties to even, on the bit pattern (Sec. 4.4's
+// full-to-low precision cast).  NaN keeps sign and top payload bits, forced quiet.
+__device__ __forceinline__ uint32_t bf16_rne(uint32_t u)
+{
+    const bool is_nan = (u & 0x7FFFFFFFu) > 0x7F800000u;
+    const uint32_t r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    return is_nan ? ((u >> 16) | 0x0040u) : r;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return bf16_rne(f2u(lo)) | (bf16_rne(f2u(hi)) << 16);
+}
+
+// number of elements (of esize bytes) from p up to the next 16-byte boundary
+__device__ __forceinline__ int64_t head_elems(const void* p, int esize, int64_t n)
+{
+    const uint32_t mis = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p)) & 15u;
+    const int64_t h = ((16u - mis) & 15u) / esize;
+    return h < n ? h : n;
+}
+
+// ---------------------------------------------------------------------------
+// unshard: flat_out[w*S + k] = cast(shard_w[k])   (Sec. 3.2.1 gather, Sec. 4.4 cast)
+// grid = nshards * tiles_per_shard blocks; block b serves shard b / tiles and
+// tile b % tiles.  A tile is kBlock * U destination vectors of 16 bytes.
+// ---------------------------------------------------------------------------
+template <int U>
+__global__ __launch_bounds__(kBlock) void unshard_bf16_kernel(PtrTable shards, int64_t S,
+                                                               uint16_t* __restrict__ out_base,
+                                                               int32_t tiles_per_shard)
+{
+    const int32_t w = blockIdx.x / tiles_per_shard;
+    const int32_t tile = blockIdx.x - w * tiles_per_shard;
+    const float* __restrict__ src = static_cast<const float*>(shards.p[w]);
+    uint16_t* __restrict__ dst = out_base + static_cast<int64_t>(w) * S;
+
+    const int64_t head = head_elems(dst, 2, S);
+    const int64_t nvec = (S - head) >> 3;                  // full 8-element destination vectors
+    const int64_t base = static_cast<int64_t>(tile) * (kBlock * U) + threadIdx.x;
+
+    f32x4 a[U], b[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t c = base + u * kBlock;
+        if (c < nvec) {
+            const float* s = src + head + (c << 3);
+            a[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(s));
+            b[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(s + 4));
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t c = base + u * kBlock;
+        if (c < nvec) {
+            u32x4 o;
+            o.x = pack_bf16x2(a[u].x, a[u].y);
+            o.y = pack_bf16x2(a[u].z, a[u].w);
+            o.z = pack_bf16x2(b[u].x, b[u].y);
+            o.w = pack_bf16x2(b[u].z, b[u].w);
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(dst + head + (c << 3)));
+        }
+    }
+    if (tile == 0) {   // ragged head and tail of this shard: at most 7 elements each
+        const int64_t tail0 = head + (nvec << 3);
+        const int64_t ntail = S - tail0;
+        const int t = threadIdx.x;
+        if (t < head) dst[t] = static_cast<uint16_t>(bf16_rne(f2u(src[t])));
+        if (t >= 64 && t - 64 < ntail) dst[tail0 + t - 64] = static_cast<uint16_t>(bf16_rne(f2u(src[tail0 + t - 64])));
+    }
+}
+
+template <int U>
+__global__ __launch_bounds__(kBlock) void unshard_f32_kernel(PtrTable shards, int64_t S,
+                                                              float* __restrict__ out_base,
+                                                              int32_t tiles_per_shard)
+{
+    const int32_t w = blockIdx.x / tiles_per_shard;
+    const int32_t tile = blockIdx.x - w * tiles_per_shard;
+    const float* __restrict__ src = static_cast<const float*>(shards.p[w]);
+    float* __restrict__ dst = out_base + static_cast<int64_t>(w) * S;
+
+    const int64_t head = head_elems(dst, 4, S);
+    const int64_t nvec = (S - head) >> 2;
+    const int64_t base = static_cast<int64_t>(tile) * (kBlock * U) + threadIdx.x;
+
+    f32x4 a[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t c = base + u * kBlock;
+        if (c < nvec) a[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(src + head + (c << 2)));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t c = base + u * kBlock;
+        if (c < nvec) __builtin_nontemporal_store(a[u], reinterpret_cast<f32x4*>(dst + head + (c << 2)));
+    }
+    if (tile == 0) {
+        const int64_t tail0 = head + (nvec << 2);
+        const int64_t ntail = S - tail0;
+        const int t = threadIdx.x;
+        if (t < head) dst[t] = src[t];
+        if (t >= 64 && t - 64 < ntail) dst[tail0 + t - 64] = src[tail0 + t - 64];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// flatten + pad + shard (Sec. 3.2.1): LDS-staged ragged pack.
+// A block owns one 16-byte-aligned destination tile of kPackTile floats in one
+// shard.  It walks the (prefix-summed) segment table for the parameters that
+// intersect the tile, copies each piece into LDS with source-aligned 16-byte
+// loads, then writes the tile out with destination-aligned 16-byte stores.  A
+// segment with a null source is the zero pad.
+// ---------------------------------------------------------------------------
+constexpr int kPackSlots = 4;                              // 16-byte slots per lane
+constexpr int kPackTile = kBlock * kPackSlots * 4;         // floats per tile (16 KiB of LDS)
+
+__global__ __launch_bounds__(kBlock) void pack_kernel(SegTable segs, int32_t nseg, MutPtrTable dsts,
+                                                      int32_t w_first, int64_t S, int64_t R0, int64_t R1,
+                                                      int32_t tiles_per_shard)
+{
+    __shared__ __attribute__((aligned(16))) float lds[kPackTile];
+
+    const int32_t wl = blockIdx.x / tiles_per_shard;
+    const int32_t tile = blockIdx.x - wl * tiles_per_shard;
+    float* __restrict__ dst = dsts.p[wl];
+    const int64_t fs = static_cast<int64_t>(w_first + wl) * S;     // flat index of dst[0]
+    const int64_t a = (reinterpret_cast<uintptr_t>(dst) >> 2) & 3;  // dst[k] is 16B-aligned iff (k + a) % 4 == 0
+    const int64_t t0 = static_cast<int64_t>(tile) * kPackTile - a; // shard-local index of LDS slot 0
+
+    // shard-local element range this block writes
+    int64_t k_lo = t0 > 0 ? t0 : 0;
+    int64_t k_hi = t0 + kPackTile < S ? t0 + kPackTile : S;
+    if (R0 - fs > k_lo) k_lo = R0 - fs;
+    if (R1 - fs < k_hi) k_hi = R1 - fs;
+    if (k_lo >= k_hi) return;                                       // uniform: whole block leaves
+    const int64_t f_lo = fs + k_lo, f_hi = fs + k_hi;
+    const int tid = threadIdx.x;
+
+    // stage [f_lo, f_hi) into lds[f - fs - t0]
+    int32_t i = 0;
+    while (i < nseg && segs.off[i + 1] <= f_lo) ++i;               // uniform scan over <= kMaxSegs entries
+    for (; i < nseg && segs.off[i] < f_hi; ++i) {
+        const int64_t lo = segs.off[i] > f_lo ? segs.off[i] : f_lo;
+        const int64_t hi = segs.off[i + 1] < f_hi ? segs.off[i + 1] : f_hi;
+        const int32_t n = static_cast<int32_t>(hi - lo);
+        float* l = lds + (lo - fs - t0);
+        const float* src = segs.src[i];
+        if (src == nullptr) {
+            for (int32_t j = tid; j < n; j += kBlock) l[j] = 0.0f;
+            continue;
+        }
+        const float* __restrict__ s = src + (lo - segs.off[i]);
+        const int32_t h = static_cast<int32_t>(head_elems(s, 4, n));
+        const int32_t nv = (n - h) >> 2;
+        if (tid < h) l[tid] = s[tid];
+        const int32_t r0 = h + (nv << 2);
+        if (tid >= 64 && tid - 64 < n - r0) l[r0 + tid - 64] = s[r0 + tid - 64];
+        for (int32_t j0 = 0; j0 < nv; j0 += kBlock * kPackSlots) {
+            f32x4 v[kPackSlots];
+#pragma unroll
+            for (int u = 0; u < kPackSlots; ++u) {
+                const int32_t j = j0 + u * kBlock + tid;
+                if (j < nv) v[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(s + h + (j << 2)));
+            }
+#pragma unroll
+            for (int u = 0; u < kPackSlots; ++u) {
+                const int32_t j = j0 + u * kBlock + tid;
+                if (j < nv) {
+                    float* q = l + h + (j << 2);
+                    q[0] = v[u].x; q[1] = v[u].y; q[2] = v[u].z; q[3] = v[u].w;
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // write out: slot q covers LDS floats [4q, 4q+4) = shard-local [t0 + 4q, t0 + 4q + 4)
+#pragma unroll
+    for (int u = 0; u < kPackSlots; ++u) {
+        const int32_t q = u * kBlock + tid;
+        const int64_t k0 = t0 + (q << 2);
+        if (k0 >= k_lo && k0 + 4 <= k_hi) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(lds + (q << 2));
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst + k0));
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (k0 + e >= k_lo && k0 + e < k_hi) dst[k0 + e] = lds[(q << 2) + e];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// reduce-scatter rank share (Sec. 3, eq. (1)) with optional fused Adam (Sec. 5.4)
+// ---------------------------------------------------------------------------
+struct AdamConsts {
+    float beta1, beta2, one_m_b1, one_m_b2, step_size, sqrt_bc2, eps;
+};
+
+enum PreMode { kPreNone = 0, kPreMul = 1, kPreDiv = 2 };
+
+// x / pre, exactly: pre == 1 is the identity, a power-of-two pre is a
+// multiplication by its (exact) reciprocal, anything else a true division.
+template <int PRE>
+__device__ __forceinline__ float pre_scale(float x, float c)
+{
+    if (PRE == kPreNone) return x;
+    if (PRE == kPreMul) return x * c;
+    return x / c;
+}
+
+__device__ __forceinline__ void adam_update(float& p, float g, float& m, float& v, const AdamConsts& c)
+{
+    const float mk = c.beta1 * m + c.one_m_b1 * g;
+    const float vk = c.beta2 * v + c.one_m_b2 * g * g;
+    const float denom = sqrtf(vk) / c.sqrt_bc2 + c.eps;
+    p = p - c.step_size * (mk / denom);
+    m = mk;
+    v = vk;
+}
+
+// four elements at once; g holds the four gradients
+__device__ __forceinline__ void adam_update4(f32x4& p, const float* g, f32x4& m, f32x4& v, const AdamConsts& c)
+{
+    float pp[4] = {p.x, p.y, p.z, p.w}, mm[4] = {m.x, m.y, m.z, m.w}, vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) adam_update(pp[e], g[e], mm[e], vv[e], c);
+    p = f32x4{pp[0], pp[1], pp[2], pp[3]};
+    m = f32x4{mm[0], mm[1], mm[2], mm[3]};
+    v = f32x4{vv[0], vv[1], vv[2], vv[3]};
+}
+
+template <bool BF16>
+__device__ __forceinline__ float load_grad(const void* base, int64_t k)
+{
+    if (BF16) return u2f(static_cast<uint32_t>(static_cast<const uint16_t*>(base)[k]) << 16);
+    return static_cast<const float*>(base)[k];
+}
+
+struct RsArgs {
+    int32_t W;            // ranks in this launch's table
+    int32_t cont;         // 1: accumulator continues from out[] (a later launch of a split W)
+    int32_t last;         // 1: apply the post divide (and Adam) in this launch
+    float pre_c;          // pre (kPreDiv) or 1/pre (kPreMul)
+    float post;
+    int64_t S;
+    float* out;           // grad shard (may be null only when fused and !cont and last)
+    float* p;             // Adam state (fused only)
+    float* m;
+    float* v;
+    uint16_t* p_lp;       // optional bf16 copy of the updated p (fused only)
+    AdamConsts adam;
+};
+
+// E = elements per lane-chunk: 4 for fp32 gradients, 8 for bf16 (16-byte loads
+// from every rank either way).  U chunks per lane.
+template <bool BF16, int PRE, bool FUSED, int U>
+__global__ __launch_bounds__(kBlock) void reduce_kernel(PtrTable grads, RsArgs a)
+{
+    constexpr int E = BF16 ? 8 : 4;
+    // The chunk grid is aligned on the primary fp32 output.
+    float* __restrict__ master = FUSED ? a.p : a.out;
+    const int64_t S = a.S;
+    const int64_t head = head_elems(master, 4, S);
+    const int64_t nvec = (S - head) / E;
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * (kBlock * U) + threadIdx.x;
+
+    float acc[U][E];
+    bool live[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t c = base + u * kBlock;
+        live[u] = c < nvec;
+    }
+
+    // first term (or the carried partial sum)
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (!live[u]) continue;
+        const int64_t k = head + (base + u * kBlock) * E;
+        if (a.cont) {
+            const f32x4 t0 = *reinterpret_cast<const f32x4_a4*>(a.out + k);
+            acc[u][0] = t0.x; acc[u][1] = t0.y; acc[u][2] = t0.z; acc[u][3] = t0.w;
+            if constexpr (E == 8) {
+                const f32x4 t1 = *reinterpret_cast<const f32x4_a4*>(a.out + k + 4);
+                acc[u][4] = t1.x; acc[u][5] = t1.y; acc[u][6] = t1.z; acc[u][7] = t1.w;
+            }
+        }
+    }
+
+    const int32_t W = a.W;
+    for (int32_t w0 = 0; w0 < W; w0 += 8) {
+        u32x4 x[8][U];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (w0 + j < W) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (!live[u]) continue;
+                    const int64_t k = head + (base + u * kBlock) * E;
+                    if constexpr (BF16)
+                        x[j][u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a2*>(
+                            static_cast<const uint16_t*>(grads.p[w0 + j]) + k));
+                    else
+                        x[j][u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a4*>(
+                            static_cast<const float*>(grads.p[w0 + j]) + k));
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (w0 + j < W) {
+                const bool init = (w0 + j == 0) && !a.cont;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (!live[u]) continue;
+                    float t[E];
+                    if constexpr (BF16) {   // exact upcast: the bf16 pattern is the top half of the fp32 one
+                        t[0] = u2f(x[j][u].x << 16); t[1] = u2f(x[j][u].x & 0xFFFF0000u);
+                        t[2] = u2f(x[j][u].y << 16); t[3] = u2f(x[j][u].y & 0xFFFF0000u);
+                        t[4] = u2f(x[j][u].z << 16); t[5] = u2f(x[j][u].z & 0xFFFF0000u);
+                        t[6] = u2f(x[j][u].w << 16); t[7] = u2f(x[j][u].w & 0xFFFF0000u);
+                    } else {
+                        t[0] = u2f(x[j][u].x); t[1] = u2f(x[j][u].y);
+                        t[2] = u2f(x[j][u].z); t[3] = u2f(x[j][u].w);
+                    }
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        const float term = pre_scale<PRE>(t[e], a.pre_c);
+                        acc[u][e] = init ? term : acc[u][e] + term;
+                    }
+                }
+            }
+        }
+    }
+
+    // epilogue
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (!live[u]) continue;
+        const int64_t k = head + (base + u * kBlock) * E;
+        if (a.last) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[u][e] = acc[u][e] / a.post;
+        }
+        if (a.out != nullptr) {
+#pragma unroll
+            for (int q = 0; q < E / 4; ++q) {
+                f32x4 o = {acc[u][4 * q], acc[u][4 * q + 1], acc[u][4 * q + 2], acc[u][4 * q + 3]};
+                *reinterpret_cast<f32x4_a4*>(a.out + k + 4 * q) = o;
+            }
+        }
+        if (FUSED) {
+            uint32_t lp[E / 2];
+#pragma unroll
+            for (int q = 0; q < E / 4; ++q) {
+                f32x4 pv = *reinterpret_cast<const f32x4*>(a.p + k + 4 * q);
+                f32x4 mv = *reinterpret_cast<const f32x4_a4*>(a.m + k + 4 * q);
+                f32x4 vv = *reinterpret_cast<const f32x4_a4*>(a.v + k + 4 * q);
+                adam_update4(pv, &acc[u][4 * q], mv, vv, a.adam);
+                *reinterpret_cast<f32x4*>(a.p + k + 4 * q) = pv;
+                *reinterpret_cast<f32x4_a4*>(a.m + k + 4 * q) = mv;
+                *reinterpret_cast<f32x4_a4*>(a.v + k + 4 * q) = vv;
+                lp[2 * q] = pack_bf16x2(pv.x, pv.y);
+                lp[2 * q + 1] = pack_bf16x2(pv.z, pv.w);
+            }
+            if (a.p_lp != nullptr) {
+                if constexpr (E == 8) {
+                    u32x4 o = {lp[0], lp[1], lp[2], lp[3]};
+                    *reinterpret_cast<u32x4_a2*>(a.p_lp + k) = o;
+                } else {
+                    u32x2 o = {lp[0], lp[1]};
+                    *reinterpret_cast<u32x2_a2*>(a.p_lp + k) = o;
+                }
+            }
+        }
+    }
+
+    // ragged head / tail (fewer than 4 + E elements in total): one lane per element
+    if (blockIdx.x == 0) {
+        const int64_t tail0 = head + nvec * E;
+        const int64_t nrag = head + (S - tail0);
+        const int t = threadIdx.x;
+        if (t < nrag) {
+            const int64_t k = t < head ? t : tail0 + (t - head);
+            float r = a.cont ? a.out[k] : 0.0f;
+            for (int32_t w = 0; w < W; ++w) {
+                const float term = pre_scale<PRE>(load_grad<BF16>(grads.p[w], k), a.pre_c);
+                r = (w == 0 && !a.cont) ? term : r + term;
+            }
+            if (a.last) r = r / a.post;
+            if (a.out != nullptr) a.out[k] = r;
+            if (FUSED) {
+                float pv = a.p[k], mv = a.m[k], vv = a.v[k];
+                adam_update(pv, r, mv, vv, a.adam);
+                a.p[k] = pv; a.m[k] = mv; a.v[k] = vv;
+                if (a.p_lp != nullptr) a.p_lp[k] = static_cast<uint16_t>(bf16_rne(f2u(pv)));
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Adam on the shard (Sec. 5.4; state sharded as in Sec. 3)
+// ---------------------------------------------------------------------------
+template <int U>
+__global__ __launch_bounds__(kBlock) void adam_kernel(float* __restrict__ p, const float* __restrict__ g,
+                                                       float* __restrict__ m, float* __restrict__ v,
+                                                       int64_t S, AdamConsts c)
+{
+    const int64_t head = head_elems(p, 4, S);
+    const int64_t nvec = (S - head) >> 2;
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * (kBlock * U) + threadIdx.x;
+
+    f32x4 pv[U], gv[U], mv[U], vv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t cidx = base + u * kBlock;
+        if (cidx < nvec) {
+            const int64_t k = head + (cidx << 2);
+            pv[u] = *reinterpret_cast<const f32x4*>(p + k);
+            gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(g + k));
+            mv[u] = *reinterpret_cast<const f32x4_a4*>(m + k);
+            vv[u] = *reinterpret_cast<const f32x4_a4*>(v + k);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t cidx = base + u * kBlock;
+        if (cidx < nvec) {
+            const int64_t k = head + (cidx << 2);
+            const float gg[4] = {gv[u].x, gv[u].y, gv[u].z, gv[u].w};
+            adam_update4(pv[u], gg, mv[u], vv[u], c);
+            *reinterpret_cast<f32x4*>(p + k) = pv[u];
+            *reinterpret_cast<f32x4_a4*>(m + k) = mv[u];
+            *reinterpret_cast<f32x4_a4*>(v + k) = vv[u];
+        }
+    }
+    if (blockIdx.x == 0) {
+        const int64_t tail0 = head + (nvec << 2);
+        const int64_t nrag = head + (S - tail0);
+        const int t = threadIdx.x;
+        if (t < nrag) {
+            const int64_t k = t < head ? t : tail0 + (t - head);
+            float pk = p[k], mk = m[k], vk = v[k];
+            adam_update(pk, g[k], mk, vk, c);
+            p[k] = pk; m[k] = mk; v[k] = vk;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+int launch_status()
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        fsdp::set_last_hip_error(static_cast<int>(e));
+        return FSDP_ERR_HIP;
+    }
+    return FSDP_OK;
+}
+
+inline bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Blocks of a 1-D grid must fit HIP's 2^31 - 1 limit; with >= 4 KiB per block
+// that is > 8 TB of data, far beyond the 288 GB of HBM, but check anyway.
+inline bool grid_ok(int64_t blocks) { return blocks > 0 && blocks <= 0x7FFFFFFFLL; }
+
+bool is_pow2_float(float x, float* recip)
+{
+    int e = 0;
+    const float m = std::frexp(x, &e);       // x = m * 2^e, m in [0.5, 1)
+    if (m != 0.5f) return false;
+    const float r = 1.0f / x;                 // exact for a power of two unless it leaves the normal range
+    if (!std::isfinite(r) || r == 0.0f || std::fpclassify(r) == FP_SUBNORMAL || std::fpclassify(x) == FP_SUBNORMAL)
+        return false;
+    *recip = r;
+    return true;
+}
+
+int check_adam_args(int64_t step, float lr, float b1, float b2, float eps)
+{
+    if (step < 1) return FSDP_ERR_INVALID_ARG;
+    if (!std::isfinite(lr)) return FSDP_ERR_INVALID_ARG;
+    if (!(b1 >= 0.0f && b1 < 1.0f) || !(b2 >= 0.0f && b2 < 1.0f)) return FSDP_ERR_INVALID_ARG;
+    if (!(eps >= 0.0f) || !std::isfinite(eps)) return FSDP_ERR_INVALID_ARG;
+    return FSDP_OK;
+}
+
+AdamConsts make_adam_consts(int64_t step, float lr, float b1, float b2, float eps)
+{
+    AdamConsts c;
+    const float bc1 = static_cast<float>(1.0 - std::pow(static_cast<double>(b1), static_cast<double>(step)));
+    const float bc2 = static_cast<float>(1.0 - std::pow(static_cast<double>(b2), static_cast<double>(step)));
+    c.beta1 = b1;
+    c.beta2 = b2;
+    c.one_m_b1 = 1.0f - b1;
+    c.one_m_b2 = 1.0f - b2;
+    c.step_size = lr / bc1;
+    c.sqrt_bc2 = std::sqrt(bc2);
+    c.eps = eps;
+    return c;
+}
+
+template <bool BF16, int PRE, bool FUSED>
+void launch_reduce(const PtrTable& tab, const RsArgs& a, hipStream_t st)
+{
+    constexpr int E = BF16 ? 8 : 4;
+    constexpr int U = BF16 ? 1 : 2;
+    const int64_t blocks = ceil_div(a.S / E + 1, kBlock * U);
+    hipLaunchKernelGGL((reduce_kernel<BF16, PRE, FUSED, U>), dim3(static_cast<uint32_t>(blocks)), dim3(kBlock), 0,
+                       st, tab, a);
+}
+
+template <bool BF16, bool FUSED>
+void launch_reduce_pre(int pre_mode, const PtrTable& tab, const RsArgs& a, hipStream_t st)
+{
+    if (pre_mode == kPreNone) launch_reduce<BF16, kPreNone, FUSED>(tab, a, st);
+    else if (pre_mode == kPreMul) launch_reduce<BF16, kPreMul, FUSED>(tab, a, st);
+    else launch_reduce<BF16, kPreDiv, FUSED>(tab, a, st);
+}
+
+// shared driver of fsdp_reduce_scatter_local and fsdp_reduce_scatter_adam_fused
+int reduce_driver(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dtype_t grad_dtype, int32_t rank,
+                  float pre, float post, float* out, bool fused, float* p, float* m, float* v, uint16_t* p_lp,
+                  const AdamConsts& adam, hipStream_t st)
+{
+    const int32_t W = L->world_size;
+    const int64_t S = L->S;
+    const bool bf16 = grad_dtype == FSDP_BF16;
+    const int64_t esz = bf16 ? 2 : 4;
+    if (!grid_ok(ceil_div(S / 4 + 1, kBlock))) return FSDP_ERR_OVERFLOW;
+
+    float pre_c = pre;
+    int pre_mode = kPreDiv;
+    float recip;
+    if (pre == 1.0f) pre_mode = kPreNone;
+    else if (is_pow2_float(pre, &recip)) { pre_mode = kPreMul; pre_c = recip; }
+
+    for (int32_t w0 = 0; w0 < W; w0 += kMaxRanks) {
+        const int32_t nw = W - w0 < kMaxRanks ? W - w0 : kMaxRanks;
+        PtrTable tab = {};
+        for (int32_t j = 0; j < nw; ++j)
+            tab.p[j] = static_cast<const char*>(grad_ptrs[w0 + j]) + static_cast<int64_t>(rank) * S * esz;
+        RsArgs a = {};
+        a.W = nw;
+        a.cont = w0 > 0;
+        a.last = w0 + nw == W;
+        a.pre_c = pre_c;
+        a.post = post;
+        a.S = S;
+        a.out = out;
+        a.p = p; a.m = m; a.v = v; a.p_lp = p_lp;
+        a.adam = adam;
+        const bool fuse_now = fused && a.last;
+        if (bf16) {
+            if (fuse_now) launch_reduce_pre<true, true>(pre_mode, tab, a, st);
+            else launch_reduce_pre<true, false>(pre_mode, tab, a, st);
+        } else {
+            if (fuse_now) launch_reduce_pre<false, true>(pre_mode, tab, a, st);
+            else launch_reduce_pre<false, false>(pre_mode, tab, a, st);
+        }
+        const int rc = launch_status();
+        if (rc != FSDP_OK) return rc;
+    }
+    return FSDP_OK;
+}
+
+int check_reduce_args(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dtype_t grad_dtype, int32_t rank,
+                      float pre, float post)
+{
+    if (!L || !grad_ptrs) return FSDP_ERR_NULL_PTR;
+    if (grad_dtype != FSDP_F32 && grad_dtype != FSDP_BF16) return FSDP_ERR_BAD_DTYPE;
+    if (rank < 0 || rank >= L->world_size) return FSDP_ERR_RANK_RANGE;
+    if (!std::isfinite(pre) || !std::isfinite(post) || !(pre > 0.0f) || !(post > 0.0f)) return FSDP_ERR_INVALID_ARG;
+    const uintptr_t al = grad_dtype == FSDP_BF16 ? 2 : 4;
+    for (int32_t w = 0; w < L->world_size; ++w) {
+        if (!grad_ptrs[w]) return FSDP_ERR_NULL_PTR;
+        if (misaligned(grad_ptrs[w], al)) return FSDP_ERR_INVALID_ARG;
+    }
+    return FSDP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fsdp_flatten_shard(const fsdp_layout_t* L, const void* const* param_ptrs, float* const* shard_ptrs,
+                       void* hip_stream)
+{
+    if (!L || !param_ptrs || !shard_ptrs) return FSDP_ERR_NULL_PTR;
+    const int32_t W = L->world_size;
+    const int64_t S = L->S;
+    for (int32_t i = 0; i < L->num_params; ++i) {
+        if (L->numel[i] == 0) continue;
+        if (!param_ptrs[i]) return FSDP_ERR_NULL_PTR;
+        if (misaligned(param_ptrs[i], 4)) return FSDP_ERR_INVALID_ARG;
+    }
+    for (int32_t w = 0; w < W; ++w) {
+        if (!shard_ptrs[w]) return FSDP_ERR_NULL_PTR;
+        if (misaligned(shard_ptrs[w], 4)) return FSDP_ERR_INVALID_ARG;
+    }
+    const int64_t tiles = ceil_div(S + 3, kPackTile);
+    if (!grid_ok(tiles * kMaxRanks)) return FSDP_ERR_OVERFLOW;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+    // Non-empty segments in flat order: the parameters, then the pad.
+    std::vector<const float*> seg_src;
+    std::vector<int64_t> seg_off;
+    try {
+        for (int32_t i = 0; i < L->num_params; ++i) {
+            if (L->numel[i] == 0) continue;
+            seg_src.push_back(static_cast<const float*>(param_ptrs[i]));
+            seg_off.push_back(L->off[i]);
+        }
+        if (L->pad > 0) {
+            seg_src.push_back(nullptr);
+            seg_off.push_back(L->N);
+        }
+        seg_off.push_back(L->P);
+    } catch (const std::bad_alloc&) {
+        return FSDP_ERR_OOM;
+    }
+    const int64_t nsegs = static_cast<int64_t>(seg_src.size());
+
+    // One launch covers the flat range where a batch of <= kMaxSegs segments
+    // meets a batch of <= kMaxRanks shards.
+    for (int64_t s0 = 0; s0 < nsegs; s0 += kMaxSegs) {
+        const int32_t ns = static_cast<int32_t>(nsegs - s0 < kMaxSegs ? nsegs - s0 : kMaxSegs);
+        SegTable segs = {};
+        for (int32_t j = 0; j < ns; ++j) {
+            segs.src[j] = seg_src[s0 + j];
+            segs.off[j] = seg_off[s0 + j];
+        }
+        segs.off[ns] = seg_off[s0 + ns];
+        const int64_t B0 = segs.off[0], B1 = segs.off[ns];
+        const int32_t wa = static_cast<int32_t>(B0 / S), wb = static_cast<int32_t>((B1 - 1) / S);
+        for (int32_t w0 = wa; w0 <= wb; w0 += kMaxRanks) {
+            const int32_t nw = wb - w0 + 1 < kMaxRanks ? wb - w0 + 1 : kMaxRanks;
+            MutPtrTable dsts = {};
+            for (int32_t j = 0; j < nw; ++j) dsts.p[j] = shard_ptrs[w0 + j];
+            const int64_t lo = static_cast<int64_t>(w0) * S, hi = static_cast<int64_t>(w0 + nw) * S;
+            const int64_t R0 = B0 > lo ? B0 : lo, R1 = B1 < hi ? B1 : hi;
+            hipLaunchKernelGGL(pack_kernel, dim3(static_cast<uint32_t>(tiles * nw)), dim3(kBlock), 0, st, segs, ns,
+                               dsts, w0, S, R0, R1, static_cast<int32_t>(tiles));
+            const int rc = launch_status();
+            if (rc != FSDP_OK) return rc;
+        }
+    }
+    return FSDP_OK;
+}
+
+int fsdp_unshard(const fsdp_layout_t* L, const float* const* shard_ptrs, void* flat_out, fsdp_dtype_t out_dtype,
+                 void* hip_stream)
+{
+    if (!L || !shard_ptrs || !flat_out) return FSDP_ERR_NULL_PTR;
+    if (out_dtype != FSDP_F32 && out_dtype != FSDP_BF16) return FSDP_ERR_BAD_DTYPE;
+    const int32_t W = L->world_size;
+    const int64_t S = L->S;
+    for (int32_t w = 0; w < W; ++w) {
+        if (!shard_ptrs[w]) return FSDP_ERR_NULL_PTR;
+        if (misaligned(shard_ptrs[w], 4)) return FSDP_ERR_INVALID_ARG;
+    }
+    const bool bf16 = out_dtype == FSDP_BF16;
+    if (misaligned(flat_out, bf16 ? 2 : 4)) return FSDP_ERR_INVALID_ARG;
+    constexpr int U = 4;
+    const int64_t vec = bf16 ? 8 : 4;
+    const int64_t tiles = ceil_div(S / vec + 1, kBlock * U);
+    if (!grid_ok(tiles * kMaxRanks)) return FSDP_ERR_OVERFLOW;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+    for (int32_t w0 = 0; w0 < W; w0 += kMaxRanks) {
+        const int32_t nw = W - w0 < kMaxRanks ? W - w0 : kMaxRanks;
+        PtrTable tab = {};
+        for (int32_t j = 0; j < nw; ++j) tab.p[j] = shard_ptrs[w0 + j];
+        const dim3 grid(static_cast<uint32_t>(tiles * nw));
+        if (bf16) {
+            uint16_t* base = static_cast<uint16_t*>(flat_out) + static_cast<int64_t>(w0) * S;
+            hipLaunchKernelGGL((unshard_bf16_kernel<U>), grid, dim3(kBlock), 0, st, tab, S, base,
+                               static_cast<int32_t>(tiles));
+        } else {
+            float* base = static_cast<float*>(flat_out) + static_cast<int64_t>(w0) * S;
+            hipLaunchKernelGGL((unshard_f32_kernel<U>), grid, dim3(kBlock), 0, st, tab, S, base,
+                               static_cast<int32_t>(tiles));
+        }
+        const int rc = launch_status();
+        if (rc != FSDP_OK) return rc;
+    }
+    return FSDP_OK;
+}
+
+int fsdp_reduce_scatter_local(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dtype_t grad_dtype,
+                              int32_t rank, float pre_div, float post_div, float* grad_shard_out, void* hip_stream)
+{
+    int rc = check_reduce_args(L, grad_ptrs, grad_dtype, rank, pre_div, post_div);
+    if (rc != FSDP_OK) return rc;
+    if (!grad_shard_out) return FSDP_ERR_NULL_PTR;
+    if (misaligned(grad_shard_out, 4)) return FSDP_ERR_INVALID_ARG;
+    const AdamConsts none = {};
+    return reduce_driver(L, grad_ptrs, grad_dtype, rank, pre_div, post_div, grad_shard_out, false, nullptr, nullptr,
+                         nullptr, nullptr, none, static_cast<hipStream_t>(hip_stream));
+}
+
+int fsdp_shard_adam_step(const fsdp_layout_t* L, float* p_shard, const float* g_shard, float* exp_avg,
+                         float* exp_avg_sq, int64_t step, float lr, float beta1, float beta2, float eps,
+                         void* hip_stream)
+{
+    if (!L || !p_shard || !g_shard || !exp_avg || !exp_avg_sq) return FSDP_ERR_NULL_PTR;
+    int rc = check_adam_args(step, lr, beta1, beta2, eps);
+    if (rc != FSDP_OK) return rc;
+    if (misaligned(p_shard, 4) || misaligned(g_shard, 4) || misaligned(exp_avg, 4) || misaligned(exp_avg_sq, 4))
+        return FSDP_ERR_INVALID_ARG;
+    constexpr int U = 2;
+    const int64_t blocks = ceil_div(L->S / 4 + 1, kBlock * U);
+    if (!grid_ok(blocks)) return FSDP_ERR_OVERFLOW;
+    const AdamConsts c = make_adam_consts(step, lr, beta1, beta2, eps);
+    hipLaunchKernelGGL((adam_kernel<U>), dim3(static_cast<uint32_t>(blocks)), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(hip_stream), p_shard, g_shard, exp_avg, exp_avg_sq, L->S, c);
+    return launch_status();
+}
+
+int fsdp_reduce_scatter_adam_fused(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dtype_t grad_dtype,
+                                   int32_t rank, float pre_div, float post_div, float* grad_shard_out,
+                                   float* p_shard, float* exp_avg, float* exp_avg_sq, int64_t step, float lr,
+                                   float beta1, float beta2, float eps, void* p_lp_out, void* hip_stream)
+{
+    int rc = check_reduce_args(L, grad_ptrs, grad_dtype, rank, pre_div, post_div);
+    if (rc != FSDP_OK) return rc;
+    if (!p_shard || !exp_avg || !exp_avg_sq) return FSDP_ERR_NULL_PTR;
+    rc = check_adam_args(step, lr, beta1, beta2, eps);
+    if (rc != FSDP_OK) return rc;
+    if (L->world_size > kMaxRanks && !grad_shard_out) return FSDP_ERR_NULL_PTR;
+    if (misaligned(p_shard, 4) || misaligned(exp_avg, 4) || misaligned(exp_avg_sq, 4) ||
+        (grad_shard_out && misaligned(grad_shard_out, 4)) || (p_lp_out && misaligned(p_lp_out, 2)))
+        return FSDP_ERR_INVALID_ARG;
+    const AdamConsts c = make_adam_consts(step, lr, beta1, beta2, eps);
+    return reduce_driver(L, grad_ptrs, grad_dtype, rank, pre_div, post_div, grad_shard_out, true, p_shard, exp_avg,
+                         exp_avg_sq, static_cast<uint16_t*>(p_lp_out), c, static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,219 @@
+"""Host-side tests of the C ABI: the library loads, exports every symbol the
+header declares, plans layouts like the oracle does, and turns every invalid
+argument into an error code before anything is launched.  No GPU needed."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+import workloads
+from paper_2304_11277_amd import build as fbuild
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    fbuild.build_lib(force=False)
+    import paper_2304_11277_amd as f
+    return f
+
+
+def test_header_symbols_are_exported(L):
+    hdr = open(os.path.join(ROOT, "include", "fsdp_flat.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(fsdp_[a-z_0-9]+)\s*\(", hdr))
+    assert {"fsdp_layout_init", "fsdp_flatten_shard", "fsdp_unshard", "fsdp_reduce_scatter_local",
+            "fsdp_shard_adam_step"} <= names
+    raw = ctypes.CDLL(L.library_path())
+    for n in sorted(names):
+        assert hasattr(raw, n), n
+
+
+def test_binding_names_match_c_names(L):
+    for n in ("fsdp_layout_init", "fsdp_flatten_shard", "fsdp_unshard", "fsdp_reduce_scatter_local",
+              "fsdp_shard_adam_step", "fsdp_reduce_scatter_adam_fused", "fsdp_view_ptr",
+              "fsdp_default_divide_factors"):
+        assert callable(getattr(L, n))
+
+
+def test_layout_matches_oracle_on_configs_and_ragged(L):
+    cases = [(workloads.config(i).units[j].shapes, workloads.config(i).world_size)
+             for i in range(workloads.NUM_CONFIGS) for j in workloads.config(i).distinct_units]
+    cases += [(workloads.ragged_unit().shapes, W) for W in (1, 2, 3, 7, 8, 12, 64, 100)]
+    cases += [(((3, 4), (3,)), 16)]
+    for shapes, W in cases:
+        lay = L.fsdp_layout_init(shapes, W)
+        off, N, S, P, pad = oracle.layout(shapes, W)
+        assert (lay.numel, lay.shard, lay.padded, lay.pad) == (N, S, P, pad)
+        assert lay.offsets == off[:-1]
+        assert lay.numels == [off[i + 1] - off[i] for i in range(len(shapes))]
+        assert (lay.num_params, lay.world_size) == (len(shapes), W)
+        lay.close()
+
+
+def test_fig3_worked_example_through_the_abi(L):
+    lay = L.fsdp_layout_init([(3, 4), (3,)], 16)
+    assert (lay.numel, lay.shard, lay.padded, lay.pad) == (15, 1, 16, 1)
+
+
+def test_default_divide_factors(L):
+    expect = {1: (1, 1), 2: (2, 1), 3: (1, 3), 6: (2, 3), 8: (4, 2), 12: (4, 3), 16: (4, 4), 64: (8, 8),
+              128: (16, 8), 7: (1, 7)}
+    for W, (pre, post) in expect.items():
+        assert L.fsdp_default_divide_factors(W) == (float(pre), float(post))
+        assert pre * post == W
+
+
+# ---- error codes, straight through ctypes -------------------------------
+
+OK, INVALID, NULL, OVERFLOW, OOM, BAD_DTYPE, RANK_RANGE, HIP = 0, -1, -2, -3, -4, -5, -6, -7
+
+
+def _init(raw, shapes, W):
+    flat = [d for s in shapes for d in s]
+    dims = (ctypes.c_int64 * max(1, len(flat)))(*flat)
+    nd = (ctypes.c_int32 * max(1, len(shapes)))(*[len(s) for s in shapes])
+    out = ctypes.c_void_p()
+    rc = raw.fsdp_layout_init(dims, nd, len(shapes), W, ctypes.byref(out))
+    return rc, out
+
+
+def test_layout_init_errors(L):
+    raw = L.lib()
+    assert _init(raw, [(2, 3)], 0)[0] == INVALID
+    assert _init(raw, [(2, 3)], -4)[0] == INVALID
+    assert _init(raw, [], 4)[0] == INVALID
+    assert _init(raw, [(2, -3)], 4)[0] == INVALID
+    assert _init(raw, [(0, 5), (0,)], 4)[0] == INVALID            # N == 0
+    assert _init(raw, [(2 ** 40, 2 ** 40)], 4)[0] == OVERFLOW     # numel past int64
+    assert _init(raw, [(2 ** 62,), (2 ** 62,)], 4)[0] == OVERFLOW  # sum past int64
+    assert _init(raw, [(2 ** 61,)], 4)[0] == OVERFLOW             # 4 * P past int64
+    assert _init(raw, [(0, 2 ** 62, 2 ** 62), (3,)], 4)[0] == OK  # a zero dim is numel 0, not an overflow
+    nd = (ctypes.c_int32 * 1)(1)
+    out = ctypes.c_void_p()
+    assert raw.fsdp_layout_init(None, nd, 1, 2, ctypes.byref(out)) == NULL
+    dims = (ctypes.c_int64 * 1)(5)
+    assert raw.fsdp_layout_init(dims, None, 1, 2, ctypes.byref(out)) == NULL
+    assert raw.fsdp_layout_init(dims, nd, 1, 2, None) == NULL
+    nd[0] = -1
+    assert raw.fsdp_layout_init(dims, nd, 1, 2, ctypes.byref(out)) == INVALID
+    raw.fsdp_layout_destroy(None)                                   # no-op
+
+
+def test_query_errors(L):
+    raw = L.lib()
+    rc, h = _init(raw, [(4, 3), (3,)], 4)
+    assert rc == OK
+    n = ctypes.c_int64()
+    assert raw.fsdp_layout_info(None, None, None, None, None, None, None) == NULL
+    assert raw.fsdp_layout_info(h, ctypes.byref(n), None, None, None, None, None) == OK and n.value == 15
+    assert raw.fsdp_layout_param(h, 2, None, None) == RANK_RANGE
+    assert raw.fsdp_layout_param(h, -1, None, None) == RANK_RANGE
+    assert raw.fsdp_layout_param(None, 0, None, None) == NULL
+    out = ctypes.c_void_p()
+    base = ctypes.c_void_p(0x1000)
+    assert raw.fsdp_view_ptr(h, base, 1, 1, ctypes.byref(out)) == OK and out.value == 0x1000 + 12 * 2
+    assert raw.fsdp_view_ptr(h, base, 0, 1, ctypes.byref(out)) == OK and out.value == 0x1000 + 12 * 4
+    assert raw.fsdp_view_ptr(h, base, 2, 1, ctypes.byref(out)) == BAD_DTYPE
+    assert raw.fsdp_view_ptr(h, base, 0, 5, ctypes.byref(out)) == RANK_RANGE
+    assert raw.fsdp_view_ptr(h, None, 0, 0, ctypes.byref(out)) == NULL
+    assert raw.fsdp_view_ptr(h, base, 0, 0, None) == NULL
+    pre, post = ctypes.c_float(), ctypes.c_float()
+    assert raw.fsdp_default_divide_factors(0, ctypes.byref(pre), ctypes.byref(post)) == INVALID
+    assert raw.fsdp_default_divide_factors(8, None, ctypes.byref(post)) == NULL
+    raw.fsdp_layout_destroy(h)
+
+
+def _table(vals):
+    return (ctypes.c_void_p * len(vals))(*vals)
+
+
+def test_compute_entry_points_reject_bad_arguments_before_launch(L):
+    """Fake (never dereferenced) device addresses: every call must fail in host
+    validation, so nothing reaches a device."""
+    raw = L.lib()
+    rc, h = _init(raw, [(4, 3), (3,)], 4)
+    assert rc == OK
+    good4 = _table([0x10000 + 64 * i for i in range(4)])
+    good2 = _table([0x20000, 0x20100])
+    with_null = _table([0x10000, None, 0x10080, 0x100C0])
+    odd = _table([0x10000, 0x10042, 0x10080, 0x100C0])   # 2-byte aligned only
+    buf = ctypes.c_void_p(0x30000)
+    st = None
+    # flatten
+    assert raw.fsdp_flatten_shard(None, good2, good4, st) == NULL
+    assert raw.fsdp_flatten_shard(h, None, good4, st) == NULL
+    assert raw.fsdp_flatten_shard(h, good2, None, st) == NULL
+    assert raw.fsdp_flatten_shard(h, _table([0x20000, None]), good4, st) == NULL
+    assert raw.fsdp_flatten_shard(h, good2, with_null, st) == NULL
+    assert raw.fsdp_flatten_shard(h, _table([0x20002, 0x20100]), good4, st) == INVALID
+    assert raw.fsdp_flatten_shard(h, good2, odd, st) == INVALID
+    # unshard
+    assert raw.fsdp_unshard(None, good4, buf, 1, st) == NULL
+    assert raw.fsdp_unshard(h, None, buf, 1, st) == NULL
+    assert raw.fsdp_unshard(h, good4, None, 1, st) == NULL
+    assert raw.fsdp_unshard(h, with_null, buf, 1, st) == NULL
+    assert raw.fsdp_unshard(h, good4, buf, 2, st) == BAD_DTYPE
+    assert raw.fsdp_unshard(h, good4, buf, -1, st) == BAD_DTYPE
+    assert raw.fsdp_unshard(h, odd, buf, 1, st) == INVALID
+    assert raw.fsdp_unshard(h, good4, ctypes.c_void_p(0x30001), 1, st) == INVALID
+    assert raw.fsdp_unshard(h, good4, ctypes.c_void_p(0x30002), 0, st) == INVALID
+    # reduce-scatter
+    f = ctypes.c_float
+    assert raw.fsdp_reduce_scatter_local(None, good4, 0, 0, f(2), f(2), buf, st) == NULL
+    assert raw.fsdp_reduce_scatter_local(h, None, 0, 0, f(2), f(2), buf, st) == NULL
+    assert raw.fsdp_reduce_scatter_local(h, good4, 0, 0, f(2), f(2), None, st) == NULL
+    assert raw.fsdp_reduce_scatter_local(h, with_null, 0, 0, f(2), f(2), buf, st) == NULL
+    assert raw.fsdp_reduce_scatter_local(h, good4, 7, 0, f(2), f(2), buf, st) == BAD_DTYPE
+    assert raw.fsdp_reduce_scatter_local(h, good4, 0, 4, f(2), f(2), buf, st) == RANK_RANGE
+    assert raw.fsdp_reduce_scatter_local(h, good4, 0, -1, f(2), f(2), buf, st) == RANK_RANGE
+    for bad in (0.0, -1.0, float("inf"), float("nan")):
+        assert raw.fsdp_reduce_scatter_local(h, good4, 0, 0, f(bad), f(2), buf, st) == INVALID
+        assert raw.fsdp_reduce_scatter_local(h, good4, 0, 0, f(2), f(bad), buf, st) == INVALID
+    assert raw.fsdp_reduce_scatter_local(h, odd, 0, 0, f(2), f(2), buf, st) == INVALID     # fp32 needs 4 B
+    assert raw.fsdp_reduce_scatter_local(h, _table([0x10001, 0x10040, 0x10080, 0x100C0]), 1, 0, f(2), f(2), buf,
+                                         st) == INVALID
+    # adam
+    p, g, m, v = (ctypes.c_void_p(0x40000 + 0x100 * i) for i in range(4))
+    i64 = ctypes.c_int64
+    ok_h = (f(1e-4), f(0.9), f(0.999), f(1e-8))
+    assert raw.fsdp_shard_adam_step(None, p, g, m, v, i64(1), *ok_h, st) == NULL
+    for k in range(4):
+        a = [p, g, m, v]
+        a[k] = None
+        assert raw.fsdp_shard_adam_step(h, *a, i64(1), *ok_h, st) == NULL
+    assert raw.fsdp_shard_adam_step(h, p, g, m, v, i64(0), *ok_h, st) == INVALID
+    assert raw.fsdp_shard_adam_step(h, p, g, m, v, i64(1), f(float("nan")), f(0.9), f(0.999), f(1e-8), st) == INVALID
+    assert raw.fsdp_shard_adam_step(h, p, g, m, v, i64(1), f(1e-4), f(1.0), f(0.999), f(1e-8), st) == INVALID
+    assert raw.fsdp_shard_adam_step(h, p, g, m, v, i64(1), f(1e-4), f(0.9), f(-0.1), f(1e-8), st) == INVALID
+    assert raw.fsdp_shard_adam_step(h, p, g, m, v, i64(1), f(1e-4), f(0.9), f(0.999), f(-1e-8), st) == INVALID
+    assert raw.fsdp_shard_adam_step(h, ctypes.c_void_p(0x40002), g, m, v, i64(1), *ok_h, st) == INVALID
+    # fused
+    assert raw.fsdp_reduce_scatter_adam_fused(h, good4, 0, 9, f(2), f(2), None, p, m, v, i64(1), *ok_h, None,
+                                              st) == RANK_RANGE
+    assert raw.fsdp_reduce_scatter_adam_fused(h, good4, 0, 0, f(2), f(2), None, None, m, v, i64(1), *ok_h, None,
+                                              st) == NULL
+    assert raw.fsdp_reduce_scatter_adam_fused(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(0), *ok_h, None,
+                                              st) == INVALID
+    assert raw.fsdp_reduce_scatter_adam_fused(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(1), *ok_h,
+                                              ctypes.c_void_p(0x50001), st) == INVALID
+    raw.fsdp_layout_destroy(h)
+    # W > 64 needs the gradient shard buffer to carry partial sums
+    rc, h2 = _init(raw, [(1000,)], 65)
+    assert rc == OK
+    many = _table([0x10000 + 64 * i for i in range(65)])
+    assert raw.fsdp_reduce_scatter_adam_fused(h2, many, 0, 0, f(1), f(65), None, p, m, v, i64(1), *ok_h, None,
+                                              st) == NULL
+    raw.fsdp_layout_destroy(h2)
+
+
+def test_binding_rejects_host_tensors(L):
+    import torch
+    lay = L.fsdp_layout_init([(4, 3), (3,)], 4)
+    cpu = [torch.zeros(4) for _ in range(4)]
+    with pytest.raises(TypeError):
+        L.fsdp_unshard(lay, cpu, torch.zeros(16, dtype=torch.bfloat16))
+    assert L.lib().fsdp_status_string(-6) == b"rank or parameter index out of range"

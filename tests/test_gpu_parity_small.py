@@ -1,0 +1,325 @@
+"""GPU parity, small and ragged cases: the HIP path (through the C ABI) against
+the CPU oracle, element by element, on sizes that span several tiles and a
+ragged tail.  Bit-exact for pack / gather / cast / reduce; Adam within 1e-6."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from gpu_helpers import (POISON16, POISON32, adam_close, carve, first_diff, load_product, np_bits, np_f32, np_grad,
+                         same_bits)
+
+pytestmark = pytest.mark.gpu
+
+LR, B1, B2, EPS = 1e-4, 0.9, 0.999, 1e-8
+
+EDGE_BITS = [0x00000000, 0x80000000, 0x3F800000, 0x3F808000, 0x3F818000, 0x3F808001, 0x3F807FFF, 0x7F7F8000,
+             0x7F7F7FFF, 0xFF7F8000, 0x00008000, 0x00018000, 0x00008001, 0x00000001, 0x807FFFFF, 0x7F800000,
+             0xFF800000, 0x7FC00000, 0xFFC00000, 0x7F800001, 0xFF80FFFF, 0x7FA00000, 0x7FFFFFFF]
+
+
+@pytest.fixture(scope="module")
+def F():
+    assert torch.cuda.is_available()
+    return load_product()
+
+
+def big_unit():
+    """Several tiles per shard, a ragged tail, more than one pack-launch worth of
+    parameters, and edge-value content."""
+    shapes = [(len(EDGE_BITS),), (257, 129), (1,), (), (0, 3), (100003,), (64, 64), (7,)]
+    shapes += [(i + 1,) for i in range(40)] + [(333, 77), (5, 5, 5), (20011,)]
+    return workloads.Unit("big_ragged", tuple(shapes))
+
+
+def make_params(unit, seed, misalign):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    out = []
+    for i, shp in enumerate(unit.shapes):
+        n = workloads.numel(shp)
+        t = carve(n, torch.float32, (i % 4) if misalign else 0)
+        if n:
+            t.normal_(0.0, 0.02, generator=g)
+        out.append(t.view(shp) if n else torch.empty(shp, dtype=torch.float32, device="cuda"))
+    if unit.shapes[0] == (len(EDGE_BITS),):
+        out[0].copy_(torch.tensor(np.array(EDGE_BITS, dtype=np.uint32).view(np.float32)))
+    return out
+
+
+def alloc_shards(W, S, mode):
+    """mode: 'separate' (each its own allocation), 'contig' (base + w*S),
+    'contig_odd' (base + 1 + w*S: only element-aligned)."""
+    if mode == "separate":
+        return [carve(S, torch.float32, 0, fill=POISON32) for _ in range(W)], None
+    off = 1 if mode == "contig_odd" else 0
+    base = carve(W * S, torch.float32, off, fill=POISON32)
+    return [base[w * S:(w + 1) * S] for w in range(W)], base
+
+
+@pytest.mark.parametrize("W", [1, 2, 3, 7, 8, 12, 64, 100])
+@pytest.mark.parametrize("mode", ["separate", "contig", "contig_odd"])
+def test_flatten_shard_and_unshard(F, W, mode):
+    unit = big_unit() if W <= 12 else workloads.ragged_unit()
+    params = make_params(unit, 1234 + W, misalign=(mode != "separate"))
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    shards, _ = alloc_shards(W, lay.shard, mode)
+    F.fsdp_flatten_shard(lay, params, shards)
+    torch.cuda.synchronize()
+    ref_shards, (off, N, S, P, pad) = oracle.flatten_shard([np_f32(p) for p in params], W)
+    assert (lay.numel, lay.shard, lay.padded, lay.pad) == (N, S, P, pad)
+    for w in range(W):
+        got = np_bits(shards[w])
+        assert same_bits(got, ref_shards[w].view(np.uint32)), f"shard {w}: {first_diff(got, ref_shards[w].view(np.uint32))}"
+
+    # unshard, bf16 (cast + gather) and fp32 (gather), destination aligned and not
+    for dst_off in (0, 1, 3):
+        flat_lp = carve(P, torch.bfloat16, dst_off, fill=POISON16)
+        F.fsdp_unshard(lay, shards, flat_lp)
+        flat_fp = carve(P, torch.float32, dst_off, fill=POISON32)
+        F.fsdp_unshard(lay, shards, flat_fp)
+        torch.cuda.synchronize()
+        ref_lp = oracle.unshard_bf16(ref_shards)
+        ref_fp = oracle.unshard_f32(ref_shards)
+        assert same_bits(np_bits(flat_lp), ref_lp), first_diff(np_bits(flat_lp), ref_lp)
+        assert same_bits(np_bits(flat_fp), ref_fp.view(np.uint32)), first_diff(np_bits(flat_fp), ref_fp.view(np.uint32))
+
+    # views (Sec. 3.2.3): zero copy, original shapes, flatten o unflatten = identity
+    views_fp = F.fsdp_views(lay, flat_fp)
+    views_lp = F.fsdp_views(lay, flat_lp)
+    for i, (v, p) in enumerate(zip(views_fp, params)):
+        assert tuple(v.shape) == tuple(p.shape)
+        if v.numel():
+            assert v.data_ptr() == flat_fp.data_ptr() + 4 * off[i]
+            assert views_lp[i].data_ptr() == flat_lp.data_ptr() + 2 * off[i]
+        assert same_bits(np_bits(v), np_bits(p))
+        assert same_bits(np_bits(views_lp[i]).reshape(-1), oracle.cast_bf16(np_f32(p)).reshape(-1))
+
+
+def make_grads(W, P, N, dtype, seed, outliers=False, elem_offset=0):
+    grads = []
+    for w in range(W):
+        t = carve(P, dtype, elem_offset)
+        workloads.gen_rank_grad(P, N, w, 0, "bf16" if dtype == torch.bfloat16 else "f32", device="cuda", seed=seed,
+                                outlier_frac=0.01 if outliers else 0.0, outlier_scale=1e3, out=t)
+        grads.append(t)
+    return grads
+
+
+@pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("W,pre,post", [(1, 1.0, 1.0), (2, 2.0, 1.0), (3, 1.0, 3.0), (3, 3.0, 1.0), (8, 4.0, 2.0),
+                                        (12, 4.0, 3.0), (16, 4.0, 4.0), (64, 8.0, 8.0), (70, 2.0, 35.0),
+                                        (130, 1.0, 130.0), (5, 2.5, 2.0)])
+def test_reduce_scatter_bit_exact(F, gdt, W, pre, post):
+    unit = workloads.ragged_unit() if W > 16 else big_unit()
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S, P, N = lay.shard, lay.padded, lay.numel
+    grads = make_grads(W, P, N, gdt, 99 + W, outliers=True, elem_offset=(1 if W % 2 else 0))
+    # special values in rank 0 / all ranks: signed zeros, a denormal, a large value
+    for w, g in enumerate(grads):
+        g[:4] = torch.tensor([-0.0, -0.0 if w != 1 else 0.0, 1e-40, 3e38 if w < 2 else 0.0], dtype=gdt)
+    host = [np_grad(g) for g in grads]
+    ranks = range(W) if W <= 16 else (0, 1, W // 2, W - 1)
+    for r in ranks:
+        out = carve(S, torch.float32, r % 3, fill=POISON32)
+        F.fsdp_reduce_scatter_local(lay, grads, r, pre, post, out)
+        torch.cuda.synchronize()
+        ref = oracle.reduce_scatter(host, r, pre, post)
+        got = np_bits(out)
+        assert same_bits(got, ref.view(np.uint32)), f"rank {r}: {first_diff(got, ref.view(np.uint32))}"
+
+
+def test_reduce_order_witness_on_gpu(F):
+    """((1e8 + 1) - 1e8) + 1 = 1 only in strict rank order."""
+    lay = F.fsdp_layout_init([(4000,)], 4)
+    vals = [1e8, 1.0, -1e8, 1.0]
+    grads = [torch.full((lay.padded,), v, dtype=torch.float32, device="cuda") for v in vals]
+    out = torch.empty(lay.shard, dtype=torch.float32, device="cuda")
+    F.fsdp_reduce_scatter_local(lay, grads, 2, 1.0, 1.0, out)
+    torch.cuda.synchronize()
+    assert bool((out == 1.0).all())
+
+
+def _adam_state(S, t, seed, offs=(0, 0, 0, 0)):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    p = carve(S, torch.float32, offs[0]).normal_(0, 0.02, generator=g)
+    gr = carve(S, torch.float32, offs[1]).normal_(0, 1e-3, generator=g)
+    m = carve(S, torch.float32, offs[2])
+    v = carve(S, torch.float32, offs[3])
+    if t > 1:
+        m.normal_(0, 1e-3, generator=g)
+        v.uniform_(0, 1e-6, generator=g)
+    else:
+        m.zero_()
+        v.zero_()
+    return p, gr, m, v
+
+
+@pytest.mark.parametrize("t", [1, 2, 7, 1000])
+@pytest.mark.parametrize("S,offs", [(1, (0, 0, 0, 0)), (5, (1, 2, 3, 0)), (4099, (0, 0, 0, 0)), (100003, (3, 1, 0, 2)),
+                                    (262144, (0, 0, 0, 0))])
+def test_adam_step(F, t, S, offs):
+    lay = F.fsdp_layout_init([(S,)], 1)
+    p, g, m, v = _adam_state(S, t, 5 + t + S, offs)
+    g[:1] = 0.0
+    hp, hg, hm, hv = (np_f32(x).copy() for x in (p, g, m, v))
+    F.fsdp_shard_adam_step(lay, p, g, m, v, t, LR, B1, B2, EPS)
+    torch.cuda.synchronize()
+    rp, rm, rv = oracle.adam_f32(hp, hg, hm, hv, t, LR, B1, B2, EPS)
+    ok, bad = adam_close(np_f32(p), np_f32(m), np_f32(v), rp, rm, rv, hp, hm, hg)
+    assert ok, f"vs fp32 oracle: {bad}"
+    dp, dm, dv = oracle.adam_f64(hp, hg, hm, hv, t, LR, B1, B2, EPS)
+    ok, bad = adam_close(np_f32(p), np_f32(m), np_f32(v), dp, dm, dv, hp, hm, hg)
+    assert ok, f"vs fp64 oracle: {bad}"
+    assert same_bits(np_bits(g), hg.view(np.uint32))            # the gradient is not modified
+
+
+def test_adam_pad_stays_zero_and_is_deterministic(F):
+    S = 10007
+    lay = F.fsdp_layout_init([(S,)], 1)
+    p, g, m, v = _adam_state(S, 1, 77)
+    p[-5:] = 0.0
+    g[-5:] = 0.0
+    snap = [x.clone() for x in (p, g, m, v)]
+    F.fsdp_shard_adam_step(lay, p, g, m, v, 1, LR, B1, B2, EPS)
+    torch.cuda.synchronize()
+    assert not np_bits(p)[-5:].any() and not np_bits(m)[-5:].any() and not np_bits(v)[-5:].any()
+    p2, g2, m2, v2 = snap
+    F.fsdp_shard_adam_step(lay, p2, g2, m2, v2, 1, LR, B1, B2, EPS)
+    torch.cuda.synchronize()
+    assert same_bits(np_bits(p), np_bits(p2)) and same_bits(np_bits(m), np_bits(m2)) and same_bits(np_bits(v), np_bits(v2))
+
+
+@pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("W", [3, 8, 70])
+@pytest.mark.parametrize("with_outputs", [True, False])
+def test_fused_reduce_scatter_adam_equals_two_calls(F, gdt, W, with_outputs):
+    unit = big_unit() if W <= 8 else workloads.ragged_unit()
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S, P, N = lay.shard, lay.padded, lay.numel
+    pre, post = F.fsdp_default_divide_factors(W)
+    grads = make_grads(W, P, N, gdt, 300 + W)
+    r = W - 1
+    t = 3
+    p, _, m, v = _adam_state(S, t, 17, (1, 0, 2, 3))
+    p2, m2, v2 = p.clone(), m.clone(), v.clone()
+    hp, hm, hv = (np_f32(x).copy() for x in (p, m, v))
+    # two calls
+    gs = torch.empty(S, dtype=torch.float32, device="cuda")
+    F.fsdp_reduce_scatter_local(lay, grads, r, pre, post, gs)
+    F.fsdp_shard_adam_step(lay, p, gs, m, v, t, LR, B1, B2, EPS)
+    # fused
+    need_g = with_outputs or W > 64
+    gs2 = carve(S, torch.float32, 1, fill=POISON32) if need_g else None
+    lp = carve(S, torch.bfloat16, 1, fill=POISON16) if with_outputs else None
+    F.fsdp_reduce_scatter_adam_fused(lay, grads, r, pre, post, gs2, p2, m2, v2, t, LR, B1, B2, EPS, lp)
+    torch.cuda.synchronize()
+    for a, b in ((p, p2), (m, m2), (v, v2)):
+        assert same_bits(np_bits(a), np_bits(b)), first_diff(np_bits(a), np_bits(b))
+    if need_g:
+        assert same_bits(np_bits(gs), np_bits(gs2))
+    if with_outputs:
+        assert same_bits(np_bits(lp), oracle.cast_bf16(np_f32(p2)))
+    # and against the oracle
+    ref_g = oracle.reduce_scatter([np_grad(g) for g in grads], r, pre, post)
+    assert same_bits(np_bits(gs), ref_g.view(np.uint32))
+    rp, rm, rv = oracle.adam_f32(hp, ref_g, hm, hv, t, LR, B1, B2, EPS)
+    ok, bad = adam_close(np_f32(p2), np_f32(m2), np_f32(v2), rp, rm, rv, hp, hm, ref_g)
+    assert ok, bad
+
+
+def test_whole_path_two_iterations_pad_stays_zero(F):
+    """flatten -> [unshard -> reduce-scatter -> Adam] x 2 for every rank of a
+    W = 12 unit with a pad; checks the unsharded bf16 buffer after the updates
+    and that the pad never leaves zero (state is caller-owned: resume = same buffers)."""
+    unit = workloads.Unit("u", ((1001, 7), (13,), (2048,)))
+    W = 12
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S, P, N = lay.shard, lay.padded, lay.numel
+    assert lay.pad > 0
+    params = workloads.gen_params(unit, 0, device="cuda")
+    shards = [torch.empty(S, dtype=torch.float32, device="cuda") for _ in range(W)]
+    F.fsdp_flatten_shard(lay, params, shards)
+    ms = [torch.zeros(S, device="cuda") for _ in range(W)]
+    vs = [torch.zeros(S, device="cuda") for _ in range(W)]
+    h_shards, _ = oracle.flatten_shard([np_f32(p) for p in params], W)
+    h_m = [np.zeros(S, np.float32) for _ in range(W)]
+    h_v = [np.zeros(S, np.float32) for _ in range(W)]
+    pre, post = F.fsdp_default_divide_factors(W)
+    flat = torch.empty(P, dtype=torch.bfloat16, device="cuda")
+    gs = torch.empty(S, dtype=torch.float32, device="cuda")
+    for t in (1, 2):
+        F.fsdp_unshard(lay, shards, flat)
+        torch.cuda.synchronize()
+        assert same_bits(np_bits(flat), oracle.unshard_bf16(h_shards))
+        grads = [workloads.gen_rank_grad(P, N, w, t, "f32", device="cuda") for w in range(W)]
+        h_grads = [np_f32(g) for g in grads]
+        for r in range(W):
+            F.fsdp_reduce_scatter_local(lay, grads, r, pre, post, gs)
+            F.fsdp_shard_adam_step(lay, shards[r], gs, ms[r], vs[r], t, LR, B1, B2, EPS)
+            torch.cuda.synchronize()
+            ref_g = oracle.reduce_scatter(h_grads, r, pre, post)
+            assert same_bits(np_bits(gs), ref_g.view(np.uint32))
+            old = h_shards[r]
+            h_shards[r], h_m[r], h_v[r] = oracle.adam_f32(old, ref_g, h_m[r], h_v[r], t, LR, B1, B2, EPS)
+            ok, bad = adam_close(np_f32(shards[r]), np_f32(ms[r]), np_f32(vs[r]), h_shards[r], h_m[r], h_v[r], old)
+            assert ok, (t, r, bad)
+            # keep both sides on identical state so that later steps stay comparable
+            shards[r].copy_(torch.from_numpy(h_shards[r]))
+            ms[r].copy_(torch.from_numpy(h_m[r]))
+            vs[r].copy_(torch.from_numpy(h_v[r]))
+        assert not np_bits(shards[W - 1])[S - lay.pad:].any()
+    views = F.fsdp_views(lay, flat)
+    assert [tuple(v.shape) for v in views] == [tuple(s) for s in unit.shapes]
+
+
+def test_hip_graph_replay_matches_eager(F):
+    """The entry points allocate and synchronise nothing, so a caller may
+    capture them; every replay must reproduce the eager result."""
+    unit = workloads.Unit("u", ((513, 33), (77,), (4096,)))
+    W = 8
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S, P, N = lay.shard, lay.padded, lay.numel
+    pre, post = F.fsdp_default_divide_factors(W)
+    params = workloads.gen_params(unit, 3, device="cuda")
+    shards = [torch.empty(S, dtype=torch.float32, device="cuda") for _ in range(W)]
+    F.fsdp_flatten_shard(lay, params, shards)
+    grads = [workloads.gen_rank_grad(P, N, w, 0, "f32", device="cuda") for w in range(W)]
+    flat = torch.empty(P, dtype=torch.bfloat16, device="cuda")
+    gs = torch.empty(S, dtype=torch.float32, device="cuda")
+    p0 = shards[0].clone()
+    m = torch.zeros(S, device="cuda")
+    v = torch.zeros(S, device="cuda")
+
+    def step():
+        F.fsdp_unshard(lay, shards, flat)
+        F.fsdp_reduce_scatter_local(lay, grads, 0, pre, post, gs)
+        F.fsdp_shard_adam_step(lay, shards[0], gs, m, v, 1, LR, B1, B2, EPS)
+
+    step()
+    torch.cuda.synchronize()
+    eager = [x.clone() for x in (flat, gs, shards[0], m, v)]
+
+    def reset():
+        shards[0].copy_(p0)
+        m.fill_(0.0)
+        v.fill_(0.0)
+        flat.fill_(0.0)
+        gs.fill_(0.0)
+
+    reset()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    for _ in range(3):
+        reset()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(eager, (flat, gs, shards[0], m, v)):
+            assert same_bits(np_bits(a), np_bits(b))
