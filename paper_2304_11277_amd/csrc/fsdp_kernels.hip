@@ -717,7 +717,9 @@ int fsdp_unshard(const fsdp_layout_t* L, const float* const* shard_ptrs, void* f
     }
     const bool bf16 = out_dtype == FSDP_BF16;
     if (misaligned(flat_out, bf16 ? 2 : 4)) return FSDP_ERR_INVALID_ARG;
-    constexpr int U = 4;
+    // One destination vector per lane measured fastest on MI355X for the cast
+    // (more, shorter workgroups hide the ramp of small units better).
+    constexpr int U = 1;
     const int64_t vec = bf16 ? 8 : 4;
     const int64_t tiles = ceil_div(S / vec + 1, kBlock * U);
     if (!grid_ok(tiles * kMaxRanks)) return FSDP_ERR_OVERFLOW;

@@ -1,0 +1,131 @@
+"""GPU parity at the benchmark's full sizes: each distinct unit shape of the
+five configurations, through the same entry points and launch configuration
+bench.py times, compared element by element with the CPU oracle.
+
+Inputs are generated once on the device from the seeded workload module and
+copied to the host bit for bit; for the two largest configurations the host
+receives only the rank's slice of every rank's gradient buffer, which is all
+the reduce-scatter's rank share reads."""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from gpu_helpers import adam_close, first_diff, load_product, np_bits, np_f32, same_bits
+
+pytestmark = pytest.mark.gpu
+
+CASES = [(c, u) for c in range(workloads.NUM_CONFIGS) for u in workloads.config(c).distinct_units]
+
+
+def _ranks(cfg, W):
+    return list(range(W)) if cfg <= 2 else [0, 1, W - 1]
+
+
+@pytest.fixture(scope="module")
+def F():
+    assert torch.cuda.is_available()
+    return load_product()
+
+
+@pytest.mark.parametrize("cfg,unit_index", CASES, ids=[f"cfg{c}-unit{u}" for c, u in CASES])
+def test_config_unit_matches_oracle(F, cfg, unit_index):
+    wl = workloads.config(cfg)
+    unit = wl.units[unit_index]
+    W = wl.world_size
+    hp = (wl.lr, wl.beta1, wl.beta2, wl.eps)
+    print(f"\n[case] {wl.name} unit {unit.name} W={W}", flush=True)
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S, P, N = lay.shard, lay.padded, lay.numel
+    pre, post = F.fsdp_default_divide_factors(W)
+    off_ref, N_ref, S_ref, P_ref, pad_ref = oracle.layout(unit.shapes, W)
+    assert (N, S, P, lay.pad) == (N_ref, S_ref, P_ref, pad_ref)
+
+    # ---- flatten + pad + shard (contiguous shards: base + w*S, as bench.py lays them out)
+    params = workloads.gen_params(unit, unit_index, device="cuda")
+    base = torch.empty(W * S, dtype=torch.float32, device="cuda")
+    base.view(torch.int32).fill_(0x7FC00001)
+    shards = [base[w * S:(w + 1) * S] for w in range(W)]
+    F.fsdp_flatten_shard(lay, params, shards)
+    torch.cuda.synchronize()
+    h_params = [np_f32(p) for p in params]
+    del params
+    h_shards, _ = oracle.flatten_shard(h_params, W)
+    del h_params
+    got = np_bits(base)
+    ref = np.concatenate(h_shards).view(np.uint32)
+    assert same_bits(got, ref), "flatten_shard: " + first_diff(got, ref)
+    del got, ref
+    print("[step] flatten_shard bit-exact", flush=True)
+
+    # ---- unshard: cast + gather into the bf16 flat buffer, and the views
+    flat = torch.empty(P, dtype=torch.bfloat16, device="cuda")
+    flat.view(torch.int16).fill_(0x7FCD)
+    F.fsdp_unshard(lay, shards, flat)
+    torch.cuda.synchronize()
+    ref = oracle.unshard_bf16(h_shards)
+    got = np_bits(flat)
+    assert same_bits(got, ref), "unshard: " + first_diff(got, ref)
+    views = F.fsdp_views(lay, flat)
+    assert [tuple(v.shape) for v in views] == [tuple(s) for s in unit.shapes]
+    for i, v in enumerate(views):
+        assert v.data_ptr() == flat.data_ptr() + 2 * off_ref[i]
+    del got, ref, views, flat
+    print("[step] unshard bit-exact", flush=True)
+
+    # ---- gradients of the W simulated ranks
+    gdt = torch.float32 if wl.grad_dtype == "f32" else torch.bfloat16
+    grads = []
+    for w in range(W):
+        g = torch.empty(P, dtype=gdt, device="cuda")
+        workloads.gen_rank_grad(P, N, w, unit_index, wl.grad_dtype, device="cuda", outlier_frac=wl.outlier_frac,
+                                outlier_scale=wl.outlier_scale, out=g)
+        grads.append(g)
+    torch.cuda.synchronize()
+
+    gs = torch.empty(S, dtype=torch.float32, device="cuda")
+    for r in _ranks(cfg, W):
+        if gdt == torch.float32:
+            h_slices = [np_f32(g[r * S:(r + 1) * S]) for g in grads]
+        else:
+            h_slices = [np_bits(g[r * S:(r + 1) * S]) for g in grads]
+        ref_g = oracle.reduce_slices(h_slices, pre, post)
+        del h_slices
+        gs.view(torch.int32).fill_(0x7FC00001)
+        F.fsdp_reduce_scatter_local(lay, grads, r, pre, post, gs)
+        torch.cuda.synchronize()
+        got = np_bits(gs)
+        assert same_bits(got, ref_g.view(np.uint32)), f"reduce-scatter rank {r}: " + first_diff(got, ref_g.view(np.uint32))
+
+        # Adam on this rank's shard, first step from zero state; then the fused call from the same start
+        p = shards[r].clone()
+        m = torch.zeros(S, device="cuda")
+        v = torch.zeros(S, device="cuda")
+        F.fsdp_shard_adam_step(lay, p, gs, m, v, 1, *hp)
+        p2 = shards[r].clone()
+        m2 = torch.zeros(S, device="cuda")
+        v2 = torch.zeros(S, device="cuda")
+        F.fsdp_reduce_scatter_adam_fused(lay, grads, r, pre, post, None, p2, m2, v2, 1, *hp, None)
+        torch.cuda.synchronize()
+        z = np.zeros(S, np.float32)
+        rp, rm, rv = oracle.adam_f32(h_shards[r], ref_g, z, z, 1, *hp)
+        gp, gm, gv = np_f32(p), np_f32(m), np_f32(v)
+        ok, bad = adam_close(gp, gm, gv, rp, rm, rv, h_shards[r])
+        assert ok, f"Adam rank {r} vs fp32 oracle: {bad}"
+        dp, dm, dv = oracle.adam_f64(h_shards[r], ref_g, z, z, 1, *hp)
+        ok, bad = adam_close(gp, gm, gv, dp, dm, dv, h_shards[r])
+        assert ok, f"Adam rank {r} vs fp64 oracle: {bad}"
+        exact = same_bits(gp.view(np.uint32), rp.view(np.uint32))
+        for a, b, n in ((p, p2, "p"), (m, m2, "m"), (v, v2, "v")):
+            assert same_bits(np_bits(a), np_bits(b)), f"fused {n} differs from the two-call path at rank {r}"
+        if lay.pad and r == W - 1:
+            assert not np_bits(p)[S - lay.pad:].any()
+        print(f"[step] rank {r}: reduce-scatter bit-exact, Adam within 1e-6 (bit-identical to fp32 oracle: {exact}), "
+              f"fused == two calls", flush=True)
+        del p, m, v, p2, m2, v2, rp, rm, rv, dp, dm, dv, gp, gm, gv, ref_g
+    del grads, shards, base, h_shards
+    gc.collect()
+    torch.cuda.empty_cache()
