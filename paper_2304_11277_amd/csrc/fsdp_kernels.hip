@@ -23,6 +23,8 @@ namespace {
 constexpr int kBlock = 256;                           // 4 wavefronts of 64 lanes
 constexpr int kMaxRanks = FSDP_MAX_RANKS_PER_LAUNCH;  // rank pointers per kernarg table
 constexpr int kMaxSegs = 24;                          // parameter segments per pack launch
+// launch shapes of the reduce kernels (measured on MI355X)
+constexpr int kReduceBlock = 256;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -291,8 +293,9 @@ struct RsArgs {
     int32_t W;            // ranks in this launch's table
     int32_t cont;         // 1: accumulator continues from out[] (a later launch of a split W)
     int32_t last;         // 1: apply the post divide (and Adam) in this launch
+    int32_t post_mul;     // 1: post is a power of two, post_c holds its exact reciprocal
     float pre_c;          // pre (kPreDiv) or 1/pre (kPreMul)
-    float post;
+    float post_c;         // post, or 1/post when post_mul
     int64_t S;
     float* out;           // grad shard (may be null only when fused and !cont and last)
     float* p;             // Adam state (fused only)
@@ -302,117 +305,115 @@ struct RsArgs {
     AdamConsts adam;
 };
 
-// E = elements per lane-chunk: 4 for fp32 gradients, 8 for bf16 (16-byte loads
-// from every rank either way).  U chunks per lane.
-template <bool BF16, int PRE, bool FUSED, int U>
-__global__ __launch_bounds__(kBlock) void reduce_kernel(PtrTable grads, RsArgs a)
+__device__ __forceinline__ float post_scale(float x, const RsArgs& a)
+{
+    return a.post_mul ? x * a.post_c : x / a.post_c;
+}
+
+// Loads one 16-byte vector from each of N consecutive ranks (all N loads are
+// issued before the first use), then adds the N terms to acc strictly in rank
+// order.  E = 4 elements per vector for fp32 gradients, 8 for bf16.
+template <bool BF16, int PRE, int N, int E>
+__device__ __forceinline__ void accumulate_ranks(const PtrTable& grads, int32_t w0, int64_t k, float pre_c,
+                                                 float (&acc)[E])
+{
+    u32x4 x[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        if constexpr (BF16)
+            x[j] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4_a2*>(static_cast<const uint16_t*>(grads.p[w0 + j]) + k));
+        else
+            x[j] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4_a4*>(static_cast<const float*>(grads.p[w0 + j]) + k));
+    }
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        float t[E];
+        if constexpr (BF16) {   // exact upcast: the bf16 pattern is the top half of the fp32 one
+            t[0] = u2f(x[j].x << 16); t[1] = u2f(x[j].x & 0xFFFF0000u);
+            t[2] = u2f(x[j].y << 16); t[3] = u2f(x[j].y & 0xFFFF0000u);
+            t[4] = u2f(x[j].z << 16); t[5] = u2f(x[j].z & 0xFFFF0000u);
+            t[6] = u2f(x[j].w << 16); t[7] = u2f(x[j].w & 0xFFFF0000u);
+        } else {
+            t[0] = u2f(x[j].x); t[1] = u2f(x[j].y); t[2] = u2f(x[j].z); t[3] = u2f(x[j].w);
+        }
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[e] = acc[e] + pre_scale<PRE>(t[e], pre_c);
+    }
+}
+
+// One lane owns one chunk of E consecutive elements (one 16-byte load per
+// rank).  The accumulator starts at -0.0f, the identity of IEEE addition
+// ((-0) + x == x bit for bit, signed zeros included), which is the same as
+// initialising it from rank 0's term; a later launch of a split W starts from
+// the carried partial sum instead.  Ranks are walked in groups of 8, 4, 2, 1.
+// In the fused form the chunk's Adam state is fetched before the rank loop so
+// that the lane pays one memory latency, not two.  Everything a live lane does
+// sits under one branch, so the loads of a group issue back to back.
+template <bool BF16, int PRE, bool FUSED, int B>
+__global__ __launch_bounds__(B) void reduce_kernel(PtrTable grads, RsArgs a)
 {
     constexpr int E = BF16 ? 8 : 4;
+    constexpr int Q = E / 4;
     // The chunk grid is aligned on the primary fp32 output.
     float* __restrict__ master = FUSED ? a.p : a.out;
     const int64_t S = a.S;
     const int64_t head = head_elems(master, 4, S);
     const int64_t nvec = (S - head) / E;
-    const int64_t base = static_cast<int64_t>(blockIdx.x) * (kBlock * U) + threadIdx.x;
-
-    float acc[U][E];
-    bool live[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int64_t c = base + u * kBlock;
-        live[u] = c < nvec;
-    }
-
-    // first term (or the carried partial sum)
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        if (!live[u]) continue;
-        const int64_t k = head + (base + u * kBlock) * E;
-        if (a.cont) {
-            const f32x4 t0 = *reinterpret_cast<const f32x4_a4*>(a.out + k);
-            acc[u][0] = t0.x; acc[u][1] = t0.y; acc[u][2] = t0.z; acc[u][3] = t0.w;
-            if constexpr (E == 8) {
-                const f32x4 t1 = *reinterpret_cast<const f32x4_a4*>(a.out + k + 4);
-                acc[u][4] = t1.x; acc[u][5] = t1.y; acc[u][6] = t1.z; acc[u][7] = t1.w;
-            }
-        }
-    }
-
+    const int64_t c = static_cast<int64_t>(blockIdx.x) * B + threadIdx.x;
     const int32_t W = a.W;
-    for (int32_t w0 = 0; w0 < W; w0 += 8) {
-        u32x4 x[8][U];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            if (w0 + j < W) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    if (!live[u]) continue;
-                    const int64_t k = head + (base + u * kBlock) * E;
-                    if constexpr (BF16)
-                        x[j][u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a2*>(
-                            static_cast<const uint16_t*>(grads.p[w0 + j]) + k));
-                    else
-                        x[j][u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a4*>(
-                            static_cast<const float*>(grads.p[w0 + j]) + k));
-                }
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            if (w0 + j < W) {
-                const bool init = (w0 + j == 0) && !a.cont;
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    if (!live[u]) continue;
-                    float t[E];
-                    if constexpr (BF16) {   // exact upcast: the bf16 pattern is the top half of the fp32 one
-                        t[0] = u2f(x[j][u].x << 16); t[1] = u2f(x[j][u].x & 0xFFFF0000u);
-                        t[2] = u2f(x[j][u].y << 16); t[3] = u2f(x[j][u].y & 0xFFFF0000u);
-                        t[4] = u2f(x[j][u].z << 16); t[5] = u2f(x[j][u].z & 0xFFFF0000u);
-                        t[6] = u2f(x[j][u].w << 16); t[7] = u2f(x[j][u].w & 0xFFFF0000u);
-                    } else {
-                        t[0] = u2f(x[j][u].x); t[1] = u2f(x[j][u].y);
-                        t[2] = u2f(x[j][u].z); t[3] = u2f(x[j][u].w);
-                    }
-#pragma unroll
-                    for (int e = 0; e < E; ++e) {
-                        const float term = pre_scale<PRE>(t[e], a.pre_c);
-                        acc[u][e] = init ? term : acc[u][e] + term;
-                    }
-                }
-            }
-        }
-    }
 
-    // epilogue
+    if (c < nvec) {
+        const int64_t k = head + c * E;
+        f32x4 pv[Q], mv[Q], vv[Q];
+        if constexpr (FUSED) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        if (!live[u]) continue;
-        const int64_t k = head + (base + u * kBlock) * E;
+            for (int q = 0; q < Q; ++q) {
+                pv[q] = *reinterpret_cast<const f32x4*>(a.p + k + 4 * q);
+                mv[q] = *reinterpret_cast<const f32x4_a4*>(a.m + k + 4 * q);
+                vv[q] = *reinterpret_cast<const f32x4_a4*>(a.v + k + 4 * q);
+            }
+        }
+        float acc[E];
+        if (a.cont) {
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const f32x4 t = *reinterpret_cast<const f32x4_a4*>(a.out + k + 4 * q);
+                acc[4 * q] = t.x; acc[4 * q + 1] = t.y; acc[4 * q + 2] = t.z; acc[4 * q + 3] = t.w;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[e] = -0.0f;
+        }
+
+        int32_t w = 0;
+        for (; w + 8 <= W; w += 8) accumulate_ranks<BF16, PRE, 8, E>(grads, w, k, a.pre_c, acc);
+        if (W & 4) { accumulate_ranks<BF16, PRE, 4, E>(grads, w, k, a.pre_c, acc); w += 4; }
+        if (W & 2) { accumulate_ranks<BF16, PRE, 2, E>(grads, w, k, a.pre_c, acc); w += 2; }
+        if (W & 1) { accumulate_ranks<BF16, PRE, 1, E>(grads, w, k, a.pre_c, acc); }
+
         if (a.last) {
 #pragma unroll
-            for (int e = 0; e < E; ++e) acc[u][e] = acc[u][e] / a.post;
+            for (int e = 0; e < E; ++e) acc[e] = post_scale(acc[e], a);
         }
         if (a.out != nullptr) {
 #pragma unroll
-            for (int q = 0; q < E / 4; ++q) {
-                f32x4 o = {acc[u][4 * q], acc[u][4 * q + 1], acc[u][4 * q + 2], acc[u][4 * q + 3]};
+            for (int q = 0; q < Q; ++q) {
+                f32x4 o = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
                 *reinterpret_cast<f32x4_a4*>(a.out + k + 4 * q) = o;
             }
         }
-        if (FUSED) {
+        if constexpr (FUSED) {
             uint32_t lp[E / 2];
 #pragma unroll
-            for (int q = 0; q < E / 4; ++q) {
-                f32x4 pv = *reinterpret_cast<const f32x4*>(a.p + k + 4 * q);
-                f32x4 mv = *reinterpret_cast<const f32x4_a4*>(a.m + k + 4 * q);
-                f32x4 vv = *reinterpret_cast<const f32x4_a4*>(a.v + k + 4 * q);
-                adam_update4(pv, &acc[u][4 * q], mv, vv, a.adam);
-                *reinterpret_cast<f32x4*>(a.p + k + 4 * q) = pv;
-                *reinterpret_cast<f32x4_a4*>(a.m + k + 4 * q) = mv;
-                *reinterpret_cast<f32x4_a4*>(a.v + k + 4 * q) = vv;
-                lp[2 * q] = pack_bf16x2(pv.x, pv.y);
-                lp[2 * q + 1] = pack_bf16x2(pv.z, pv.w);
+            for (int q = 0; q < Q; ++q) {
+                adam_update4(pv[q], &acc[4 * q], mv[q], vv[q], a.adam);
+                *reinterpret_cast<f32x4*>(a.p + k + 4 * q) = pv[q];
+                *reinterpret_cast<f32x4_a4*>(a.m + k + 4 * q) = mv[q];
+                *reinterpret_cast<f32x4_a4*>(a.v + k + 4 * q) = vv[q];
+                lp[2 * q] = pack_bf16x2(pv[q].x, pv[q].y);
+                lp[2 * q + 1] = pack_bf16x2(pv[q].z, pv[q].w);
             }
             if (a.p_lp != nullptr) {
                 if constexpr (E == 8) {
@@ -433,18 +434,15 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(PtrTable grads, RsArgs a
         const int t = threadIdx.x;
         if (t < nrag) {
             const int64_t k = t < head ? t : tail0 + (t - head);
-            float r = a.cont ? a.out[k] : 0.0f;
-            for (int32_t w = 0; w < W; ++w) {
-                const float term = pre_scale<PRE>(load_grad<BF16>(grads.p[w], k), a.pre_c);
-                r = (w == 0 && !a.cont) ? term : r + term;
-            }
-            if (a.last) r = r / a.post;
+            float r = a.cont ? a.out[k] : -0.0f;
+            for (int32_t w = 0; w < W; ++w) r = r + pre_scale<PRE>(load_grad<BF16>(grads.p[w], k), a.pre_c);
+            if (a.last) r = post_scale(r, a);
             if (a.out != nullptr) a.out[k] = r;
-            if (FUSED) {
-                float pv = a.p[k], mv = a.m[k], vv = a.v[k];
-                adam_update(pv, r, mv, vv, a.adam);
-                a.p[k] = pv; a.m[k] = mv; a.v[k] = vv;
-                if (a.p_lp != nullptr) a.p_lp[k] = static_cast<uint16_t>(bf16_rne(f2u(pv)));
+            if constexpr (FUSED) {
+                float pk = a.p[k], mk = a.m[k], vk = a.v[k];
+                adam_update(pk, r, mk, vk, a.adam);
+                a.p[k] = pk; a.m[k] = mk; a.v[k] = vk;
+                if (a.p_lp != nullptr) a.p_lp[k] = static_cast<uint16_t>(bf16_rne(f2u(pk)));
             }
         }
     }
@@ -453,38 +451,24 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(PtrTable grads, RsArgs a
 // ---------------------------------------------------------------------------
 // Adam on the shard (Sec. 5.4; state sharded as in Sec. 3)
 // ---------------------------------------------------------------------------
-template <int U>
 __global__ __launch_bounds__(kBlock) void adam_kernel(float* __restrict__ p, const float* __restrict__ g,
                                                        float* __restrict__ m, float* __restrict__ v,
                                                        int64_t S, AdamConsts c)
 {
     const int64_t head = head_elems(p, 4, S);
     const int64_t nvec = (S - head) >> 2;
-    const int64_t base = static_cast<int64_t>(blockIdx.x) * (kBlock * U) + threadIdx.x;
-
-    f32x4 pv[U], gv[U], mv[U], vv[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int64_t cidx = base + u * kBlock;
-        if (cidx < nvec) {
-            const int64_t k = head + (cidx << 2);
-            pv[u] = *reinterpret_cast<const f32x4*>(p + k);
-            gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(g + k));
-            mv[u] = *reinterpret_cast<const f32x4_a4*>(m + k);
-            vv[u] = *reinterpret_cast<const f32x4_a4*>(v + k);
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int64_t cidx = base + u * kBlock;
-        if (cidx < nvec) {
-            const int64_t k = head + (cidx << 2);
-            const float gg[4] = {gv[u].x, gv[u].y, gv[u].z, gv[u].w};
-            adam_update4(pv[u], gg, mv[u], vv[u], c);
-            *reinterpret_cast<f32x4*>(p + k) = pv[u];
-            *reinterpret_cast<f32x4_a4*>(m + k) = mv[u];
-            *reinterpret_cast<f32x4_a4*>(v + k) = vv[u];
-        }
+    const int64_t cidx = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (cidx < nvec) {
+        const int64_t k = head + (cidx << 2);
+        f32x4 pv = *reinterpret_cast<const f32x4*>(p + k);
+        const f32x4 gv = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(g + k));
+        f32x4 mv = *reinterpret_cast<const f32x4_a4*>(m + k);
+        f32x4 vv = *reinterpret_cast<const f32x4_a4*>(v + k);
+        const float gg[4] = {gv.x, gv.y, gv.z, gv.w};
+        adam_update4(pv, gg, mv, vv, c);
+        *reinterpret_cast<f32x4*>(p + k) = pv;
+        *reinterpret_cast<f32x4_a4*>(m + k) = mv;
+        *reinterpret_cast<f32x4_a4*>(v + k) = vv;
     }
     if (blockIdx.x == 0) {
         const int64_t tail0 = head + (nvec << 2);
@@ -560,10 +544,10 @@ template <bool BF16, int PRE, bool FUSED>
 void launch_reduce(const PtrTable& tab, const RsArgs& a, hipStream_t st)
 {
     constexpr int E = BF16 ? 8 : 4;
-    constexpr int U = BF16 ? 1 : 2;
-    const int64_t blocks = ceil_div(a.S / E + 1, kBlock * U);
-    hipLaunchKernelGGL((reduce_kernel<BF16, PRE, FUSED, U>), dim3(static_cast<uint32_t>(blocks)), dim3(kBlock), 0,
-                       st, tab, a);
+    constexpr int B = kReduceBlock;
+    const int64_t blocks = ceil_div(a.S / E + 1, B);
+    hipLaunchKernelGGL((reduce_kernel<BF16, PRE, FUSED, B>), dim3(static_cast<uint32_t>(blocks)), dim3(B), 0, st,
+                       tab, a);
 }
 
 template <bool BF16, bool FUSED>
@@ -590,6 +574,9 @@ int reduce_driver(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dty
     float recip;
     if (pre == 1.0f) pre_mode = kPreNone;
     else if (is_pow2_float(pre, &recip)) { pre_mode = kPreMul; pre_c = recip; }
+    float post_c = post;
+    int32_t post_mul = 0;
+    if (is_pow2_float(post, &recip)) { post_mul = 1; post_c = recip; }
 
     for (int32_t w0 = 0; w0 < W; w0 += kMaxRanks) {
         const int32_t nw = W - w0 < kMaxRanks ? W - w0 : kMaxRanks;
@@ -601,7 +588,8 @@ int reduce_driver(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dty
         a.cont = w0 > 0;
         a.last = w0 + nw == W;
         a.pre_c = pre_c;
-        a.post = post;
+        a.post_mul = post_mul;
+        a.post_c = post_c;
         a.S = S;
         a.out = out;
         a.p = p; a.m = m; a.v = v; a.p_lp = p_lp;
@@ -766,11 +754,10 @@ int fsdp_shard_adam_step(const fsdp_layout_t* L, float* p_shard, const float* g_
     if (rc != FSDP_OK) return rc;
     if (misaligned(p_shard, 4) || misaligned(g_shard, 4) || misaligned(exp_avg, 4) || misaligned(exp_avg_sq, 4))
         return FSDP_ERR_INVALID_ARG;
-    constexpr int U = 2;
-    const int64_t blocks = ceil_div(L->S / 4 + 1, kBlock * U);
+    const int64_t blocks = ceil_div(L->S / 4 + 1, kBlock);
     if (!grid_ok(blocks)) return FSDP_ERR_OVERFLOW;
     const AdamConsts c = make_adam_consts(step, lr, beta1, beta2, eps);
-    hipLaunchKernelGGL((adam_kernel<U>), dim3(static_cast<uint32_t>(blocks)), dim3(kBlock), 0,
+    hipLaunchKernelGGL(adam_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kBlock), 0,
                        static_cast<hipStream_t>(hip_stream), p_shard, g_shard, exp_avg, exp_avg_sq, L->S, c);
     return launch_status();
 }
