@@ -39,7 +39,9 @@ def parse_args():
     ap.add_argument("--mode", choices=["fused", "separate"], default="fused",
                     help="fused: reduce-scatter + Adam in one launch; separate: the two entry points")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
-    ap.add_argument("--streams", type=int, choices=[1, 2], default=2,
+    ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
+                    help="run only N launches of a plain 256 MiB copy kernel (calibrates rocprofv3 --pmc byte counters)")
+    ap.add_argument("--streams", type=int, choices=[1, 2], default=1,
                     help="2: unshards on one stream, reduce-scatter+Adam on a second (unit i's update overlaps "
                          "unit i+1's unshard, as in the paper's overlap of communication streams); 1: one stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -98,6 +100,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.probe_copy:
+        probe_copy(args.probe_copy, torch, fbuild)
+        return
     wl = workloads.config(args.config)
     units = list(wl.units)
     if args.max_units:
@@ -235,6 +240,26 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu, "kernels": per_kernel,
     }
     print(json.dumps(out), flush=True)
+
+
+def probe_copy(n, torch, fbuild):
+    """N launches of a plain copy of 256 MiB (reads 256 MiB, writes 256 MiB)."""
+    import ctypes
+    lib = ctypes.CDLL(fbuild.build_probe(force=False))
+    lib.fsdp_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    nbytes = 256 << 20
+    bufs = [(torch.ones(nbytes // 4, dtype=torch.float32, device="cuda"),
+             torch.empty(nbytes // 4, dtype=torch.float32, device="cuda")) for _ in range(3)]
+    torch.cuda.synchronize()
+    st = torch.cuda.current_stream().cuda_stream
+    for i in range(n):
+        src, dst = bufs[i % len(bufs)]
+        rc = lib.fsdp_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, st)
+        assert rc == 0, rc
+    torch.cuda.synchronize()
+    assert bool((bufs[0][1] == 1).all())
+    print(json.dumps({"probe": "copy", "launches": n, "bytes_read_per_launch": nbytes,
+                      "bytes_written_per_launch": nbytes}), flush=True)
 
 
 def cpu_baseline(states, wl, pre, post, rank, hp, torch):

@@ -11,6 +11,9 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfsdp_flat.so")
 SOURCES = [os.path.join(CSRC, "fsdp_layout.cpp"), os.path.join(CSRC, "fsdp_kernels.hip")]
 HEADERS = [os.path.join(ROOT, "include", "fsdp_flat.h"), os.path.join(CSRC, "fsdp_internal.h")]
+# counter-calibration copy kernel: a library of its own, loaded by bench.py --probe-copy only
+PROBE_LIB = os.path.join(HERE, "libfsdp_probe.so")
+PROBE_SRC = os.path.join(CSRC, "copy_probe.hip")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -49,5 +52,15 @@ def build_lib(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+def build_probe(force: bool = True) -> str:
+    if not force and os.path.exists(PROBE_LIB) and os.path.getmtime(PROBE_LIB) >= os.path.getmtime(PROBE_SRC):
+        return PROBE_LIB
+    tmp = PROBE_LIB + f".tmp{os.getpid()}"
+    subprocess.check_call([hipcc(), *HIPCC_FLAGS, "-x", "hip", PROBE_SRC, "-o", tmp])
+    os.replace(tmp, PROBE_LIB)
+    return PROBE_LIB
+
+
 if __name__ == "__main__":
     print(build_lib(force=True, verbose=True))
+    print(build_probe(force=True))
