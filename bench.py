@@ -36,14 +36,13 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="index into BASELINE.json configs (default 1)")
     ap.add_argument("--max-units", type=int, default=0, help="limit the number of units (0 = all)")
-    ap.add_argument("--mode", choices=["fused", "separate"], default="fused",
-                    help="fused: reduce-scatter + Adam in one launch; separate: the two entry points")
+    ap.add_argument("--mode", choices=["prefetch", "fused", "separate"], default="prefetch",
+                    help="prefetch: unit i's fused reduce-scatter+Adam shares one launch with unit i+1's unshard "
+                         "(backward prefetching); fused: reduce-scatter + Adam in one launch, unshard in another; "
+                         "separate: the three required entry points, one launch each")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
                     help="run only N launches of a plain 256 MiB copy kernel (calibrates rocprofv3 --pmc byte counters)")
-    ap.add_argument("--streams", type=int, choices=[1, 2], default=1,
-                    help="2: unshards on one stream, reduce-scatter+Adam on a second (unit i's update overlaps "
-                         "unit i+1's unshard, as in the paper's overlap of communication streams); 1: one stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
@@ -54,7 +53,7 @@ def parse_args():
 class UnitState:
     """Device buffers of one FSDP unit (caller-owned, as the library expects)."""
 
-    def __init__(self, F, wl, unit, index, torch, workloads):
+    def __init__(self, F, wl, unit, index, torch, workloads, share_grads_with=None):
         W = wl.world_size
         self.name = unit.name
         self.lay = F.fsdp_layout_init(unit.shapes, W)
@@ -67,12 +66,18 @@ class UnitState:
         F.fsdp_flatten_shard(self.lay, params, self.shards)
         del params
         gdt = torch.float32 if wl.grad_dtype == "f32" else torch.bfloat16
-        self.grads = []
-        for w in range(W):
-            g = torch.empty(P, dtype=gdt, device="cuda")
-            workloads.gen_rank_grad(P, N, w, index, wl.grad_dtype, device="cuda", outlier_frac=wl.outlier_frac,
-                                    outlier_scale=wl.outlier_scale, out=g)
-            self.grads.append(g)
+        if share_grads_with is not None:
+            # HBM cannot hold W gradient buffers for every unit of the largest workloads:
+            # units of equal shape then rotate over a few distinct sets of buffers.
+            assert share_grads_with.P == P
+            self.grads = share_grads_with.grads
+        else:
+            self.grads = []
+            for w in range(W):
+                g = torch.empty(P, dtype=gdt, device="cuda")
+                workloads.gen_rank_grad(P, N, w, index, wl.grad_dtype, device="cuda", outlier_frac=wl.outlier_frac,
+                                        outlier_scale=wl.outlier_scale, out=g)
+                self.grads.append(g)
         self.m = torch.zeros(S, dtype=torch.float32, device="cuda")
         self.v = torch.zeros(S, dtype=torch.float32, device="cuda")
         self.gshard = torch.empty(S, dtype=torch.float32, device="cuda")
@@ -109,7 +114,19 @@ def main():
         units = units[:args.max_units]
     pre, post = F.fsdp_default_divide_factors(wl.world_size)
     t0 = time.time()
-    states = [UnitState(F, wl, u, i, torch, workloads) for i, u in enumerate(units)]
+    states = []
+    grad_budget = 160e9          # bytes of HBM given to the simulated ranks' gradient buffers
+    used = 0.0
+    for i, u in enumerate(units):
+        share = None
+        need = wl.world_size * sum(workloads.numel(s) for s in u.shapes) * (4 if wl.grad_dtype == "f32" else 2)
+        if used + need > grad_budget:
+            same = [s for s in states if s.unit_shapes == u.shapes and s.owns_grads]
+            share = same[len(states) % len(same)] if same else None
+        st = UnitState(F, wl, u, i, torch, workloads, share_grads_with=share)
+        st.unit_shapes, st.owns_grads = u.shapes, share is None
+        used += need if share is None else 0
+        states.append(st)
     flat = torch.empty(max(s.P for s in states), dtype=torch.bfloat16, device="cuda")   # transient, reused
     torch.cuda.synchronize()
     log(f"[bench] {wl.name}: {len(states)} units, W={wl.world_size}, grads {wl.grad_dtype}, "
@@ -117,39 +134,52 @@ def main():
     hp = (wl.lr, wl.beta1, wl.beta2, wl.eps)
     rank = 0
 
+    # The unsharded flat parameter is transient (Sec. 3.2.1: peak memory is the
+    # largest unit); two buffers alternate, as with at most two unshards in flight.
+    flats = [flat, torch.empty_like(flat)]
+
     def unshard(s, buf):
         F.fsdp_unshard(s.lay, s.shard_tab, buf[:s.P])
 
     def reduce_adam(s, t):
-        if args.mode == "fused":
-            F.fsdp_reduce_scatter_adam_fused(s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m, s.v, t,
-                                             *hp, None)
-        else:
-            F.fsdp_reduce_scatter_local(s.lay, s.grad_tab, rank, pre, post, s.gshard)
-            F.fsdp_shard_adam_step(s.lay, s.shards[rank], s.gshard, s.m, s.v, t, *hp)
+        F.fsdp_reduce_scatter_adam_fused(s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m, s.v, t,
+                                         *hp, None)
 
-    # The unsharded flat parameter is transient (Sec. 3.2.1: peak memory is the
-    # largest unit); two buffers alternate, as with at most two unshards in flight.
-    flats = [flat, torch.empty_like(flat)] if args.streams == 2 else [flat]
+    def reduce_adam_prefetch(s, t, nxt, buf):
+        F.fsdp_reduce_scatter_adam_prefetch_unshard(s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m,
+                                                    s.v, t, *hp, None, nxt.lay, nxt.shard_tab, buf[:nxt.P])
+
+    # One step as a list of launches: (kernel kind, callable(t), algorithmic bytes).
+    launches = []
+    n = len(states)
+    for i, s in enumerate(states):
+        buf = flats[i % 2]
+        if args.mode == "prefetch":
+            if i == 0:
+                launches.append(("unshard", (lambda t, s=s, buf=buf: unshard(s, buf)), s.b_unshard))
+            if i + 1 < n:
+                nxt, nbuf = states[i + 1], flats[(i + 1) % 2]
+                launches.append(("reduce_adam+unshard",
+                                 (lambda t, s=s, nxt=nxt, nbuf=nbuf: reduce_adam_prefetch(s, t, nxt, nbuf)),
+                                 s.b_reduce + s.b_adam + nxt.b_unshard))
+            else:
+                launches.append(("reduce_adam", (lambda t, s=s: reduce_adam(s, t)), s.b_reduce + s.b_adam))
+        else:
+            launches.append(("unshard", (lambda t, s=s, buf=buf: unshard(s, buf)), s.b_unshard))
+            if args.mode == "fused":
+                launches.append(("reduce_adam", (lambda t, s=s: reduce_adam(s, t)), s.b_reduce + s.b_adam))
+            else:
+                launches.append(("reduce_scatter", (lambda t, s=s: F.fsdp_reduce_scatter_local(
+                    s.lay, s.grad_tab, rank, pre, post, s.gshard)), s.b_reduce))
+                launches.append(("adam", (lambda t, s=s: F.fsdp_shard_adam_step(
+                    s.lay, s.shards[rank], s.gshard, s.m, s.v, t, *hp)), s.b_adam))
 
     main_s = torch.cuda.Stream()
-    side_s = torch.cuda.Stream() if args.streams == 2 else None
 
     def step(t):
-        """One pass over all units.  Issued on main_s (and side_s)."""
-        if side_s is None:
-            for s in states:
-                unshard(s, flats[0])
-                reduce_adam(s, t)
-            return
-        for i, s in enumerate(states):
-            unshard(s, flats[i % 2])
-            ev = torch.cuda.Event()
-            ev.record(main_s)
-            side_s.wait_event(ev)                 # unit i's update follows its own unshard (it rewrites shard r)
-            with torch.cuda.stream(side_s):
-                reduce_adam(s, t)
-        main_s.wait_stream(side_s)                # the next pass reads the updated shards
+        """One pass over all units, in order, on main_s."""
+        for _kind, fn, _b in launches:
+            fn(t)
 
     use_graph = not args.no_graph
     graph = None
@@ -190,26 +220,29 @@ def main():
         # launch stream: average duration per launch with the same cold-cache
         # rotation over the units' buffers as in the timed steps.
         reps = 10
-        kinds = {"unshard": (lambda s: unshard(s, flats[0]), lambda s: s.b_unshard),
-                 "reduce_adam": (lambda s: reduce_adam(s, 2), lambda s: s.b_reduce + s.b_adam)}
+        kinds = []
+        for kind, _fn, _b in launches:
+            if kind not in kinds:
+                kinds.append(kind)
         with torch.cuda.stream(main_s):
-            for kind, (fn, nbytes) in kinds.items():
-                for s in states:
-                    fn(s)
+            for kind in kinds:
+                mine = [(fn, b) for k, fn, b in launches if k == kind]
+                for fn, _b in mine:
+                    fn(2)
                 a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 torch.cuda.synchronize()
                 a.record()
                 for _ in range(reps):
-                    for s in states:
-                        fn(s)
+                    for fn, _b in mine:
+                        fn(2)
                 b.record()
                 torch.cuda.synchronize()
                 tot_us = a.elapsed_time(b) * 1e3 / reps
-                nb = sum(nbytes(s) for s in states)
-                nl = len(states) * (2 if kind == "reduce_adam" and args.mode == "separate" else 1)
-                per_kernel[kind] = {"launches_per_step": nl, "avg_us": tot_us / nl,
-                                    "alg_bytes_per_launch": nb / nl, "GBps": nb / (tot_us * 1e-6) / 1e9}
-        dom = max(per_kernel, key=lambda k: per_kernel[k]["avg_us"])
+                nb = sum(b_ for _fn, b_ in mine)
+                per_kernel[kind] = {"launches_per_step": len(mine), "avg_us": tot_us / len(mine),
+                                    "total_us_per_step": tot_us, "alg_bytes_per_launch": nb / len(mine),
+                                    "GBps": nb / (tot_us * 1e-6) / 1e9}
+        dom = max(per_kernel, key=lambda k: per_kernel[k]["total_us_per_step"])
         traffic = None
         try:
             with open(args.traffic_json) as fh:
@@ -235,7 +268,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "units": len(states), "world_size": wl.world_size,
                    "grad_dtype": wl.grad_dtype, "unshard_dtype": "bf16", "rank": rank, "mode": args.mode,
-                   "hip_graph": use_graph, "streams": args.streams, "alg_bytes_per_step": step_bytes},
+                   "hip_graph": use_graph, "launches_per_step": len(launches), "alg_bytes_per_step": step_bytes},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "roofline": roofline, "cpu_baseline": cpu, "kernels": per_kernel,
     }

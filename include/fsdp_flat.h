@@ -137,6 +137,25 @@ int fsdp_reduce_scatter_adam_fused(const fsdp_layout_t* layout, const void* cons
                                    float beta1, float beta2, float eps, void* p_lp_out,
                                    void* hip_stream);
 
+/* ---- Sec. 3.3.2 backward prefetching as ONE launch ---------------------------
+ * The fused reduce-scatter + Adam of one unit (arguments as above) together
+ * with the unshard of another unit (next_*: arguments as fsdp_unshard), which
+ * must not depend on each other: the buffers of the two halves must not
+ * overlap.  The paper issues the next AllGather before the current
+ * ReduceScatter on separate streams; here both share one grid, so the drain of
+ * one half overlaps the ramp of the other with no cross-queue synchronisation.
+ * Results are bit-identical to calling fsdp_reduce_scatter_adam_fused and
+ * fsdp_unshard one after the other, which is also what happens (two launches)
+ * when either W exceeds FSDP_MAX_RANKS_PER_LAUNCH or next_out_dtype is FSDP_F32. */
+int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* layout, const void* const* grad_ptrs,
+                                              fsdp_dtype_t grad_dtype, int32_t rank, float pre_div,
+                                              float post_div, float* grad_shard_out, float* p_shard,
+                                              float* exp_avg, float* exp_avg_sq, int64_t step, float lr,
+                                              float beta1, float beta2, float eps, void* p_lp_out,
+                                              const fsdp_layout_t* next_layout,
+                                              const float* const* next_shard_ptrs, void* next_flat_out,
+                                              fsdp_dtype_t next_out_dtype, void* hip_stream);
+
 /* Last hipError_t seen by this thread inside the library (0 if none). */
 int fsdp_last_hip_error(void);
 /* Static string for a fsdp_status_t. */

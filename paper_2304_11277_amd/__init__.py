@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     fsdp_flatten_shard,
     fsdp_layout_init,
     fsdp_reduce_scatter_adam_fused,
+    fsdp_reduce_scatter_adam_prefetch_unshard,
     fsdp_reduce_scatter_local,
     fsdp_shard_adam_step,
     fsdp_unshard,

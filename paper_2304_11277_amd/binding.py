@@ -59,6 +59,8 @@ _SIGNATURES = {
     "fsdp_shard_adam_step": [_vp, _vp, _vp, _vp, _vp, _i64, _f32, _f32, _f32, _f32, _vp],
     "fsdp_reduce_scatter_adam_fused": [_vp, _pp, ctypes.c_int, _i32, _f32, _f32, _vp, _vp, _vp, _vp, _i64,
                                        _f32, _f32, _f32, _f32, _vp, _vp],
+    "fsdp_reduce_scatter_adam_prefetch_unshard": [_vp, _pp, ctypes.c_int, _i32, _f32, _f32, _vp, _vp, _vp, _vp, _i64,
+                                                  _f32, _f32, _f32, _f32, _vp, _vp, _pp, _vp, ctypes.c_int, _vp],
     "fsdp_last_hip_error": [],
 }
 
@@ -281,3 +283,24 @@ def fsdp_reduce_scatter_adam_fused(layout: Layout, grad_ptrs, rank: int, pre_div
                                                 float(post_div), _vp(g_out), *[_vp(x) for x in ptrs], int(step),
                                                 float(lr), float(beta1), float(beta2), float(eps), _vp(lp),
                                                 _stream_handle(stream)))
+
+
+def fsdp_reduce_scatter_adam_prefetch_unshard(layout: Layout, grad_ptrs, rank: int, pre_div: float, post_div: float,
+                                              grad_shard_out: Optional[torch.Tensor], p_shard, exp_avg, exp_avg_sq,
+                                              step: int, lr: float, beta1: float, beta2: float, eps: float,
+                                              p_lp_out: Optional[torch.Tensor], next_layout: Layout, next_shard_ptrs,
+                                              next_flat_out: torch.Tensor, stream=None) -> None:
+    tab, gdt = _grad_table(layout, grad_ptrs)
+    S = layout.shard
+    g_out = _dev_tensor(grad_shard_out, torch.float32, S, "grad_shard_out") if grad_shard_out is not None else None
+    lp = _dev_tensor(p_lp_out, torch.bfloat16, S, "p_lp_out") if p_lp_out is not None else None
+    ptrs = [_dev_tensor(t, torch.float32, S, n) for t, n in
+            ((p_shard, "p_shard"), (exp_avg, "exp_avg"), (exp_avg_sq, "exp_avg_sq"))]
+    shards = _ptr_table(next_shard_ptrs, torch.float32, next_layout.shard, next_layout.world_size, "next_shard_ptrs")
+    dt = _flat_dtype(next_flat_out)
+    _dev_tensor(next_flat_out, next_flat_out.dtype, next_layout.padded, "next_flat_out")
+    _check("fsdp_reduce_scatter_adam_prefetch_unshard",
+           lib().fsdp_reduce_scatter_adam_prefetch_unshard(
+               layout.handle, tab.array, gdt, int(rank), float(pre_div), float(post_div), _vp(g_out),
+               *[_vp(x) for x in ptrs], int(step), float(lr), float(beta1), float(beta2), float(eps), _vp(lp),
+               next_layout.handle, shards.array, _vp(next_flat_out.data_ptr()), dt, _stream_handle(stream)))

@@ -76,41 +76,28 @@ __device__ __forceinline__ int64_t head_elems(const void* p, int esize, int64_t 
 // grid = nshards * tiles_per_shard blocks; block b serves shard b / tiles and
 // tile b % tiles.  A tile is kBlock * U destination vectors of 16 bytes.
 // ---------------------------------------------------------------------------
-template <int U>
-__global__ __launch_bounds__(kBlock) void unshard_bf16_kernel(PtrTable shards, int64_t S,
-                                                               uint16_t* __restrict__ out_base,
-                                                               int32_t tiles_per_shard)
+// bid = index of the workgroup among the unshard workgroups of the launch
+__device__ __forceinline__ void unshard_bf16_body(const PtrTable& shards, int64_t S, uint16_t* __restrict__ out_base,
+                                                  int32_t tiles_per_shard, uint32_t bid)
 {
-    const int32_t w = blockIdx.x / tiles_per_shard;
-    const int32_t tile = blockIdx.x - w * tiles_per_shard;
+    const int32_t w = bid / tiles_per_shard;
+    const int32_t tile = bid - w * tiles_per_shard;
     const float* __restrict__ src = static_cast<const float*>(shards.p[w]);
     uint16_t* __restrict__ dst = out_base + static_cast<int64_t>(w) * S;
 
     const int64_t head = head_elems(dst, 2, S);
     const int64_t nvec = (S - head) >> 3;                  // full 8-element destination vectors
-    const int64_t base = static_cast<int64_t>(tile) * (kBlock * U) + threadIdx.x;
-
-    f32x4 a[U], b[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int64_t c = base + u * kBlock;
-        if (c < nvec) {
-            const float* s = src + head + (c << 3);
-            a[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(s));
-            b[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(s + 4));
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int64_t c = base + u * kBlock;
-        if (c < nvec) {
-            u32x4 o;
-            o.x = pack_bf16x2(a[u].x, a[u].y);
-            o.y = pack_bf16x2(a[u].z, a[u].w);
-            o.z = pack_bf16x2(b[u].x, b[u].y);
-            o.w = pack_bf16x2(b[u].z, b[u].w);
-            __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(dst + head + (c << 3)));
-        }
+    const int64_t c = static_cast<int64_t>(tile) * kBlock + threadIdx.x;
+    if (c < nvec) {
+        const float* s = src + head + (c << 3);
+        const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(s));
+        const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(s + 4));
+        u32x4 o;
+        o.x = pack_bf16x2(a.x, a.y);
+        o.y = pack_bf16x2(a.z, a.w);
+        o.z = pack_bf16x2(b.x, b.y);
+        o.w = pack_bf16x2(b.z, b.w);
+        __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(dst + head + (c << 3)));
     }
     if (tile == 0) {   // ragged head and tail of this shard: at most 7 elements each
         const int64_t tail0 = head + (nvec << 3);
@@ -121,7 +108,13 @@ __global__ __launch_bounds__(kBlock) void unshard_bf16_kernel(PtrTable shards, i
     }
 }
 
-template <int U>
+__global__ __launch_bounds__(kBlock) void unshard_bf16_kernel(PtrTable shards, int64_t S,
+                                                               uint16_t* __restrict__ out_base,
+                                                               int32_t tiles_per_shard)
+{
+    unshard_bf16_body(shards, S, out_base, tiles_per_shard, blockIdx.x);
+}
+
 __global__ __launch_bounds__(kBlock) void unshard_f32_kernel(PtrTable shards, int64_t S,
                                                               float* __restrict__ out_base,
                                                               int32_t tiles_per_shard)
@@ -133,18 +126,10 @@ __global__ __launch_bounds__(kBlock) void unshard_f32_kernel(PtrTable shards, in
 
     const int64_t head = head_elems(dst, 4, S);
     const int64_t nvec = (S - head) >> 2;
-    const int64_t base = static_cast<int64_t>(tile) * (kBlock * U) + threadIdx.x;
-
-    f32x4 a[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int64_t c = base + u * kBlock;
-        if (c < nvec) a[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(src + head + (c << 2)));
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int64_t c = base + u * kBlock;
-        if (c < nvec) __builtin_nontemporal_store(a[u], reinterpret_cast<f32x4*>(dst + head + (c << 2)));
+    const int64_t c = static_cast<int64_t>(tile) * kBlock + threadIdx.x;
+    if (c < nvec) {
+        const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(src + head + (c << 2)));
+        __builtin_nontemporal_store(a, reinterpret_cast<f32x4*>(dst + head + (c << 2)));
     }
     if (tile == 0) {
         const int64_t tail0 = head + (nvec << 2);
@@ -352,7 +337,7 @@ __device__ __forceinline__ void accumulate_ranks(const PtrTable& grads, int32_t 
 // that the lane pays one memory latency, not two.  Everything a live lane does
 // sits under one branch, so the loads of a group issue back to back.
 template <bool BF16, int PRE, bool FUSED, int B>
-__global__ __launch_bounds__(B) void reduce_kernel(PtrTable grads, RsArgs a)
+__device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs& a, uint32_t bid)
 {
     constexpr int E = BF16 ? 8 : 4;
     constexpr int Q = E / 4;
@@ -361,7 +346,7 @@ __global__ __launch_bounds__(B) void reduce_kernel(PtrTable grads, RsArgs a)
     const int64_t S = a.S;
     const int64_t head = head_elems(master, 4, S);
     const int64_t nvec = (S - head) / E;
-    const int64_t c = static_cast<int64_t>(blockIdx.x) * B + threadIdx.x;
+    const int64_t c = static_cast<int64_t>(bid) * B + threadIdx.x;
     const int32_t W = a.W;
 
     if (c < nvec) {
@@ -428,7 +413,7 @@ __global__ __launch_bounds__(B) void reduce_kernel(PtrTable grads, RsArgs a)
     }
 
     // ragged head / tail (fewer than 4 + E elements in total): one lane per element
-    if (blockIdx.x == 0) {
+    if (bid == 0) {
         const int64_t tail0 = head + nvec * E;
         const int64_t nrag = head + (S - tail0);
         const int t = threadIdx.x;
@@ -446,6 +431,29 @@ __global__ __launch_bounds__(B) void reduce_kernel(PtrTable grads, RsArgs a)
             }
         }
     }
+}
+
+template <bool BF16, int PRE, bool FUSED, int B>
+__global__ __launch_bounds__(B) void reduce_kernel(PtrTable grads, RsArgs a)
+{
+    reduce_body<BF16, PRE, FUSED, B>(grads, a, blockIdx.x);
+}
+
+// Backward prefetching (Sec. 3.3.2) as one launch: the first n_reduce
+// workgroups run the fused reduce-scatter + Adam of one unit, the rest the
+// unshard of another unit.  The two do not depend on each other, so sharing a
+// grid lets the drain of one overlap the ramp of the other without any
+// cross-queue synchronisation.
+template <bool BF16, int PRE>
+__global__ __launch_bounds__(kBlock) void reduce_adam_unshard_kernel(PtrTable grads, RsArgs a, uint32_t n_reduce,
+                                                                      PtrTable shards, int64_t S_next,
+                                                                      uint16_t* __restrict__ out_base,
+                                                                      int32_t tiles_per_shard)
+{
+    if (blockIdx.x < n_reduce)
+        reduce_body<BF16, PRE, true, kBlock>(grads, a, blockIdx.x);
+    else
+        unshard_bf16_body(shards, S_next, out_base, tiles_per_shard, blockIdx.x - n_reduce);
 }
 
 // ---------------------------------------------------------------------------
@@ -707,9 +715,8 @@ int fsdp_unshard(const fsdp_layout_t* L, const float* const* shard_ptrs, void* f
     if (misaligned(flat_out, bf16 ? 2 : 4)) return FSDP_ERR_INVALID_ARG;
     // One destination vector per lane measured fastest on MI355X for the cast
     // (more, shorter workgroups hide the ramp of small units better).
-    constexpr int U = 1;
     const int64_t vec = bf16 ? 8 : 4;
-    const int64_t tiles = ceil_div(S / vec + 1, kBlock * U);
+    const int64_t tiles = ceil_div(S / vec + 1, kBlock);
     if (!grid_ok(tiles * kMaxRanks)) return FSDP_ERR_OVERFLOW;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
@@ -720,11 +727,11 @@ int fsdp_unshard(const fsdp_layout_t* L, const float* const* shard_ptrs, void* f
         const dim3 grid(static_cast<uint32_t>(tiles * nw));
         if (bf16) {
             uint16_t* base = static_cast<uint16_t*>(flat_out) + static_cast<int64_t>(w0) * S;
-            hipLaunchKernelGGL((unshard_bf16_kernel<U>), grid, dim3(kBlock), 0, st, tab, S, base,
+            hipLaunchKernelGGL(unshard_bf16_kernel, grid, dim3(kBlock), 0, st, tab, S, base,
                                static_cast<int32_t>(tiles));
         } else {
             float* base = static_cast<float*>(flat_out) + static_cast<int64_t>(w0) * S;
-            hipLaunchKernelGGL((unshard_f32_kernel<U>), grid, dim3(kBlock), 0, st, tab, S, base,
+            hipLaunchKernelGGL(unshard_f32_kernel, grid, dim3(kBlock), 0, st, tab, S, base,
                                static_cast<int32_t>(tiles));
         }
         const int rc = launch_status();
@@ -779,6 +786,87 @@ int fsdp_reduce_scatter_adam_fused(const fsdp_layout_t* L, const void* const* gr
     const AdamConsts c = make_adam_consts(step, lr, beta1, beta2, eps);
     return reduce_driver(L, grad_ptrs, grad_dtype, rank, pre_div, post_div, grad_shard_out, true, p_shard, exp_avg,
                          exp_avg_sq, static_cast<uint16_t*>(p_lp_out), c, static_cast<hipStream_t>(hip_stream));
+}
+
+int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* L, const void* const* grad_ptrs,
+                                              fsdp_dtype_t grad_dtype, int32_t rank, float pre_div, float post_div,
+                                              float* grad_shard_out, float* p_shard, float* exp_avg,
+                                              float* exp_avg_sq, int64_t step, float lr, float beta1, float beta2,
+                                              float eps, void* p_lp_out, const fsdp_layout_t* next_layout,
+                                              const float* const* next_shard_ptrs, void* next_flat_out,
+                                              fsdp_dtype_t next_out_dtype, void* hip_stream)
+{
+    // validate both halves before anything is launched
+    int rc = check_reduce_args(L, grad_ptrs, grad_dtype, rank, pre_div, post_div);
+    if (rc != FSDP_OK) return rc;
+    if (!p_shard || !exp_avg || !exp_avg_sq) return FSDP_ERR_NULL_PTR;
+    rc = check_adam_args(step, lr, beta1, beta2, eps);
+    if (rc != FSDP_OK) return rc;
+    if (L->world_size > kMaxRanks && !grad_shard_out) return FSDP_ERR_NULL_PTR;
+    if (misaligned(p_shard, 4) || misaligned(exp_avg, 4) || misaligned(exp_avg_sq, 4) ||
+        (grad_shard_out && misaligned(grad_shard_out, 4)) || (p_lp_out && misaligned(p_lp_out, 2)))
+        return FSDP_ERR_INVALID_ARG;
+    const fsdp_layout_t* N = next_layout;
+    if (!N || !next_shard_ptrs || !next_flat_out) return FSDP_ERR_NULL_PTR;
+    if (next_out_dtype != FSDP_F32 && next_out_dtype != FSDP_BF16) return FSDP_ERR_BAD_DTYPE;
+    for (int32_t w = 0; w < N->world_size; ++w) {
+        if (!next_shard_ptrs[w]) return FSDP_ERR_NULL_PTR;
+        if (misaligned(next_shard_ptrs[w], 4)) return FSDP_ERR_INVALID_ARG;
+    }
+    if (misaligned(next_flat_out, next_out_dtype == FSDP_BF16 ? 2 : 4)) return FSDP_ERR_INVALID_ARG;
+
+    const int64_t E = grad_dtype == FSDP_BF16 ? 8 : 4;
+    const int64_t n_reduce = ceil_div(L->S / E + 1, kBlock);
+    const int64_t tiles = ceil_div(N->S / 8 + 1, kBlock);
+    const int64_t n_unshard = tiles * N->world_size;
+    const bool one_launch = L->world_size <= kMaxRanks && N->world_size <= kMaxRanks &&
+                            next_out_dtype == FSDP_BF16 && grid_ok(n_reduce + n_unshard);
+    if (!one_launch) {   // same results from the two separate entry points, one after the other
+        rc = fsdp_reduce_scatter_adam_fused(L, grad_ptrs, grad_dtype, rank, pre_div, post_div, grad_shard_out, p_shard,
+                                            exp_avg, exp_avg_sq, step, lr, beta1, beta2, eps, p_lp_out, hip_stream);
+        if (rc != FSDP_OK) return rc;
+        return fsdp_unshard(N, next_shard_ptrs, next_flat_out, next_out_dtype, hip_stream);
+    }
+
+    const int64_t esz = grad_dtype == FSDP_BF16 ? 2 : 4;
+    PtrTable gtab = {}, stab = {};
+    for (int32_t w = 0; w < L->world_size; ++w)
+        gtab.p[w] = static_cast<const char*>(grad_ptrs[w]) + static_cast<int64_t>(rank) * L->S * esz;
+    for (int32_t w = 0; w < N->world_size; ++w) stab.p[w] = next_shard_ptrs[w];
+    RsArgs a = {};
+    int pre_mode = kPreDiv;
+    float recip;
+    a.pre_c = pre_div;
+    if (pre_div == 1.0f) pre_mode = kPreNone;
+    else if (is_pow2_float(pre_div, &recip)) { pre_mode = kPreMul; a.pre_c = recip; }
+    a.post_c = post_div;
+    if (is_pow2_float(post_div, &recip)) { a.post_mul = 1; a.post_c = recip; }
+    a.W = L->world_size;
+    a.cont = 0;
+    a.last = 1;
+    a.S = L->S;
+    a.out = grad_shard_out;
+    a.p = p_shard; a.m = exp_avg; a.v = exp_avg_sq; a.p_lp = static_cast<uint16_t*>(p_lp_out);
+    a.adam = make_adam_consts(step, lr, beta1, beta2, eps);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const dim3 grid(static_cast<uint32_t>(n_reduce + n_unshard));
+    const uint32_t nr = static_cast<uint32_t>(n_reduce);
+    uint16_t* out_base = static_cast<uint16_t*>(next_flat_out);
+    const int32_t tl = static_cast<int32_t>(tiles);
+#define FSDP_LAUNCH_COMBINED(BF, PRE) \
+    hipLaunchKernelGGL((reduce_adam_unshard_kernel<BF, PRE>), grid, dim3(kBlock), 0, st, gtab, a, nr, stab, N->S, \
+                       out_base, tl)
+    if (grad_dtype == FSDP_BF16) {
+        if (pre_mode == kPreNone) FSDP_LAUNCH_COMBINED(true, kPreNone);
+        else if (pre_mode == kPreMul) FSDP_LAUNCH_COMBINED(true, kPreMul);
+        else FSDP_LAUNCH_COMBINED(true, kPreDiv);
+    } else {
+        if (pre_mode == kPreNone) FSDP_LAUNCH_COMBINED(false, kPreNone);
+        else if (pre_mode == kPreMul) FSDP_LAUNCH_COMBINED(false, kPreMul);
+        else FSDP_LAUNCH_COMBINED(false, kPreDiv);
+    }
+#undef FSDP_LAUNCH_COMBINED
+    return launch_status();
 }
 
 }  // extern "C"

@@ -200,6 +200,19 @@ def test_compute_entry_points_reject_bad_arguments_before_launch(L):
                                               st) == INVALID
     assert raw.fsdp_reduce_scatter_adam_fused(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(1), *ok_h,
                                               ctypes.c_void_p(0x50001), st) == INVALID
+    # one-launch prefetch form: both halves are validated before anything is launched
+    rc, hn = _init(raw, [(64,)], 4)
+    assert rc == OK
+    pf = raw.fsdp_reduce_scatter_adam_prefetch_unshard
+    assert pf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, None, good4, buf, 1, st) == NULL
+    assert pf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, hn, None, buf, 1, st) == NULL
+    assert pf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, hn, good4, None, 1, st) == NULL
+    assert pf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, hn, with_null, buf, 1, st) == NULL
+    assert pf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, hn, good4, buf, 3, st) == BAD_DTYPE
+    assert pf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, hn, odd, buf, 1, st) == INVALID
+    assert pf(h, good4, 0, 4, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, hn, good4, buf, 1, st) == RANK_RANGE
+    assert pf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(0), *ok_h, None, hn, good4, buf, 1, st) == INVALID
+    raw.fsdp_layout_destroy(hn)
     raw.fsdp_layout_destroy(h)
     # W > 64 needs the gradient shard buffer to carry partial sums
     rc, h2 = _init(raw, [(1000,)], 65)

@@ -323,3 +323,46 @@ def test_hip_graph_replay_matches_eager(F):
         torch.cuda.synchronize()
         for a, b in zip(eager, (flat, gs, shards[0], m, v)):
             assert same_bits(np_bits(a), np_bits(b))
+
+
+@pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("W,W_next,out_dt", [(8, 8, torch.bfloat16), (3, 12, torch.bfloat16), (12, 1, torch.bfloat16),
+                                             (70, 8, torch.bfloat16), (8, 100, torch.bfloat16),
+                                             (8, 8, torch.float32)])
+def test_prefetch_launch_equals_separate_calls(F, gdt, W, W_next, out_dt):
+    """Reduce-scatter + Adam of one unit and the unshard of another in one
+    launch (backward prefetching) must give exactly what the separate entry
+    points give, and match the oracle; W > 64 or an fp32 unshard fall back to
+    two launches with the same results."""
+    unit_a = big_unit() if W <= 12 else workloads.ragged_unit()
+    unit_b = workloads.Unit("next", ((1023, 65), (7,), (30001,), (3, 3)))
+    la = F.fsdp_layout_init(unit_a.shapes, W)
+    lb = F.fsdp_layout_init(unit_b.shapes, W_next)
+    pre, post = F.fsdp_default_divide_factors(W)
+    grads = make_grads(W, la.padded, la.numel, gdt, 500 + W)
+    r = W // 2
+    t = 4
+    p, _, m, v = _adam_state(la.shard, t, 23, (0, 0, 1, 2))
+    p2, m2, v2 = p.clone(), m.clone(), v.clone()
+    params_b = make_params(unit_b, 77, misalign=True)
+    shards_b, _ = alloc_shards(W_next, lb.shard, "contig_odd")
+    F.fsdp_flatten_shard(lb, params_b, shards_b)
+    poison = POISON16 if out_dt == torch.bfloat16 else POISON32
+    flat1 = carve(lb.padded, out_dt, 1, fill=poison)
+    flat2 = carve(lb.padded, out_dt, 1, fill=poison)
+    gs1 = carve(la.shard, torch.float32, 0, fill=POISON32)
+    gs2 = carve(la.shard, torch.float32, 0, fill=POISON32)
+    # separate calls
+    F.fsdp_reduce_scatter_adam_fused(la, grads, r, pre, post, gs1, p, m, v, t, LR, B1, B2, EPS, None)
+    F.fsdp_unshard(lb, shards_b, flat1)
+    # one launch
+    F.fsdp_reduce_scatter_adam_prefetch_unshard(la, grads, r, pre, post, gs2, p2, m2, v2, t, LR, B1, B2, EPS, None,
+                                                lb, shards_b, flat2)
+    torch.cuda.synchronize()
+    for a, b, name in ((p, p2, "p"), (m, m2, "m"), (v, v2, "v"), (gs1, gs2, "g"), (flat1, flat2, "flat")):
+        assert same_bits(np_bits(a), np_bits(b)), f"{name}: {first_diff(np_bits(a), np_bits(b))}"
+    ref_g = oracle.reduce_scatter([np_grad(g) for g in grads], r, pre, post)
+    assert same_bits(np_bits(gs2), ref_g.view(np.uint32))
+    h_sh = [np_f32(x) for x in shards_b]
+    ref_flat = oracle.unshard_bf16(h_sh) if out_dt == torch.bfloat16 else oracle.unshard_f32(h_sh).view(np.uint32)
+    assert same_bits(np_bits(flat2), ref_flat)
