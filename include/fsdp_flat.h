@@ -146,7 +146,9 @@ int fsdp_reduce_scatter_adam_fused(const fsdp_layout_t* layout, const void* cons
  * one half overlaps the ramp of the other with no cross-queue synchronisation.
  * Results are bit-identical to calling fsdp_reduce_scatter_adam_fused and
  * fsdp_unshard one after the other, which is also what happens (two launches)
- * when either W exceeds FSDP_MAX_RANKS_PER_LAUNCH or next_out_dtype is FSDP_F32. */
+ * when either W exceeds FSDP_MAX_RANKS_PER_LAUNCH, when next_out_dtype is
+ * FSDP_F32, or when both halves move more than 128 MiB (sharing a grid only
+ * pays while the fixed cost of a launch is visible next to the smaller half). */
 int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* layout, const void* const* grad_ptrs,
                                               fsdp_dtype_t grad_dtype, int32_t rank, float pre_div,
                                               float post_div, float* grad_shard_out, float* p_shard,

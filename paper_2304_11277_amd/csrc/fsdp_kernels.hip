@@ -25,6 +25,8 @@ constexpr int kMaxRanks = FSDP_MAX_RANKS_PER_LAUNCH;  // rank pointers per kerna
 constexpr int kMaxSegs = 24;                          // parameter segments per pack launch
 // launch shapes of the reduce kernels (measured on MI355X)
 constexpr int kReduceBlock = 256;
+// the prefetch entry point shares one grid only while its smaller half moves at most this many bytes
+constexpr int64_t kOneLaunchMaxBytes = 128ll << 20;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -295,16 +297,17 @@ __device__ __forceinline__ float post_scale(float x, const RsArgs& a)
     return a.post_mul ? x * a.post_c : x / a.post_c;
 }
 
-// Loads one 16-byte vector from each of N consecutive ranks (all N loads are
-// issued before the first use), then adds the N terms to acc strictly in rank
-// order.  E = 4 elements per vector for fp32 gradients, 8 for bf16.
-template <bool BF16, int PRE, int N, int E>
-__device__ __forceinline__ void accumulate_ranks(const PtrTable& grads, int32_t w0, int64_t k, float pre_c,
-                                                 float (&acc)[E])
+// Rank groups: kGroup ranks are loaded together (one 16-byte vector each, all
+// loads issued back to back), then added strictly in rank order.  The host pads
+// the pointer table up to a multiple of kGroup with copies of the last rank's
+// pointer, so the loads need no predicate; the adds of the padding are skipped.
+constexpr int kGroup = 8;
+
+template <bool BF16>
+__device__ __forceinline__ void load_ranks(const PtrTable& grads, int32_t w0, int64_t k, u32x4 (&x)[kGroup])
 {
-    u32x4 x[N];
 #pragma unroll
-    for (int j = 0; j < N; ++j) {
+    for (int j = 0; j < kGroup; ++j) {
         if constexpr (BF16)
             x[j] = __builtin_nontemporal_load(
                 reinterpret_cast<const u32x4_a2*>(static_cast<const uint16_t*>(grads.p[w0 + j]) + k));
@@ -312,19 +315,27 @@ __device__ __forceinline__ void accumulate_ranks(const PtrTable& grads, int32_t 
             x[j] = __builtin_nontemporal_load(
                 reinterpret_cast<const u32x4_a4*>(static_cast<const float*>(grads.p[w0 + j]) + k));
     }
+}
+
+// acc += x[0..n) in order; E = 4 elements per vector for fp32 gradients, 8 for bf16
+template <bool BF16, int PRE, int E>
+__device__ __forceinline__ void add_ranks(const u32x4 (&x)[kGroup], int32_t n, float pre_c, float (&acc)[E])
+{
 #pragma unroll
-    for (int j = 0; j < N; ++j) {
-        float t[E];
-        if constexpr (BF16) {   // exact upcast: the bf16 pattern is the top half of the fp32 one
-            t[0] = u2f(x[j].x << 16); t[1] = u2f(x[j].x & 0xFFFF0000u);
-            t[2] = u2f(x[j].y << 16); t[3] = u2f(x[j].y & 0xFFFF0000u);
-            t[4] = u2f(x[j].z << 16); t[5] = u2f(x[j].z & 0xFFFF0000u);
-            t[6] = u2f(x[j].w << 16); t[7] = u2f(x[j].w & 0xFFFF0000u);
-        } else {
-            t[0] = u2f(x[j].x); t[1] = u2f(x[j].y); t[2] = u2f(x[j].z); t[3] = u2f(x[j].w);
+    for (int j = 0; j < kGroup; ++j) {
+        if (j < n) {   // uniform
+            float t[E];
+            if constexpr (BF16) {   // exact upcast: the bf16 pattern is the top half of the fp32 one
+                t[0] = u2f(x[j].x << 16); t[1] = u2f(x[j].x & 0xFFFF0000u);
+                t[2] = u2f(x[j].y << 16); t[3] = u2f(x[j].y & 0xFFFF0000u);
+                t[4] = u2f(x[j].z << 16); t[5] = u2f(x[j].z & 0xFFFF0000u);
+                t[6] = u2f(x[j].w << 16); t[7] = u2f(x[j].w & 0xFFFF0000u);
+            } else {
+                t[0] = u2f(x[j].x); t[1] = u2f(x[j].y); t[2] = u2f(x[j].z); t[3] = u2f(x[j].w);
+            }
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[e] = acc[e] + pre_scale<PRE>(t[e], pre_c);
         }
-#pragma unroll
-        for (int e = 0; e < E; ++e) acc[e] = acc[e] + pre_scale<PRE>(t[e], pre_c);
     }
 }
 
@@ -332,11 +343,12 @@ __device__ __forceinline__ void accumulate_ranks(const PtrTable& grads, int32_t 
 // rank).  The accumulator starts at -0.0f, the identity of IEEE addition
 // ((-0) + x == x bit for bit, signed zeros included), which is the same as
 // initialising it from rank 0's term; a later launch of a split W starts from
-// the carried partial sum instead.  Ranks are walked in groups of 8, 4, 2, 1.
+// the carried partial sum instead.  Ranks are walked in groups of eight, two
+// groups in flight.
 // In the fused form the chunk's Adam state is fetched before the rank loop so
 // that the lane pays one memory latency, not two.  Everything a live lane does
 // sits under one branch, so the loads of a group issue back to back.
-template <bool BF16, int PRE, bool FUSED, int B>
+template <bool BF16, int PRE, bool FUSED, bool PIPE, int B>
 __device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs& a, uint32_t bid)
 {
     constexpr int E = BF16 ? 8 : 4;
@@ -372,11 +384,25 @@ __device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs&
             for (int e = 0; e < E; ++e) acc[e] = -0.0f;
         }
 
-        int32_t w = 0;
-        for (; w + 8 <= W; w += 8) accumulate_ranks<BF16, PRE, 8, E>(grads, w, k, a.pre_c, acc);
-        if (W & 4) { accumulate_ranks<BF16, PRE, 4, E>(grads, w, k, a.pre_c, acc); w += 4; }
-        if (W & 2) { accumulate_ranks<BF16, PRE, 2, E>(grads, w, k, a.pre_c, acc); w += 2; }
-        if (W & 1) { accumulate_ranks<BF16, PRE, 1, E>(grads, w, k, a.pre_c, acc); }
+        if constexpr (PIPE) {
+            // W > kGroup: two groups in flight, the next group's loads are issued
+            // before the current group's adds wait for their data
+            u32x4 xa[kGroup], xb[kGroup];
+            const int32_t ngroups = (W + kGroup - 1) / kGroup;
+            load_ranks<BF16>(grads, 0, k, xa);
+            for (int32_t g = 0; g < ngroups; g += 2) {
+                const bool has_b = g + 1 < ngroups;
+                if (has_b) load_ranks<BF16>(grads, (g + 1) * kGroup, k, xb);
+                add_ranks<BF16, PRE, E>(xa, W - g * kGroup, a.pre_c, acc);
+                if (g + 2 < ngroups) load_ranks<BF16>(grads, (g + 2) * kGroup, k, xa);
+                if (has_b) add_ranks<BF16, PRE, E>(xb, W - (g + 1) * kGroup, a.pre_c, acc);
+            }
+        } else {
+            // W <= kGroup: one group, fewer registers
+            u32x4 xa[kGroup];
+            load_ranks<BF16>(grads, 0, k, xa);
+            add_ranks<BF16, PRE, E>(xa, W, a.pre_c, acc);
+        }
 
         if (a.last) {
 #pragma unroll
@@ -433,10 +459,10 @@ __device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs&
     }
 }
 
-template <bool BF16, int PRE, bool FUSED, int B>
+template <bool BF16, int PRE, bool FUSED, bool PIPE, int B>
 __global__ __launch_bounds__(B) void reduce_kernel(PtrTable grads, RsArgs a)
 {
-    reduce_body<BF16, PRE, FUSED, B>(grads, a, blockIdx.x);
+    reduce_body<BF16, PRE, FUSED, PIPE, B>(grads, a, blockIdx.x);
 }
 
 // Backward prefetching (Sec. 3.3.2) as one launch: the first n_reduce
@@ -444,14 +470,14 @@ __global__ __launch_bounds__(B) void reduce_kernel(PtrTable grads, RsArgs a)
 // unshard of another unit.  The two do not depend on each other, so sharing a
 // grid lets the drain of one overlap the ramp of the other without any
 // cross-queue synchronisation.
-template <bool BF16, int PRE>
+template <bool BF16, int PRE, bool PIPE>
 __global__ __launch_bounds__(kBlock) void reduce_adam_unshard_kernel(PtrTable grads, RsArgs a, uint32_t n_reduce,
                                                                       PtrTable shards, int64_t S_next,
                                                                       uint16_t* __restrict__ out_base,
                                                                       int32_t tiles_per_shard)
 {
     if (blockIdx.x < n_reduce)
-        reduce_body<BF16, PRE, true, kBlock>(grads, a, blockIdx.x);
+        reduce_body<BF16, PRE, true, PIPE, kBlock>(grads, a, blockIdx.x);
     else
         unshard_bf16_body(shards, S_next, out_base, tiles_per_shard, blockIdx.x - n_reduce);
 }
@@ -548,14 +574,25 @@ AdamConsts make_adam_consts(int64_t step, float lr, float b1, float b2, float ep
     return c;
 }
 
+// the reduce kernel loads whole groups of kGroup ranks: repeat the last pointer up to the group boundary
+void pad_rank_table(PtrTable& tab, int32_t n)
+{
+    static_assert(kMaxRanks % kGroup == 0, "the padded table must fit");
+    for (int32_t j = n; j % kGroup != 0; ++j) tab.p[j] = tab.p[n - 1];
+}
+
 template <bool BF16, int PRE, bool FUSED>
 void launch_reduce(const PtrTable& tab, const RsArgs& a, hipStream_t st)
 {
     constexpr int E = BF16 ? 8 : 4;
     constexpr int B = kReduceBlock;
     const int64_t blocks = ceil_div(a.S / E + 1, B);
-    hipLaunchKernelGGL((reduce_kernel<BF16, PRE, FUSED, B>), dim3(static_cast<uint32_t>(blocks)), dim3(B), 0, st,
-                       tab, a);
+    if (a.W > kGroup)
+        hipLaunchKernelGGL((reduce_kernel<BF16, PRE, FUSED, true, B>), dim3(static_cast<uint32_t>(blocks)), dim3(B), 0,
+                           st, tab, a);
+    else
+        hipLaunchKernelGGL((reduce_kernel<BF16, PRE, FUSED, false, B>), dim3(static_cast<uint32_t>(blocks)), dim3(B),
+                           0, st, tab, a);
 }
 
 template <bool BF16, bool FUSED>
@@ -591,6 +628,7 @@ int reduce_driver(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dty
         PtrTable tab = {};
         for (int32_t j = 0; j < nw; ++j)
             tab.p[j] = static_cast<const char*>(grad_ptrs[w0 + j]) + static_cast<int64_t>(rank) * S * esz;
+        pad_rank_table(tab, nw);
         RsArgs a = {};
         a.W = nw;
         a.cont = w0 > 0;
@@ -819,7 +857,13 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* L, const void
     const int64_t n_reduce = ceil_div(L->S / E + 1, kBlock);
     const int64_t tiles = ceil_div(N->S / 8 + 1, kBlock);
     const int64_t n_unshard = tiles * N->world_size;
-    const bool one_launch = L->world_size <= kMaxRanks && N->world_size <= kMaxRanks &&
+    // Sharing a grid pays while the fixed cost of a launch (about 2 us of ramp
+    // and drain) is visible next to the smaller half; for large halves the
+    // shared kernel's register budget costs the unshard more than it saves.
+    const int64_t reduce_bytes = (grad_dtype == FSDP_BF16 ? 2 : 4) * L->P + 24 * L->S;
+    const int64_t unshard_bytes = 6 * N->P;
+    const bool small_half = (reduce_bytes < unshard_bytes ? reduce_bytes : unshard_bytes) <= kOneLaunchMaxBytes;
+    const bool one_launch = small_half && L->world_size <= kMaxRanks && N->world_size <= kMaxRanks &&
                             next_out_dtype == FSDP_BF16 && grid_ok(n_reduce + n_unshard);
     if (!one_launch) {   // same results from the two separate entry points, one after the other
         rc = fsdp_reduce_scatter_adam_fused(L, grad_ptrs, grad_dtype, rank, pre_div, post_div, grad_shard_out, p_shard,
@@ -832,6 +876,7 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* L, const void
     PtrTable gtab = {}, stab = {};
     for (int32_t w = 0; w < L->world_size; ++w)
         gtab.p[w] = static_cast<const char*>(grad_ptrs[w]) + static_cast<int64_t>(rank) * L->S * esz;
+    pad_rank_table(gtab, L->world_size);
     for (int32_t w = 0; w < N->world_size; ++w) stab.p[w] = next_shard_ptrs[w];
     RsArgs a = {};
     int pre_mode = kPreDiv;
@@ -853,9 +898,15 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* L, const void
     const uint32_t nr = static_cast<uint32_t>(n_reduce);
     uint16_t* out_base = static_cast<uint16_t*>(next_flat_out);
     const int32_t tl = static_cast<int32_t>(tiles);
-#define FSDP_LAUNCH_COMBINED(BF, PRE) \
-    hipLaunchKernelGGL((reduce_adam_unshard_kernel<BF, PRE>), grid, dim3(kBlock), 0, st, gtab, a, nr, stab, N->S, \
-                       out_base, tl)
+#define FSDP_LAUNCH_COMBINED(BF, PRE)                                                                              \
+    do {                                                                                                           \
+        if (a.W > kGroup)                                                                                          \
+            hipLaunchKernelGGL((reduce_adam_unshard_kernel<BF, PRE, true>), grid, dim3(kBlock), 0, st, gtab, a, nr, \
+                               stab, N->S, out_base, tl);                                                          \
+        else                                                                                                       \
+            hipLaunchKernelGGL((reduce_adam_unshard_kernel<BF, PRE, false>), grid, dim3(kBlock), 0, st, gtab, a,    \
+                               nr, stab, N->S, out_base, tl);                                                      \
+    } while (0)
     if (grad_dtype == FSDP_BF16) {
         if (pre_mode == kPreNone) FSDP_LAUNCH_COMBINED(true, kPreNone);
         else if (pre_mode == kPreMul) FSDP_LAUNCH_COMBINED(true, kPreMul);
