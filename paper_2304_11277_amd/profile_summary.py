@@ -17,7 +17,8 @@ import csv
 import json
 import sys
 
-LIB_KERNELS = (("unshard", "unshard"), ("reduce_kernel", "reduce_adam"), ("adam_kernel", "adam"),
+LIB_KERNELS = (("reduce_adam_unshard_kernel", "reduce_adam+unshard"), ("unshard", "unshard"),
+               ("reduce_kernel", "reduce_adam"), ("adam_kernel", "adam"),
                ("pack_kernel", "pack"), ("fsdp_probe_copy", "probe_copy"))
 
 
