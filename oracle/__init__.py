@@ -212,6 +212,33 @@ def reduce_full_f32(gradbufs: Sequence[np.ndarray], pre: float, post: float) -> 
     return out
 
 
+def reduce_slices_hybrid(slices: Sequence[np.ndarray], G: int, F: int, pre: float, post: float) -> np.ndarray:
+    """Two-level reduction of Sec. 3.2.2: slices[i*F + l] = slice of local rank
+    l in sharded group i; inner sums per group, outer sum over the groups."""
+    sl = [np.ascontiguousarray(s) for s in slices]
+    assert len(sl) == G * F
+    S = sl[0].size
+    assert all(s.size == S for s in sl)
+    out = np.empty(S, dtype=np.float32)
+    fn = lib().orc_reduce_slices_hybrid_bf16 if _is_bf16(sl) else lib().orc_reduce_slices_hybrid_f32
+    fn(_ptr_array(sl), _c_i32(G), _c_i32(F), _c_i64(S), _c_f32(pre), _c_f32(post), _vp(_ptr(out)))
+    return out
+
+
+def accumulate(acc: np.ndarray, add: np.ndarray) -> np.ndarray:
+    """Gradient accumulation (Sec. 3.3.4): returns acc + add in binary32;
+    add may be float32 or bf16 bit patterns (uint16)."""
+    acc = _f32(acc).copy()
+    add = np.ascontiguousarray(add)
+    assert add.size == acc.size
+    if add.dtype == np.uint16:
+        lib().orc_accumulate_bf16(_vp(_ptr(acc)), _vp(_ptr(add)), _c_i64(acc.size))
+    else:
+        assert add.dtype == np.float32
+        lib().orc_accumulate_f32(_vp(_ptr(acc)), _vp(_ptr(add)), _c_i64(acc.size))
+    return acc
+
+
 # ------------------------------------------------------------------ Adam
 
 def adam_f32(p, g, m, v, t: int, lr: float, beta1: float, beta2: float, eps: float):

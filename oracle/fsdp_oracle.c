@@ -205,6 +205,75 @@ void orc_reduce_full_f32(const float *const *gradbufs, int32_t W, int64_t P,
     orc_reduce_slices_f32(gradbufs, W, P, pre, post, full);
 }
 
+/* ------------------------------------------------------ hybrid sharding */
+
+/* Sec. 3.2.2: with sharding factor F < W the W ranks form G = W / F sharded
+ * groups S_1..S_G; gradients are reduce-scattered inside each sharded group and
+ * the sharded results are then all-reduced across the groups (the replicate
+ * group of this rank's position).  Eq. (1): sum_r g_r = sum_i sum_{r in S_i} g_r.
+ * In real arithmetic the two agree; in binary32 the two-level order is its own
+ * result, fixed here as: inner sums over the F ranks of a group in local-rank
+ * order (terms divided by pre first, accumulator started from the group's
+ * first term), outer sum over the groups in group order (accumulator started
+ * from group 0's inner sum), then one division by post; pre * post = W.
+ * slices[i*F + l] points at this rank position's slice (S elements) of the
+ * gradient buffer of local rank l in group i.
+ * Pins: integer gradients (exact, equals the flat sum), exact-rational model,
+ * a witness where the two-level and the flat order differ, G = 1 equals the
+ * flat reduce-scatter bit for bit. */
+void orc_reduce_slices_hybrid_f32(const float *const *slices, int32_t G, int32_t F, int64_t S,
+                                  float pre, float post, float *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < S; ++k) {
+        float outer = 0.0f;
+        for (int32_t i = 0; i < G; ++i) {
+            float inner = slices[(int64_t)i * F][k] / pre;
+            for (int32_t l = 1; l < F; ++l) inner = inner + slices[(int64_t)i * F + l][k] / pre;
+            outer = (i == 0) ? inner : outer + inner;
+        }
+        out[k] = outer / post;
+    }
+}
+
+void orc_reduce_slices_hybrid_bf16(const uint16_t *const *slices, int32_t G, int32_t F, int64_t S,
+                                   float pre, float post, float *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < S; ++k) {
+        float outer = 0.0f;
+        for (int32_t i = 0; i < G; ++i) {
+            float inner = bf16_to_f32(slices[(int64_t)i * F][k]) / pre;
+            for (int32_t l = 1; l < F; ++l) inner = inner + bf16_to_f32(slices[(int64_t)i * F + l][k]) / pre;
+            outer = (i == 0) ? inner : outer + inner;
+        }
+        out[k] = outer / post;
+    }
+}
+
+/* ------------------------------------------------ gradient accumulation */
+
+/* Sec. 3.3.4.  With communication: every micro-batch is reduce-scattered and
+ * the rank keeps adding the sharded result to its sharded gradient
+ * (acc[k] = acc[k] + new[k], S elements).  Without communication: the rank
+ * adds its own unsharded gradients locally (same operation on P elements) and
+ * reduce-scatters once at the end.  One binary32 addition per element, the
+ * running sum on the left.
+ * Pins: numpy's float32 addition (a library routine), integer exactness, and
+ * the two variations agreeing exactly on integer-valued gradients. */
+void orc_accumulate_f32(float *acc, const float *add, int64_t n)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < n; ++k) acc[k] = acc[k] + add[k];
+}
+
+/* bf16 micro-batch gradients accumulated into a binary32 buffer (exact upcast). */
+void orc_accumulate_bf16(float *acc, const uint16_t *add, int64_t n)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < n; ++k) acc[k] = acc[k] + bf16_to_f32(add[k]);
+}
+
 /* ------------------------------------------------------------------ Adam */
 
 /* Sec. 5.4 names Adam with its two optimizer states per parameter, kept

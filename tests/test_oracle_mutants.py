@@ -10,6 +10,7 @@ import pytest
 import oracle
 import test_oracle_adam as t_adam
 import test_oracle_cast as t_cast
+import test_oracle_hybrid_accum as t_hyb
 import test_oracle_layout as t_layout
 import test_oracle_reduce as t_reduce
 
@@ -36,6 +37,14 @@ MUTANTS = [
      "float acc = slices[0][k];\n        for (int32_t w = 1; w < W; ++w) acc = acc + slices[w][k];\n        out[k] = acc / pre / post;"),
     ("scatter_wrong_slice", "sl[w] = gradbufs[w] + (int64_t)r * S;", "sl[w] = gradbufs[w] + (int64_t)(r ? r - 1 : 0) * S;"),
     ("bf16_upcast_shift", "(uint32_t)h << 16", "(uint32_t)h << 15"),
+    ("hybrid_drops_groups", "outer = (i == 0) ? inner : outer + inner;", "outer = inner;"),
+    ("hybrid_rank_major_layout", "inner = inner + slices[(int64_t)i * F + l][k] / pre;",
+     "inner = inner + slices[(int64_t)l * G + i][k] / pre;"),
+    ("hybrid_flat_order", "outer = (i == 0) ? inner : outer + inner;\n        }\n        out[k] = outer / post;",
+     "outer = inner;\n        }\n        { float a_ = slices[0][k] / pre; for (int32_t w = 1; w < G * F; ++w) a_ = a_ + slices[w][k] / pre; outer = a_; }\n        out[k] = outer / post;"),
+    ("hybrid_post_per_group", "outer = (i == 0) ? inner : outer + inner;", "outer = (i == 0) ? inner / post : outer + inner / post;"),
+    ("accumulate_overwrites", "acc[k] = acc[k] + add[k];", "acc[k] = add[k];"),
+    ("accumulate_bf16_shift", "acc[k] = acc[k] + bf16_to_f32(add[k]);", "acc[k] = acc[k] + (float)add[k];"),
     ("adam_eps_inside_sqrt", "sqrtf(vk) / sqrt_bc2 + eps;", "sqrtf(vk + eps) / sqrt_bc2;"),
     ("adam_no_bias_correction2", "float sqrt_bc2 = sqrtf(bc2);", "float sqrt_bc2 = 1.0f;"),
     ("adam_no_bias_correction1", "float step_size = lr / bc1;", "float step_size = lr;"),
@@ -67,6 +76,13 @@ def _pins():
         t_reduce.test_integer_gradients_give_exact_mean,
         t_reduce.test_pre_and_post_are_true_divisions,
         t_reduce.test_bf16_inputs_upcast_exactly,
+        lambda: t_hyb.test_two_level_order_matches_exact_model(3, 4, 4.0, 3.0),
+        lambda: t_hyb.test_two_level_order_matches_exact_model(2, 3, 1.0, 6.0),
+        t_hyb.test_eq1_decomposition_is_exact_on_integers,
+        t_hyb.test_two_level_order_differs_from_flat_order_in_binary32,
+        t_hyb.test_hybrid_bf16_upcast_exact,
+        t_hyb.test_accumulate_is_float32_addition,
+        t_hyb.test_accumulation_with_and_without_communication_agree_on_integers,
         t_adam.test_closed_form_first_step_from_zero_state,
         lambda: t_adam.test_single_step_matches_torch_adam_float64(5),
         t_adam.test_checkpoint_resume,
