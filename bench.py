@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
                     help="run only N launches of a plain 256 MiB copy kernel (calibrates rocprofv3 --pmc byte counters)")
+    ap.add_argument("--next-rows", action="store_true",
+                    help="measure the kernels beyond the hot path (hybrid-sharding reduce, gradient accumulation) "
+                         "on the workload's largest unit and print their own JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
@@ -109,6 +112,9 @@ def main():
         probe_copy(args.probe_copy, torch, fbuild)
         return
     wl = workloads.config(args.config)
+    if args.next_rows:
+        next_rows(args, wl, F, torch, workloads)
+        return
     units = list(wl.units)
     if args.max_units:
         units = units[:args.max_units]
@@ -273,6 +279,52 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu, "kernels": per_kernel,
     }
     print(json.dumps(out), flush=True)
+
+
+def next_rows(args, wl, F, torch, workloads):
+    """Hybrid-sharding reduction (Sec. 3.2.2) and gradient accumulation
+    (Sec. 3.3.4) on the largest unit of the workload: one kernel each, timed
+    back to back over rotating buffer sets between one pair of HIP events."""
+    unit = max(wl.units, key=lambda u: sum(workloads.numel(s) for s in u.shapes))
+    W = wl.world_size
+    gdt = torch.float32 if wl.grad_dtype == "f32" else torch.bfloat16
+    gb = 4 if wl.grad_dtype == "f32" else 2
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S, P, N = lay.shard, lay.padded, lay.numel
+    G = 2 if 2 * W <= 64 else 1
+    nsets = max(1, min(3, int(100e9 // (W * G * P * gb + 4 * P))))   # rotate buffer sets while HBM allows
+    pre, post = F.fsdp_default_divide_factors(W * G)
+    sets = []
+    for i in range(nsets):
+        grads = [workloads.gen_rank_grad(P, N, w, i, wl.grad_dtype, device="cuda") for w in range(W * G)]
+        sets.append({"grads": F.PtrArray(grads), "flat": F.PtrArray(grads[:W]),
+                     "out": torch.zeros(S, device="cuda"), "acc": torch.zeros(P, device="cuda")})
+    rows = {
+        "reduce_scatter_hybrid": (lambda d: F.fsdp_reduce_scatter_hybrid(lay, d["grads"], G, 0, pre, post, d["out"]),
+                                  gb * S * W * G + 4 * S),
+        "reduce_scatter_accumulate": (lambda d: F.fsdp_reduce_scatter_accumulate(lay, d["flat"], 0, pre, post, d["out"]),
+                                      gb * P + 8 * S),
+        "grad_accumulate": (lambda d: F.fsdp_grad_accumulate(lay, d["acc"], d["flat"].tensors[0]), (8 + gb) * P),
+    }
+    out = {}
+    reps = 30
+    for name, (fn, nbytes) in rows.items():
+        for d in sets:
+            fn(d)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(reps):
+            fn(sets[i % nsets])
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / reps
+        out[name] = {"avg_us": round(us, 2), "alg_bytes": nbytes, "GBps": round(nbytes / us / 1e3, 1),
+                     "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)}
+        log(f"[bench] {name}: {us:.2f} us, {nbytes / us / 1e3:.1f} GB/s")
+    print(json.dumps({"metric": "effective HBM GB/s of the rows beyond the hot path", "unit": "GB/s",
+                      "config": {"workload": wl.name, "unit": unit.name, "world_size": W, "hybrid_groups": G,
+                                 "grad_dtype": wl.grad_dtype}, "rows": out}), flush=True)
 
 
 def probe_copy(n, torch, fbuild):

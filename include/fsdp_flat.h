@@ -158,6 +158,36 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* layout, const
                                               const float* const* next_shard_ptrs, void* next_flat_out,
                                               fsdp_dtype_t next_out_dtype, void* hip_stream);
 
+/* ---- Sec. 3.2.2 hybrid sharding: reduce-scatter inside each sharded group,
+ * then all-reduce of the shards across the groups -- this rank's result --------
+ * layout was built with world_size = F, the sharding factor; the world has
+ * num_groups * F ranks.  grad_ptrs: host [num_groups * F], group-major
+ * (grad_ptrs[i * F + l] = local rank l of sharded group i), P elements each;
+ * rank = this rank's position l in its sharded group.
+ * inner_i = (x_{i,0} / pre) + ... + (x_{i,F-1} / pre) in local-rank order,
+ * out[k] = (inner_0 + inner_1 + ... ) / post in group order (eq. (1): the sum
+ * over all ranks as a sum over groups of group sums; in binary32 this two-level
+ * order is its own result).  num_groups = 1 equals fsdp_reduce_scatter_local bit
+ * for bit.  Requires num_groups * F <= FSDP_MAX_RANKS_PER_LAUNCH. */
+int fsdp_reduce_scatter_hybrid(const fsdp_layout_t* layout, const void* const* grad_ptrs,
+                               fsdp_dtype_t grad_dtype, int32_t num_groups, int32_t rank,
+                               float pre_div, float post_div, float* grad_shard_out, void* hip_stream);
+
+/* ---- Sec. 3.3.4 gradient accumulation --------------------------------------
+ * With communication: every micro-batch is reduce-scattered and added to the
+ * sharded gradient the rank keeps: grad_shard_acc[k] = grad_shard_acc[k] +
+ * reduce_scatter(...)[k] (arguments as fsdp_reduce_scatter_local; the buffer is
+ * read and written).  Requires W <= FSDP_MAX_RANKS_PER_LAUNCH. */
+int fsdp_reduce_scatter_accumulate(const fsdp_layout_t* layout, const void* const* grad_ptrs,
+                                   fsdp_dtype_t grad_dtype, int32_t rank, float pre_div,
+                                   float post_div, float* grad_shard_acc, void* hip_stream);
+/* Without communication: the rank adds a micro-batch's unsharded gradient to
+ * its own unsharded fp32 accumulator, grad_acc[k] = grad_acc[k] + grad_add[k]
+ * for the P elements of the flat gradient (grad_add: fp32 or bf16), and
+ * reduce-scatters once after the last micro-batch. */
+int fsdp_grad_accumulate(const fsdp_layout_t* layout, float* grad_acc, const void* grad_add,
+                         fsdp_dtype_t add_dtype, void* hip_stream);
+
 /* Last hipError_t seen by this thread inside the library (0 if none). */
 int fsdp_last_hip_error(void);
 /* Static string for a fsdp_status_t. */

@@ -15,6 +15,9 @@ from .binding import (  # noqa: F401
     fsdp_layout_init,
     fsdp_reduce_scatter_adam_fused,
     fsdp_reduce_scatter_adam_prefetch_unshard,
+    fsdp_grad_accumulate,
+    fsdp_reduce_scatter_accumulate,
+    fsdp_reduce_scatter_hybrid,
     fsdp_reduce_scatter_local,
     fsdp_shard_adam_step,
     fsdp_unshard,

@@ -61,6 +61,9 @@ _SIGNATURES = {
                                        _f32, _f32, _f32, _f32, _vp, _vp],
     "fsdp_reduce_scatter_adam_prefetch_unshard": [_vp, _pp, ctypes.c_int, _i32, _f32, _f32, _vp, _vp, _vp, _vp, _i64,
                                                   _f32, _f32, _f32, _f32, _vp, _vp, _pp, _vp, ctypes.c_int, _vp],
+    "fsdp_reduce_scatter_hybrid": [_vp, _pp, ctypes.c_int, _i32, _i32, _f32, _f32, _vp, _vp],
+    "fsdp_reduce_scatter_accumulate": [_vp, _pp, ctypes.c_int, _i32, _f32, _f32, _vp, _vp],
+    "fsdp_grad_accumulate": [_vp, _vp, _vp, ctypes.c_int, _vp],
     "fsdp_last_hip_error": [],
 }
 
@@ -237,7 +240,7 @@ def fsdp_unshard(layout: Layout, shard_ptrs, flat_out: torch.Tensor, stream=None
                                               _stream_handle(stream)))
 
 
-def _grad_table(layout: Layout, grad_ptrs) -> Tuple[PtrArray, int]:
+def _grad_table(layout: Layout, grad_ptrs, num_groups: int = 1) -> Tuple[PtrArray, int]:
     if isinstance(grad_ptrs, PtrArray):
         gdt = grad_ptrs.tensors[0].dtype
     else:
@@ -245,7 +248,7 @@ def _grad_table(layout: Layout, grad_ptrs) -> Tuple[PtrArray, int]:
         gdt = grad_ptrs[0].dtype
     if gdt not in (torch.float32, torch.bfloat16):
         raise TypeError(f"grad dtype {gdt} not supported")
-    tab = _ptr_table(grad_ptrs, gdt, layout.padded, layout.world_size, "grad_ptrs")
+    tab = _ptr_table(grad_ptrs, gdt, layout.padded, layout.world_size * num_groups, "grad_ptrs")
     return tab, (FSDP_F32 if gdt == torch.float32 else FSDP_BF16)
 
 
@@ -304,3 +307,31 @@ def fsdp_reduce_scatter_adam_prefetch_unshard(layout: Layout, grad_ptrs, rank: i
                layout.handle, tab.array, gdt, int(rank), float(pre_div), float(post_div), _vp(g_out),
                *[_vp(x) for x in ptrs], int(step), float(lr), float(beta1), float(beta2), float(eps), _vp(lp),
                next_layout.handle, shards.array, _vp(next_flat_out.data_ptr()), dt, _stream_handle(stream)))
+
+
+def fsdp_reduce_scatter_hybrid(layout: Layout, grad_ptrs, num_groups: int, rank: int, pre_div: float,
+                               post_div: float, grad_shard_out: torch.Tensor, stream=None) -> None:
+    tab, gdt = _grad_table(layout, grad_ptrs, num_groups)
+    _dev_tensor(grad_shard_out, torch.float32, layout.shard, "grad_shard_out")
+    _check("fsdp_reduce_scatter_hybrid",
+           lib().fsdp_reduce_scatter_hybrid(layout.handle, tab.array, gdt, int(num_groups), int(rank), float(pre_div),
+                                            float(post_div), _vp(grad_shard_out.data_ptr()), _stream_handle(stream)))
+
+
+def fsdp_reduce_scatter_accumulate(layout: Layout, grad_ptrs, rank: int, pre_div: float, post_div: float,
+                                   grad_shard_acc: torch.Tensor, stream=None) -> None:
+    tab, gdt = _grad_table(layout, grad_ptrs)
+    _dev_tensor(grad_shard_acc, torch.float32, layout.shard, "grad_shard_acc")
+    _check("fsdp_reduce_scatter_accumulate",
+           lib().fsdp_reduce_scatter_accumulate(layout.handle, tab.array, gdt, int(rank), float(pre_div),
+                                                float(post_div), _vp(grad_shard_acc.data_ptr()),
+                                                _stream_handle(stream)))
+
+
+def fsdp_grad_accumulate(layout: Layout, grad_acc: torch.Tensor, grad_add: torch.Tensor, stream=None) -> None:
+    _dev_tensor(grad_acc, torch.float32, layout.padded, "grad_acc")
+    dt = _flat_dtype(grad_add)
+    _dev_tensor(grad_add, grad_add.dtype, layout.padded, "grad_add")
+    _check("fsdp_grad_accumulate",
+           lib().fsdp_grad_accumulate(layout.handle, _vp(grad_acc.data_ptr()), _vp(grad_add.data_ptr()), dt,
+                                      _stream_handle(stream)))

@@ -281,6 +281,9 @@ struct RsArgs {
     int32_t cont;         // 1: accumulator continues from out[] (a later launch of a split W)
     int32_t last;         // 1: apply the post divide (and Adam) in this launch
     int32_t post_mul;     // 1: post is a power of two, post_c holds its exact reciprocal
+    int32_t group;        // hybrid sharding: ranks per sharded group (inner sums are folded into an
+                          // outer sum after every `group` ranks); 0 = one flat sum
+    int32_t accum;        // 1: gradient accumulation, the result is added to what out[] holds
     float pre_c;          // pre (kPreDiv) or 1/pre (kPreMul)
     float post_c;         // post, or 1/post when post_mul
     int64_t S;
@@ -317,9 +320,33 @@ __device__ __forceinline__ void load_ranks(const PtrTable& grads, int32_t w0, in
     }
 }
 
-// acc += x[0..n) in order; E = 4 elements per vector for fp32 gradients, 8 for bf16
+// Two-level state of the rank walk.  Flat sum: `acc` only.  Hybrid sharding
+// (Sec. 3.2.2): `acc` is the inner sum of the current sharded group; after every
+// `group` ranks it is folded into `outer` and restarted at -0.0f.
+template <int E>
+struct RankSum {
+    float acc[E];
+    float outer[E];
+    int32_t cnt;      // ranks added to the current group (uniform)
+};
+
+template <int E>
+__device__ __forceinline__ void fold_group(RankSum<E>& s, int32_t group)
+{
+    if (group > 0 && ++s.cnt == group) {   // uniform
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            s.outer[e] = s.outer[e] + s.acc[e];
+            s.acc[e] = -0.0f;
+        }
+        s.cnt = 0;
+    }
+}
+
+// adds x[0..n) in rank order; E = 4 elements per vector for fp32 gradients, 8 for bf16
 template <bool BF16, int PRE, int E>
-__device__ __forceinline__ void add_ranks(const u32x4 (&x)[kGroup], int32_t n, float pre_c, float (&acc)[E])
+__device__ __forceinline__ void add_ranks(const u32x4 (&x)[kGroup], int32_t n, float pre_c, int32_t group,
+                                          RankSum<E>& s)
 {
 #pragma unroll
     for (int j = 0; j < kGroup; ++j) {
@@ -334,7 +361,8 @@ __device__ __forceinline__ void add_ranks(const u32x4 (&x)[kGroup], int32_t n, f
                 t[0] = u2f(x[j].x); t[1] = u2f(x[j].y); t[2] = u2f(x[j].z); t[3] = u2f(x[j].w);
             }
 #pragma unroll
-            for (int e = 0; e < E; ++e) acc[e] = acc[e] + pre_scale<PRE>(t[e], pre_c);
+            for (int e = 0; e < E; ++e) s.acc[e] = s.acc[e] + pre_scale<PRE>(t[e], pre_c);
+            fold_group<E>(s, group);
         }
     }
 }
@@ -372,7 +400,14 @@ __device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs&
                 vv[q] = *reinterpret_cast<const f32x4_a4*>(a.v + k + 4 * q);
             }
         }
-        float acc[E];
+        f32x4 old[Q];
+        if (a.accum) {   // gradient accumulation: fetch the running sum early
+#pragma unroll
+            for (int q = 0; q < Q; ++q) old[q] = *reinterpret_cast<const f32x4_a4*>(a.out + k + 4 * q);
+        }
+        RankSum<E> rs;
+        rs.cnt = 0;
+        float (&acc)[E] = rs.acc;
         if (a.cont) {
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
@@ -383,6 +418,8 @@ __device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs&
 #pragma unroll
             for (int e = 0; e < E; ++e) acc[e] = -0.0f;
         }
+#pragma unroll
+        for (int e = 0; e < E; ++e) rs.outer[e] = -0.0f;
 
         if constexpr (PIPE) {
             // W > kGroup: two groups in flight, the next group's loads are issued
@@ -393,20 +430,33 @@ __device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs&
             for (int32_t g = 0; g < ngroups; g += 2) {
                 const bool has_b = g + 1 < ngroups;
                 if (has_b) load_ranks<BF16>(grads, (g + 1) * kGroup, k, xb);
-                add_ranks<BF16, PRE, E>(xa, W - g * kGroup, a.pre_c, acc);
+                add_ranks<BF16, PRE, E>(xa, W - g * kGroup, a.pre_c, a.group, rs);
                 if (g + 2 < ngroups) load_ranks<BF16>(grads, (g + 2) * kGroup, k, xa);
-                if (has_b) add_ranks<BF16, PRE, E>(xb, W - (g + 1) * kGroup, a.pre_c, acc);
+                if (has_b) add_ranks<BF16, PRE, E>(xb, W - (g + 1) * kGroup, a.pre_c, a.group, rs);
             }
         } else {
             // W <= kGroup: one group, fewer registers
             u32x4 xa[kGroup];
             load_ranks<BF16>(grads, 0, k, xa);
-            add_ranks<BF16, PRE, E>(xa, W, a.pre_c, acc);
+            add_ranks<BF16, PRE, E>(xa, W, a.pre_c, a.group, rs);
+        }
+        if (a.group > 0) {   // every sharded group has been folded: the outer sum is the result
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[e] = rs.outer[e];
         }
 
         if (a.last) {
 #pragma unroll
             for (int e = 0; e < E; ++e) acc[e] = post_scale(acc[e], a);
+        }
+        if (a.accum) {
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                acc[4 * q] = old[q].x + acc[4 * q];
+                acc[4 * q + 1] = old[q].y + acc[4 * q + 1];
+                acc[4 * q + 2] = old[q].z + acc[4 * q + 2];
+                acc[4 * q + 3] = old[q].w + acc[4 * q + 3];
+            }
         }
         if (a.out != nullptr) {
 #pragma unroll
@@ -445,9 +495,21 @@ __device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs&
         const int t = threadIdx.x;
         if (t < nrag) {
             const int64_t k = t < head ? t : tail0 + (t - head);
+            const float old_r = a.accum ? a.out[k] : 0.0f;
             float r = a.cont ? a.out[k] : -0.0f;
-            for (int32_t w = 0; w < W; ++w) r = r + pre_scale<PRE>(load_grad<BF16>(grads.p[w], k), a.pre_c);
+            float outer_r = -0.0f;
+            int32_t cnt = 0;
+            for (int32_t w = 0; w < W; ++w) {
+                r = r + pre_scale<PRE>(load_grad<BF16>(grads.p[w], k), a.pre_c);
+                if (a.group > 0 && ++cnt == a.group) {
+                    outer_r = outer_r + r;
+                    r = -0.0f;
+                    cnt = 0;
+                }
+            }
+            if (a.group > 0) r = outer_r;
             if (a.last) r = post_scale(r, a);
+            if (a.accum) r = old_r + r;
             if (a.out != nullptr) a.out[k] = r;
             if constexpr (FUSED) {
                 float pk = a.p[k], mk = a.m[k], vk = a.v[k];
@@ -513,6 +575,42 @@ __global__ __launch_bounds__(kBlock) void adam_kernel(float* __restrict__ p, con
             float pk = p[k], mk = m[k], vk = v[k];
             adam_update(pk, g[k], mk, vk, c);
             p[k] = pk; m[k] = mk; v[k] = vk;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// gradient accumulation without communication (Sec. 3.3.4): acc[k] += add[k]
+// over the unsharded buffer; one binary32 addition per element
+// ---------------------------------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void accumulate_kernel(float* __restrict__ acc, const void* __restrict__ add,
+                                                             int64_t n)
+{
+    const int64_t head = head_elems(acc, 4, n);
+    const int64_t nvec = (n - head) >> 2;
+    const int64_t c = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (c < nvec) {
+        const int64_t k = head + (c << 2);
+        f32x4 a = *reinterpret_cast<const f32x4*>(acc + k);
+        f32x4 b;
+        if constexpr (BF16) {
+            const u32x2 h = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x2_a2*>(static_cast<const uint16_t*>(add) + k));
+            b = f32x4{u2f(h.x << 16), u2f(h.x & 0xFFFF0000u), u2f(h.y << 16), u2f(h.y & 0xFFFF0000u)};
+        } else {
+            b = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(static_cast<const float*>(add) + k));
+        }
+        a = a + b;
+        *reinterpret_cast<f32x4*>(acc + k) = a;
+    }
+    if (blockIdx.x == 0) {
+        const int64_t tail0 = head + (nvec << 2);
+        const int64_t nrag = head + (n - tail0);
+        const int t = threadIdx.x;
+        if (t < nrag) {
+            const int64_t k = t < head ? t : tail0 + (t - head);
+            acc[k] = acc[k] + load_grad<BF16>(add, k);
         }
     }
 }
@@ -606,9 +704,11 @@ void launch_reduce_pre(int pre_mode, const PtrTable& tab, const RsArgs& a, hipSt
 // shared driver of fsdp_reduce_scatter_local and fsdp_reduce_scatter_adam_fused
 int reduce_driver(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dtype_t grad_dtype, int32_t rank,
                   float pre, float post, float* out, bool fused, float* p, float* m, float* v, uint16_t* p_lp,
-                  const AdamConsts& adam, hipStream_t st)
+                  const AdamConsts& adam, hipStream_t st, int32_t num_groups = 1, bool accumulate = false)
 {
-    const int32_t W = L->world_size;
+    // hybrid sharding: num_groups sharded groups of L->world_size ranks each, table group-major
+    const int32_t W = L->world_size * num_groups;
+    if ((num_groups > 1 || accumulate) && W > kMaxRanks) return FSDP_ERR_INVALID_ARG;
     const int64_t S = L->S;
     const bool bf16 = grad_dtype == FSDP_BF16;
     const int64_t esz = bf16 ? 2 : 4;
@@ -633,6 +733,8 @@ int reduce_driver(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dty
         a.W = nw;
         a.cont = w0 > 0;
         a.last = w0 + nw == W;
+        a.group = num_groups > 1 ? L->world_size : 0;
+        a.accum = accumulate ? 1 : 0;
         a.pre_c = pre_c;
         a.post_mul = post_mul;
         a.post_c = post_c;
@@ -655,14 +757,17 @@ int reduce_driver(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dty
 }
 
 int check_reduce_args(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dtype_t grad_dtype, int32_t rank,
-                      float pre, float post)
+                      float pre, float post, int32_t num_groups = 1)
 {
     if (!L || !grad_ptrs) return FSDP_ERR_NULL_PTR;
+    if (num_groups < 1) return FSDP_ERR_INVALID_ARG;
     if (grad_dtype != FSDP_F32 && grad_dtype != FSDP_BF16) return FSDP_ERR_BAD_DTYPE;
     if (rank < 0 || rank >= L->world_size) return FSDP_ERR_RANK_RANGE;
     if (!std::isfinite(pre) || !std::isfinite(post) || !(pre > 0.0f) || !(post > 0.0f)) return FSDP_ERR_INVALID_ARG;
     const uintptr_t al = grad_dtype == FSDP_BF16 ? 2 : 4;
-    for (int32_t w = 0; w < L->world_size; ++w) {
+    const int64_t nptr = static_cast<int64_t>(L->world_size) * num_groups;
+    if (nptr > 0x7FFFFFFF) return FSDP_ERR_OVERFLOW;
+    for (int64_t w = 0; w < nptr; ++w) {
         if (!grad_ptrs[w]) return FSDP_ERR_NULL_PTR;
         if (misaligned(grad_ptrs[w], al)) return FSDP_ERR_INVALID_ARG;
     }
@@ -917,6 +1022,50 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* L, const void
         else FSDP_LAUNCH_COMBINED(false, kPreDiv);
     }
 #undef FSDP_LAUNCH_COMBINED
+    return launch_status();
+}
+
+int fsdp_reduce_scatter_hybrid(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dtype_t grad_dtype,
+                               int32_t num_groups, int32_t rank, float pre_div, float post_div,
+                               float* grad_shard_out, void* hip_stream)
+{
+    int rc = check_reduce_args(L, grad_ptrs, grad_dtype, rank, pre_div, post_div, num_groups);
+    if (rc != FSDP_OK) return rc;
+    if (!grad_shard_out) return FSDP_ERR_NULL_PTR;
+    if (misaligned(grad_shard_out, 4)) return FSDP_ERR_INVALID_ARG;
+    const AdamConsts none = {};
+    return reduce_driver(L, grad_ptrs, grad_dtype, rank, pre_div, post_div, grad_shard_out, false, nullptr, nullptr,
+                         nullptr, nullptr, none, static_cast<hipStream_t>(hip_stream), num_groups, false);
+}
+
+int fsdp_reduce_scatter_accumulate(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dtype_t grad_dtype,
+                                   int32_t rank, float pre_div, float post_div, float* grad_shard_acc,
+                                   void* hip_stream)
+{
+    int rc = check_reduce_args(L, grad_ptrs, grad_dtype, rank, pre_div, post_div);
+    if (rc != FSDP_OK) return rc;
+    if (!grad_shard_acc) return FSDP_ERR_NULL_PTR;
+    if (misaligned(grad_shard_acc, 4)) return FSDP_ERR_INVALID_ARG;
+    const AdamConsts none = {};
+    return reduce_driver(L, grad_ptrs, grad_dtype, rank, pre_div, post_div, grad_shard_acc, false, nullptr, nullptr,
+                         nullptr, nullptr, none, static_cast<hipStream_t>(hip_stream), 1, true);
+}
+
+int fsdp_grad_accumulate(const fsdp_layout_t* L, float* grad_acc, const void* grad_add, fsdp_dtype_t add_dtype,
+                         void* hip_stream)
+{
+    if (!L || !grad_acc || !grad_add) return FSDP_ERR_NULL_PTR;
+    if (add_dtype != FSDP_F32 && add_dtype != FSDP_BF16) return FSDP_ERR_BAD_DTYPE;
+    if (misaligned(grad_acc, 4) || misaligned(grad_add, add_dtype == FSDP_BF16 ? 2 : 4)) return FSDP_ERR_INVALID_ARG;
+    const int64_t blocks = ceil_div(L->P / 4 + 1, kBlock);
+    if (!grid_ok(blocks)) return FSDP_ERR_OVERFLOW;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (add_dtype == FSDP_BF16)
+        hipLaunchKernelGGL(accumulate_kernel<true>, dim3(static_cast<uint32_t>(blocks)), dim3(kBlock), 0, st, grad_acc,
+                           grad_add, L->P);
+    else
+        hipLaunchKernelGGL(accumulate_kernel<false>, dim3(static_cast<uint32_t>(blocks)), dim3(kBlock), 0, st,
+                           grad_acc, grad_add, L->P);
     return launch_status();
 }
 

@@ -213,6 +213,28 @@ def test_compute_entry_points_reject_bad_arguments_before_launch(L):
     assert pf(h, good4, 0, 4, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, hn, good4, buf, 1, st) == RANK_RANGE
     assert pf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(0), *ok_h, None, hn, good4, buf, 1, st) == INVALID
     raw.fsdp_layout_destroy(hn)
+    # hybrid sharding and gradient accumulation
+    good8 = _table([0x10000 + 64 * i for i in range(8)])
+    hy = raw.fsdp_reduce_scatter_hybrid
+    assert hy(h, good8, 0, 2, 0, f(2), f(4), None, st) == NULL
+    assert hy(h, None, 0, 2, 0, f(2), f(4), buf, st) == NULL
+    assert hy(h, good8, 0, 0, 0, f(2), f(4), buf, st) == INVALID
+    assert hy(h, good8, 0, 2, 4, f(2), f(4), buf, st) == RANK_RANGE
+    assert hy(h, good8, 5, 2, 0, f(2), f(4), buf, st) == BAD_DTYPE
+    assert hy(h, _table([0x10000 + 64 * i for i in range(7)] + [None]), 0, 2, 0, f(2), f(4), buf, st) == NULL
+    many68 = _table([0x10000 + 64 * i for i in range(68)])
+    assert hy(h, many68, 0, 17, 0, f(2), f(34), buf, st) == INVALID          # 17 groups x 4 ranks > 64
+    ra = raw.fsdp_reduce_scatter_accumulate
+    assert ra(h, good4, 0, 0, f(2), f(2), None, st) == NULL
+    assert ra(h, good4, 0, 9, f(2), f(2), buf, st) == RANK_RANGE
+    assert ra(h, good4, 0, 0, f(0), f(2), buf, st) == INVALID
+    ga = raw.fsdp_grad_accumulate
+    assert ga(None, buf, buf, 0, st) == NULL
+    assert ga(h, None, buf, 0, st) == NULL
+    assert ga(h, buf, None, 0, st) == NULL
+    assert ga(h, buf, buf, 2, st) == BAD_DTYPE
+    assert ga(h, ctypes.c_void_p(0x30002), buf, 0, st) == INVALID
+    assert ga(h, buf, ctypes.c_void_p(0x30001), 1, st) == INVALID
     raw.fsdp_layout_destroy(h)
     # W > 64 needs the gradient shard buffer to carry partial sums
     rc, h2 = _init(raw, [(1000,)], 65)

@@ -1,0 +1,135 @@
+"""GPU parity for the rows after the hot path: hybrid-sharding reduction
+(Sec. 3.2.2) and gradient accumulation with and without communication
+(Sec. 3.3.4).  Bit-exact against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from gpu_helpers import POISON32, carve, first_diff, load_product, np_bits, np_f32, np_grad, same_bits
+from test_gpu_parity_small import big_unit, make_grads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def F():
+    assert torch.cuda.is_available()
+    return load_product()
+
+
+@pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("G,Fs,pre,post", [(1, 8, 4.0, 2.0), (2, 8, 4.0, 4.0), (4, 2, 2.0, 4.0), (3, 4, 4.0, 3.0),
+                                           (8, 8, 8.0, 8.0), (2, 3, 1.0, 6.0), (5, 1, 1.0, 5.0), (16, 4, 8.0, 8.0)])
+def test_hybrid_reduce_scatter_bit_exact(F, gdt, G, Fs, pre, post):
+    unit = big_unit() if G * Fs <= 16 else workloads.ragged_unit()
+    lay = F.fsdp_layout_init(unit.shapes, Fs)            # sharding factor F, world = G * F ranks
+    S, P, N = lay.shard, lay.padded, lay.numel
+    grads = make_grads(G * Fs, P, N, gdt, 700 + G * Fs, outliers=True, elem_offset=1)
+    host = [np_grad(g) for g in grads]
+    for r in sorted({0, Fs // 2, Fs - 1}):
+        out = carve(S, torch.float32, r % 3, fill=POISON32)
+        F.fsdp_reduce_scatter_hybrid(lay, grads, G, r, pre, post, out)
+        torch.cuda.synchronize()
+        ref = oracle.reduce_slices_hybrid([h[r * S:(r + 1) * S] for h in host], G, Fs, pre, post)
+        got = np_bits(out)
+        assert same_bits(got, ref.view(np.uint32)), f"rank {r}: {first_diff(got, ref.view(np.uint32))}"
+        if G == 1:
+            flat = torch.empty(S, dtype=torch.float32, device="cuda")
+            F.fsdp_reduce_scatter_local(lay, grads, r, pre, post, flat)
+            torch.cuda.synchronize()
+            assert same_bits(np_bits(flat), got)
+
+
+def test_hybrid_order_witness_on_gpu(F):
+    """(1e8, 1 | -1e8, 1): group sums first gives 0, flat rank order gives 1."""
+    lay = F.fsdp_layout_init([(3000,)], 2)
+    grads = [torch.full((lay.padded,), v, dtype=torch.float32, device="cuda") for v in (1e8, 1.0, -1e8, 1.0)]
+    out = torch.empty(lay.shard, dtype=torch.float32, device="cuda")
+    F.fsdp_reduce_scatter_hybrid(lay, grads, 2, 1, 1.0, 1.0, out)
+    torch.cuda.synchronize()
+    assert bool((out == 0.0).all())
+
+
+def test_hybrid_rejects_too_many_ranks(F):
+    lay = F.fsdp_layout_init([(100,)], 8)
+    grads = [torch.zeros(lay.padded, device="cuda") for _ in range(72)]
+    out = torch.empty(lay.shard, device="cuda")
+    with pytest.raises(F.FsdpError) as e:
+        F.fsdp_reduce_scatter_hybrid(lay, grads, 9, 0, 1.0, 1.0, out)
+    assert e.value.status == -1
+
+
+@pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("W", [1, 3, 8, 12, 64])
+def test_gradient_accumulation_with_communication(F, gdt, W):
+    """Three micro-batches, each reduce-scattered into the running sharded gradient."""
+    unit = big_unit() if W <= 12 else workloads.ragged_unit()
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S, P, N = lay.shard, lay.padded, lay.numel
+    pre, post = F.fsdp_default_divide_factors(W)
+    r = W - 1
+    acc = carve(S, torch.float32, 1)
+    acc.zero_()
+    h_acc = np.zeros(S, np.float32)
+    for mb in range(3):
+        grads = make_grads(W, P, N, gdt, 900 + 10 * mb + W)
+        F.fsdp_reduce_scatter_accumulate(lay, grads, r, pre, post, acc)
+        torch.cuda.synchronize()
+        h_acc = oracle.accumulate(h_acc, oracle.reduce_scatter([np_grad(g) for g in grads], r, pre, post))
+        assert same_bits(np_bits(acc), h_acc.view(np.uint32)), f"micro-batch {mb}: {first_diff(np_bits(acc), h_acc.view(np.uint32))}"
+
+
+@pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("off", [0, 1, 3])
+def test_gradient_accumulation_without_communication(F, gdt, off):
+    """Unsharded local accumulation over P elements, then one reduce-scatter."""
+    unit = big_unit()
+    W = 4
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S, P, N = lay.shard, lay.padded, lay.numel
+    accs = [carve(P, torch.float32, off) for _ in range(W)]
+    for a in accs:
+        a.zero_()
+    h_accs = [np.zeros(P, np.float32) for _ in range(W)]
+    for mb in range(3):
+        grads = make_grads(W, P, N, gdt, 1200 + 10 * mb, elem_offset=(off + 1) % 2)
+        for w in range(W):
+            F.fsdp_grad_accumulate(lay, accs[w], grads[w])
+            h_accs[w] = oracle.accumulate(h_accs[w], np_grad(grads[w]))
+        torch.cuda.synchronize()
+        for w in range(W):
+            assert same_bits(np_bits(accs[w]), h_accs[w].view(np.uint32)), (mb, w)
+    out = torch.empty(S, dtype=torch.float32, device="cuda")
+    F.fsdp_reduce_scatter_local(lay, accs, 2, 2.0, 2.0, out)
+    torch.cuda.synchronize()
+    assert same_bits(np_bits(out), oracle.reduce_scatter(h_accs, 2, 2.0, 2.0).view(np.uint32))
+
+
+def test_accumulate_then_fused_adam_equals_oracle_chain(F):
+    """Two accumulated micro-batches followed by the optimizer step at t = 2 from non-zero state."""
+    unit = big_unit()
+    W = 8
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S, P, N = lay.shard, lay.padded, lay.numel
+    pre, post = F.fsdp_default_divide_factors(W)
+    r = 3
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    p = torch.empty(S, device="cuda").normal_(0, 0.02, generator=g)
+    m = torch.empty(S, device="cuda").normal_(0, 1e-3, generator=g)
+    v = torch.empty(S, device="cuda").uniform_(0, 1e-6, generator=g)
+    hp, hm, hv = np_f32(p).copy(), np_f32(m).copy(), np_f32(v).copy()
+    acc = torch.zeros(S, device="cuda")
+    h_acc = np.zeros(S, np.float32)
+    for mb in range(2):
+        grads = make_grads(W, P, N, torch.float32, 1500 + mb)
+        F.fsdp_reduce_scatter_accumulate(lay, grads, r, pre, post, acc)
+        h_acc = oracle.accumulate(h_acc, oracle.reduce_scatter([np_f32(x) for x in grads], r, pre, post))
+    F.fsdp_shard_adam_step(lay, p, acc, m, v, 2, 1e-4, 0.9, 0.999, 1e-8)
+    torch.cuda.synchronize()
+    rp, rm, rv = oracle.adam_f32(hp, h_acc, hm, hv, 2, 1e-4, 0.9, 0.999, 1e-8)
+    from gpu_helpers import adam_close
+    ok, bad = adam_close(np_f32(p), np_f32(m), np_f32(v), rp, rm, rv, hp, hm, h_acc)
+    assert ok, bad
