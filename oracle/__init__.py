@@ -162,6 +162,16 @@ def unshard_f32(shards: Sequence[np.ndarray]) -> np.ndarray:
     return out
 
 
+def gather_lp(lp_shards: Sequence[np.ndarray]) -> np.ndarray:
+    """AllGather of the ranks' bf16 shards (uint16 bit patterns) into the flat buffer."""
+    sh = [_u16(s) for s in lp_shards]
+    S = sh[0].size
+    assert all(s.size == S for s in sh)
+    out = np.empty(S * len(sh), dtype=np.uint16)
+    lib().orc_gather_lp(_ptr_array(sh), _c_i32(len(sh)), _c_i64(S), _vp(_ptr(out)))
+    return out
+
+
 def views(flat: np.ndarray, off: Sequence[int], shapes: Sequence[Sequence[int]]) -> List[np.ndarray]:
     """Per-parameter views into the unsharded flat buffer (Sec. 3.2.3): zero
     copy, view_i = flat[off_i : off_i + n_i] reshaped."""

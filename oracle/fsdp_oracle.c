@@ -134,6 +134,18 @@ void orc_unshard_f32(const float *const *shards, int32_t W, int64_t S, float *fl
     }
 }
 
+/* Low-precision gather: when every rank keeps the bf16 cast of its own shard
+ * (Sec. 4.4: one full-to-low cast per FlatParameter, collectives in the low
+ * precision), the unshard is the plain AllGather of those bf16 shards:
+ * flat_lp[w*S + k] = lp_shard_w[k].
+ * Pins: numpy.concatenate; equals orc_unshard_bf16 of the fp32 shards when
+ * lp_shard_w = cast(shard_w). */
+void orc_gather_lp(const uint16_t *const *lp_shards, int32_t W, int64_t S, uint16_t *flat_lp)
+{
+    for (int32_t w = 0; w < W; ++w)
+        for (int64_t k = 0; k < S; ++k) flat_lp[(int64_t)w * S + k] = lp_shards[w][k];
+}
+
 /* -------------------------------------------------------- reduce-scatter */
 
 static inline float bf16_to_f32(uint16_t h)

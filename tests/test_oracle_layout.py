@@ -146,3 +146,15 @@ def test_unshard_bf16_is_cast_of_parameters(W):
     assert not lp[N:].any()
     for v, a in zip(oracle.views(lp, off, unit.shapes), params):
         assert np.array_equal(v, oracle.cast_bf16(a))
+
+
+@pytest.mark.parametrize("W", [1, 3, 8])
+def test_gather_of_cast_shards_equals_unshard(W):
+    """Each rank casts its own shard and the gather moves bf16 (Sec. 4.4): the
+    same bytes as casting while gathering; and the gather is a concatenation."""
+    unit, params = _ragged_params(20 + W)
+    shards, (off, N, S, P, pad) = oracle.flatten_shard(params, W)
+    lp = [oracle.cast_bf16(s) for s in shards]
+    got = oracle.gather_lp(lp)
+    assert np.array_equal(got, np.concatenate(lp))
+    assert np.array_equal(got, oracle.unshard_bf16(shards))

@@ -37,6 +37,7 @@ MUTANTS = [
      "float acc = slices[0][k];\n        for (int32_t w = 1; w < W; ++w) acc = acc + slices[w][k];\n        out[k] = acc / pre / post;"),
     ("scatter_wrong_slice", "sl[w] = gradbufs[w] + (int64_t)r * S;", "sl[w] = gradbufs[w] + (int64_t)(r ? r - 1 : 0) * S;"),
     ("bf16_upcast_shift", "(uint32_t)h << 16", "(uint32_t)h << 15"),
+    ("gather_lp_ignores_rank", "flat_lp[(int64_t)w * S + k] = lp_shards[w][k];", "flat_lp[(int64_t)w * S + k] = lp_shards[0][k];"),
     ("hybrid_drops_groups", "outer = (i == 0) ? inner : outer + inner;", "outer = inner;"),
     ("hybrid_rank_major_layout", "inner = inner + slices[(int64_t)i * F + l][k] / pre;",
      "inner = inner + slices[(int64_t)l * G + i][k] / pre;"),
@@ -64,6 +65,7 @@ def _pins():
         lambda: t_layout.test_padding_closed_form_and_bound(3),
         lambda: t_layout.test_flatten_matches_concatenate_and_views_invert(3),
         lambda: t_layout.test_unshard_bf16_is_cast_of_parameters(3),
+        lambda: t_layout.test_gather_of_cast_shards_equals_unshard(3),
         t_cast.test_hand_vectors,
         t_cast.test_nan_stays_quiet_nan_with_sign,
         t_cast.test_nearest_neighbour_in_exact_arithmetic,
