@@ -36,10 +36,11 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="index into BASELINE.json configs (default 1)")
     ap.add_argument("--max-units", type=int, default=0, help="limit the number of units (0 = all)")
-    ap.add_argument("--mode", choices=["prefetch", "fused", "separate"], default="prefetch",
+    ap.add_argument("--mode", choices=["prefetch", "fused", "separate", "lp"], default="prefetch",
                     help="prefetch: unit i's fused reduce-scatter+Adam shares one launch with unit i+1's unshard "
                          "(backward prefetching); fused: reduce-scatter + Adam in one launch, unshard in another; "
-                         "separate: the three required entry points, one launch each")
+                         "separate: the three required entry points, one launch each; lp: every rank keeps a bf16 "
+                         "copy of its shard (written by the fused Adam), the unshard gathers bf16 (Sec. 4.4)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
                     help="run only N launches of a plain 256 MiB copy kernel (calibrates rocprofv3 --pmc byte counters)")
@@ -85,6 +86,11 @@ class UnitState:
         self.v = torch.zeros(S, dtype=torch.float32, device="cuda")
         self.gshard = torch.empty(S, dtype=torch.float32, device="cuda")
         self.shard_tab = F.PtrArray(self.shards)
+        self.lp_base = torch.empty(W * S, dtype=torch.bfloat16, device="cuda")
+        self.lp_shards = [self.lp_base[w * S:(w + 1) * S] for w in range(W)]
+        for w in range(W):
+            F.fsdp_cast_shard(self.lay, self.shards[w], self.lp_shards[w])
+        self.lp_tab = F.PtrArray(self.lp_shards)
         self.grad_tab = F.PtrArray(self.grads)
         # algorithmic bytes (fixed numerators, whatever the kernels really touch)
         self.b_unshard = 6 * P
@@ -170,6 +176,12 @@ def main():
                                  s.b_reduce + s.b_adam + nxt.b_unshard))
             else:
                 launches.append(("reduce_adam", (lambda t, s=s: reduce_adam(s, t)), s.b_reduce + s.b_adam))
+        elif args.mode == "lp":
+            launches.append(("unshard_lp", (lambda t, s=s, buf=buf: F.fsdp_unshard_lp(s.lay, s.lp_tab, buf[:s.P])),
+                             s.b_unshard))
+            launches.append(("reduce_adam_lp", (lambda t, s=s: F.fsdp_reduce_scatter_adam_fused(
+                s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m, s.v, t, *hp, s.lp_shards[rank])),
+                s.b_reduce + s.b_adam))
         else:
             launches.append(("unshard", (lambda t, s=s, buf=buf: unshard(s, buf)), s.b_unshard))
             if args.mode == "fused":

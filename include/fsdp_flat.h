@@ -188,6 +188,19 @@ int fsdp_reduce_scatter_accumulate(const fsdp_layout_t* layout, const void* cons
 int fsdp_grad_accumulate(const fsdp_layout_t* layout, float* grad_acc, const void* grad_add,
                          fsdp_dtype_t add_dtype, void* hip_stream);
 
+/* ---- Sec. 4.4: the low-precision copy of the local shard, kept per rank -----
+ * fsdp_cast_shard: lp_shard_out[k] = bf16_rne(shard[k]) for the S elements of
+ * one fp32 shard (the "full-to-low-precision cast per FlatParameter").
+ * fsdp_reduce_scatter_adam_fused can also write it (p_lp_out) while the updated
+ * shard is still in registers, which saves this pass in every later iteration.
+ * fsdp_unshard_lp: the AllGather in the low precision, flat_out[w * S + k] =
+ * lp_shard_w[k]; lp_shard_ptrs: host [W] of dev bf16 shards (S each); flat_out:
+ * dev bf16 [P].  Together they give exactly fsdp_unshard(..., FSDP_BF16). */
+int fsdp_cast_shard(const fsdp_layout_t* layout, const float* shard, void* lp_shard_out,
+                    void* hip_stream);
+int fsdp_unshard_lp(const fsdp_layout_t* layout, const void* const* lp_shard_ptrs, void* flat_out,
+                    void* hip_stream);
+
 /* Last hipError_t seen by this thread inside the library (0 if none). */
 int fsdp_last_hip_error(void);
 /* Static string for a fsdp_status_t. */

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     FsdpError,
     Layout,
     PtrArray,
+    fsdp_cast_shard,
     fsdp_default_divide_factors,
     fsdp_flatten_shard,
     fsdp_layout_init,
@@ -21,6 +22,7 @@ from .binding import (  # noqa: F401
     fsdp_reduce_scatter_local,
     fsdp_shard_adam_step,
     fsdp_unshard,
+    fsdp_unshard_lp,
     fsdp_view_ptr,
     fsdp_views,
     lib,

@@ -64,6 +64,8 @@ _SIGNATURES = {
     "fsdp_reduce_scatter_hybrid": [_vp, _pp, ctypes.c_int, _i32, _i32, _f32, _f32, _vp, _vp],
     "fsdp_reduce_scatter_accumulate": [_vp, _pp, ctypes.c_int, _i32, _f32, _f32, _vp, _vp],
     "fsdp_grad_accumulate": [_vp, _vp, _vp, ctypes.c_int, _vp],
+    "fsdp_cast_shard": [_vp, _vp, _vp, _vp],
+    "fsdp_unshard_lp": [_vp, _pp, _vp, _vp],
     "fsdp_last_hip_error": [],
 }
 
@@ -335,3 +337,17 @@ def fsdp_grad_accumulate(layout: Layout, grad_acc: torch.Tensor, grad_add: torch
     _check("fsdp_grad_accumulate",
            lib().fsdp_grad_accumulate(layout.handle, _vp(grad_acc.data_ptr()), _vp(grad_add.data_ptr()), dt,
                                       _stream_handle(stream)))
+
+
+def fsdp_cast_shard(layout: Layout, shard: torch.Tensor, lp_shard_out: torch.Tensor, stream=None) -> None:
+    _dev_tensor(shard, torch.float32, layout.shard, "shard")
+    _dev_tensor(lp_shard_out, torch.bfloat16, layout.shard, "lp_shard_out")
+    _check("fsdp_cast_shard", lib().fsdp_cast_shard(layout.handle, _vp(shard.data_ptr()),
+                                                   _vp(lp_shard_out.data_ptr()), _stream_handle(stream)))
+
+
+def fsdp_unshard_lp(layout: Layout, lp_shard_ptrs, flat_out: torch.Tensor, stream=None) -> None:
+    shards = _ptr_table(lp_shard_ptrs, torch.bfloat16, layout.shard, layout.world_size, "lp_shard_ptrs")
+    _dev_tensor(flat_out, torch.bfloat16, layout.padded, "flat_out")
+    _check("fsdp_unshard_lp", lib().fsdp_unshard_lp(layout.handle, shards.array, _vp(flat_out.data_ptr()),
+                                                   _stream_handle(stream)))

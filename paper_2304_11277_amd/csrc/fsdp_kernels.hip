@@ -142,6 +142,34 @@ __global__ __launch_bounds__(kBlock) void unshard_f32_kernel(PtrTable shards, in
     }
 }
 
+// Gather of bf16 shards (the AllGather in the low precision, Sec. 4.4):
+// flat_lp[w*S + k] = lp_shard_w[k]; 16-byte destination vectors, sources only
+// 2-byte aligned.
+__global__ __launch_bounds__(kBlock) void gather_lp_kernel(PtrTable shards, int64_t S,
+                                                            uint16_t* __restrict__ out_base,
+                                                            int32_t tiles_per_shard)
+{
+    const int32_t w = blockIdx.x / tiles_per_shard;
+    const int32_t tile = blockIdx.x - w * tiles_per_shard;
+    const uint16_t* __restrict__ src = static_cast<const uint16_t*>(shards.p[w]);
+    uint16_t* __restrict__ dst = out_base + static_cast<int64_t>(w) * S;
+
+    const int64_t head = head_elems(dst, 2, S);
+    const int64_t nvec = (S - head) >> 3;
+    const int64_t c = static_cast<int64_t>(tile) * kBlock + threadIdx.x;
+    if (c < nvec) {
+        const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a2*>(src + head + (c << 3)));
+        __builtin_nontemporal_store(a, reinterpret_cast<u32x4*>(dst + head + (c << 3)));
+    }
+    if (tile == 0) {
+        const int64_t tail0 = head + (nvec << 3);
+        const int64_t ntail = S - tail0;
+        const int t = threadIdx.x;
+        if (t < head) dst[t] = src[t];
+        if (t >= 64 && t - 64 < ntail) dst[tail0 + t - 64] = src[tail0 + t - 64];
+    }
+}
+
 // ---------------------------------------------------------------------------
 // flatten + pad + shard (Sec. 3.2.1): LDS-staged ragged pack.
 // A block owns one 16-byte-aligned destination tile of kPackTile floats in one
@@ -1067,6 +1095,46 @@ int fsdp_grad_accumulate(const fsdp_layout_t* L, float* grad_acc, const void* gr
         hipLaunchKernelGGL(accumulate_kernel<false>, dim3(static_cast<uint32_t>(blocks)), dim3(kBlock), 0, st,
                            grad_acc, grad_add, L->P);
     return launch_status();
+}
+
+int fsdp_cast_shard(const fsdp_layout_t* L, const float* shard, void* lp_shard_out, void* hip_stream)
+{
+    if (!L || !shard || !lp_shard_out) return FSDP_ERR_NULL_PTR;
+    if (misaligned(shard, 4) || misaligned(lp_shard_out, 2)) return FSDP_ERR_INVALID_ARG;
+    const int64_t tiles = ceil_div(L->S / 8 + 1, kBlock);
+    if (!grid_ok(tiles)) return FSDP_ERR_OVERFLOW;
+    PtrTable tab = {};
+    tab.p[0] = shard;
+    hipLaunchKernelGGL(unshard_bf16_kernel, dim3(static_cast<uint32_t>(tiles)), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(hip_stream), tab, L->S, static_cast<uint16_t*>(lp_shard_out),
+                       static_cast<int32_t>(tiles));
+    return launch_status();
+}
+
+int fsdp_unshard_lp(const fsdp_layout_t* L, const void* const* lp_shard_ptrs, void* flat_out, void* hip_stream)
+{
+    if (!L || !lp_shard_ptrs || !flat_out) return FSDP_ERR_NULL_PTR;
+    const int32_t W = L->world_size;
+    const int64_t S = L->S;
+    for (int32_t w = 0; w < W; ++w) {
+        if (!lp_shard_ptrs[w]) return FSDP_ERR_NULL_PTR;
+        if (misaligned(lp_shard_ptrs[w], 2)) return FSDP_ERR_INVALID_ARG;
+    }
+    if (misaligned(flat_out, 2)) return FSDP_ERR_INVALID_ARG;
+    const int64_t tiles = ceil_div(S / 8 + 1, kBlock);
+    if (!grid_ok(tiles * kMaxRanks)) return FSDP_ERR_OVERFLOW;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    for (int32_t w0 = 0; w0 < W; w0 += kMaxRanks) {
+        const int32_t nw = W - w0 < kMaxRanks ? W - w0 : kMaxRanks;
+        PtrTable tab = {};
+        for (int32_t j = 0; j < nw; ++j) tab.p[j] = lp_shard_ptrs[w0 + j];
+        uint16_t* base = static_cast<uint16_t*>(flat_out) + static_cast<int64_t>(w0) * S;
+        hipLaunchKernelGGL(gather_lp_kernel, dim3(static_cast<uint32_t>(tiles * nw)), dim3(kBlock), 0, st, tab, S,
+                           base, static_cast<int32_t>(tiles));
+        const int rc = launch_status();
+        if (rc != FSDP_OK) return rc;
+    }
+    return FSDP_OK;
 }
 
 }  // extern "C"

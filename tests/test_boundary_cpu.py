@@ -228,6 +228,16 @@ def test_compute_entry_points_reject_bad_arguments_before_launch(L):
     assert ra(h, good4, 0, 0, f(2), f(2), None, st) == NULL
     assert ra(h, good4, 0, 9, f(2), f(2), buf, st) == RANK_RANGE
     assert ra(h, good4, 0, 0, f(0), f(2), buf, st) == INVALID
+    assert raw.fsdp_cast_shard(None, buf, buf, st) == NULL
+    assert raw.fsdp_cast_shard(h, None, buf, st) == NULL
+    assert raw.fsdp_cast_shard(h, buf, None, st) == NULL
+    assert raw.fsdp_cast_shard(h, ctypes.c_void_p(0x30002), buf, st) == INVALID
+    assert raw.fsdp_cast_shard(h, buf, ctypes.c_void_p(0x30001), st) == INVALID
+    assert raw.fsdp_unshard_lp(None, good4, buf, st) == NULL
+    assert raw.fsdp_unshard_lp(h, None, buf, st) == NULL
+    assert raw.fsdp_unshard_lp(h, good4, None, st) == NULL
+    assert raw.fsdp_unshard_lp(h, with_null, buf, st) == NULL
+    assert raw.fsdp_unshard_lp(h, _table([0x10000, 0x10041, 0x10080, 0x100C0]), buf, st) == INVALID
     ga = raw.fsdp_grad_accumulate
     assert ga(None, buf, buf, 0, st) == NULL
     assert ga(h, None, buf, 0, st) == NULL

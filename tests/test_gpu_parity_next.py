@@ -133,3 +133,37 @@ def test_accumulate_then_fused_adam_equals_oracle_chain(F):
     from gpu_helpers import adam_close
     ok, bad = adam_close(np_f32(p), np_f32(m), np_f32(v), rp, rm, rv, hp, hm, h_acc)
     assert ok, bad
+
+
+@pytest.mark.parametrize("W", [1, 3, 8, 12, 100])
+@pytest.mark.parametrize("mode", ["separate", "contig_odd"])
+def test_low_precision_shard_handoff(F, W, mode):
+    """Each rank casts its own shard once (or Adam writes the bf16 copy), the
+    unshard gathers bf16: same flat buffer as the fused cast+gather."""
+    from test_gpu_parity_small import alloc_shards, make_params
+    from gpu_helpers import POISON16
+    unit = big_unit() if W <= 12 else workloads.ragged_unit()
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S, P = lay.shard, lay.padded
+    params = make_params(unit, 40 + W, misalign=False)
+    shards, _ = alloc_shards(W, S, mode)
+    F.fsdp_flatten_shard(lay, params, shards)
+    if mode == "separate":
+        lps = [carve(S, torch.bfloat16, w % 3, fill=POISON16) for w in range(W)]
+    else:
+        base = carve(W * S, torch.bfloat16, 1, fill=POISON16)
+        lps = [base[w * S:(w + 1) * S] for w in range(W)]
+    for w in range(W):
+        F.fsdp_cast_shard(lay, shards[w], lps[w])
+    flat = carve(P, torch.bfloat16, 1, fill=POISON16)
+    F.fsdp_unshard_lp(lay, lps, flat)
+    ref_flat = torch.empty(P, dtype=torch.bfloat16, device="cuda")
+    F.fsdp_unshard(lay, shards, ref_flat)
+    torch.cuda.synchronize()
+    h_shards = [np_f32(s) for s in shards]
+    for w in range(W):
+        assert same_bits(np_bits(lps[w]), oracle.cast_bf16(h_shards[w])), f"cast of shard {w}"
+    ref = oracle.gather_lp([np_bits(x) for x in lps])
+    assert same_bits(np_bits(flat), ref), first_diff(np_bits(flat), ref)
+    assert same_bits(np_bits(flat), np_bits(ref_flat))
+    assert same_bits(np_bits(flat), oracle.unshard_bf16(h_shards))
