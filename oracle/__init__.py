@@ -44,7 +44,18 @@ def lib() -> ctypes.CDLL:
         _lib.orc_bf16_rne.restype = ctypes.c_uint16
         _lib.orc_bf16_rne.argtypes = [ctypes.c_uint32]
         _lib.orc_num_threads.restype = ctypes.c_int
+        _configure(_lib)
     return _lib
+
+
+def _configure(l) -> None:
+    """restype / argtypes of the functions that do not return int."""
+    l.orc_bf16_rne.restype = ctypes.c_uint16
+    l.orc_bf16_rne.argtypes = [ctypes.c_uint32]
+    l.orc_f16_rne.restype = ctypes.c_uint16
+    l.orc_f16_rne.argtypes = [ctypes.c_uint32]
+    l.orc_unscale_check.restype = ctypes.c_float
+    l.orc_found_inf_combine.restype = ctypes.c_float
 
 
 _c_i64 = ctypes.c_int64
@@ -247,6 +258,71 @@ def accumulate(acc: np.ndarray, add: np.ndarray) -> np.ndarray:
         assert add.dtype == np.float32
         lib().orc_accumulate_f32(_vp(_ptr(acc)), _vp(_ptr(add)), _c_i64(acc.size))
     return acc
+
+
+# ------------------------------------------------- fp16 and gradient scaler
+
+def f16_rne_scalar(bits: int) -> int:
+    return int(lib().orc_f16_rne(ctypes.c_uint32(bits & 0xFFFFFFFF)))
+
+
+def cast_f16(x: np.ndarray) -> np.ndarray:
+    shape = np.shape(x)
+    x = _f32(x)
+    y = np.empty(shape, dtype=np.uint16)
+    lib().orc_cast_f16(_vp(_ptr(x)), _c_i64(x.size), _vp(_ptr(y)))
+    return y
+
+
+def cast_f16_bits(first: int, count: int) -> np.ndarray:
+    y = np.empty(count, dtype=np.uint16)
+    lib().orc_cast_f16_bits(ctypes.c_uint32(first), _c_i64(count), _vp(_ptr(y)))
+    return y
+
+
+def upcast_f16(h: np.ndarray) -> np.ndarray:
+    h = _u16(h)
+    y = np.empty(h.shape, dtype=np.float32)
+    lib().orc_upcast_f16(_vp(_ptr(h)), _c_i64(h.size), _vp(_ptr(y)))
+    return y
+
+
+def unshard_f16(shards: Sequence[np.ndarray]) -> np.ndarray:
+    sh = [_f32(s) for s in shards]
+    S = sh[0].size
+    out = np.empty(S * len(sh), dtype=np.uint16)
+    lib().orc_unshard_f16(_ptr_array(sh), _c_i32(len(sh)), _c_i64(S), _vp(_ptr(out)))
+    return out
+
+
+def reduce_slices_f16(slices: Sequence[np.ndarray], pre: float, post: float) -> np.ndarray:
+    """slices hold binary16 bit patterns (uint16)."""
+    sl = [_u16(s) for s in slices]
+    S = sl[0].size
+    out = np.empty(S, dtype=np.float32)
+    lib().orc_reduce_slices_f16(_ptr_array(sl), _c_i32(len(sl)), _c_i64(S), _c_f32(pre), _c_f32(post), _vp(_ptr(out)))
+    return out
+
+
+def unscale_check(g: np.ndarray, inv_scale: float):
+    """Returns (g * inv_scale, found_inf of this shard)."""
+    g = _f32(g).copy()
+    found = lib().orc_unscale_check(_vp(_ptr(g)), _c_i64(g.size), _c_f32(inv_scale))
+    return g, float(found)
+
+
+def found_inf_combine(flags: Sequence[float]) -> float:
+    a = np.asarray(flags, dtype=np.float32)
+    return float(lib().orc_found_inf_combine(_vp(_ptr(a)), _c_i32(a.size)))
+
+
+def scaler_update(scale: float, growth_tracker: int, found_inf: float, growth: float = 2.0, backoff: float = 0.5,
+                  growth_interval: int = 2000):
+    s = _c_f32(scale)
+    t = _c_i32(growth_tracker)
+    lib().orc_scaler_update(ctypes.byref(s), ctypes.byref(t), _c_f32(found_inf), _c_f32(growth), _c_f32(backoff),
+                            _c_i32(growth_interval))
+    return float(s.value), int(t.value)
 
 
 # ------------------------------------------------------------------ Adam

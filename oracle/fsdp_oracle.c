@@ -286,6 +286,155 @@ void orc_accumulate_bf16(float *acc, const uint16_t *add, int64_t n)
     for (int64_t k = 0; k < n; ++k) acc[k] = acc[k] + bf16_to_f32(add[k]);
 }
 
+/* ------------------------------------------- fp16 and the gradient scaler */
+
+/* Sec. 4.4 names FP16 as the other common low precision.  binary32 -> binary16,
+ * round to nearest even, written from the two formats' definitions: overflow
+ * goes to Inf, results below the smallest normal half are rounded onto the
+ * subnormal grid (quantum 2^-24), NaN keeps sign and the top ten payload bits
+ * and is made quiet.
+ * Pins: numpy's float32 -> float16 conversion over every non-NaN pattern, hand
+ * vectors, exact nearest-neighbour search. */
+uint16_t orc_f16_rne(uint32_t u)
+{
+    uint32_t sign = (u >> 16) & 0x8000u;
+    uint32_t exp = (u >> 23) & 0xFFu;
+    uint32_t man = u & 0x007FFFFFu;
+    if (exp == 0xFFu) {
+        if (man == 0) return (uint16_t)(sign | 0x7C00u);
+        return (uint16_t)(sign | 0x7C00u | 0x0200u | (man >> 13));
+    }
+    if (exp == 0) return (uint16_t)sign;                 /* binary32 zero / subnormal: far below 2^-25 */
+    int32_t e = (int32_t)exp - 127;
+    if (e > 15) return (uint16_t)(sign | 0x7C00u);
+    if (e >= -14) {
+        uint32_t h = ((uint32_t)(e + 15) << 10) | (man >> 13);
+        uint32_t rem = man & 0x1FFFu;
+        if (rem > 0x1000u || (rem == 0x1000u && (h & 1u))) h += 1;   /* a carry walks into the exponent, up to Inf */
+        return (uint16_t)(sign | h);
+    }
+    uint32_t m = man | 0x00800000u;                      /* 1.man as a 24-bit integer, value m * 2^(e-23) */
+    int32_t shift = -1 - e;                              /* to units of 2^-24 */
+    if (shift > 31) return (uint16_t)sign;
+    uint32_t h = m >> shift;
+    uint32_t rem = m & ((1u << shift) - 1u);
+    uint32_t half = 1u << (shift - 1);
+    if (rem > half || (rem == half && (h & 1u))) h += 1;
+    return (uint16_t)(sign | h);
+}
+
+void orc_cast_f16(const float *x, int64_t n, uint16_t *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < n; ++k) {
+        uint32_t u;
+        memcpy(&u, &x[k], 4);
+        y[k] = orc_f16_rne(u);
+    }
+}
+
+void orc_cast_f16_bits(uint32_t first, int64_t count, uint16_t *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < count; ++k) y[k] = orc_f16_rne(first + (uint32_t)k);
+}
+
+/* binary16 -> binary32, exact (every half is representable).
+ * Pin: numpy's float16 -> float32 over all 65536 patterns. */
+static inline float f16_to_f32(uint16_t h)
+{
+    uint32_t sign = ((uint32_t)h & 0x8000u) << 16;
+    uint32_t exp = (h >> 10) & 0x1Fu;
+    uint32_t man = h & 0x03FFu;
+    uint32_t u;
+    if (exp == 0x1Fu) {
+        u = sign | 0x7F800000u | (man << 13);
+    } else if (exp != 0) {
+        u = sign | ((exp + 112u) << 23) | (man << 13);
+    } else if (man == 0) {
+        u = sign;
+    } else {                                              /* subnormal half: man * 2^-24, normalise */
+        int32_t e = -1;
+        do { man <<= 1; ++e; } while ((man & 0x0400u) == 0);
+        u = sign | ((uint32_t)(112 - e) << 23) | ((man & 0x03FFu) << 13);
+    }
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+void orc_upcast_f16(const uint16_t *h, int64_t n, float *y)
+{
+    for (int64_t k = 0; k < n; ++k) y[k] = f16_to_f32(h[k]);
+}
+
+void orc_unshard_f16(const float *const *shards, int32_t W, int64_t S, uint16_t *flat_lp)
+{
+    for (int32_t w = 0; w < W; ++w)
+        orc_cast_f16(shards[w], S, flat_lp + (int64_t)w * S);
+}
+
+void orc_reduce_slices_f16(const uint16_t *const *slices, int32_t W, int64_t S,
+                           float pre, float post, float *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < S; ++k) {
+        float acc = f16_to_f32(slices[0][k]) / pre;
+        for (int32_t w = 1; w < W; ++w) acc = acc + f16_to_f32(slices[w][k]) / pre;
+        out[k] = acc / post;
+    }
+}
+
+/* Sec. 4.4, sharded gradient scaler.  The loss is multiplied by `scale`, so the
+ * reduced gradient shard is multiplied by inv_scale = 1/scale (one binary32
+ * multiplication per element) and checked: found_inf is 1 when any element of
+ * the reduced shard is Inf or NaN (the check looks at the value before the
+ * multiplication, as the gradient scaler the paper cites does).  Each rank sees
+ * only its shard, so the flags of all ranks are combined (a max) before any
+ * rank decides to step; a scaler that looked at the local shard only would let
+ * some ranks step and others skip.  Returns this shard's flag.
+ * Pins: torch's non-finite-check-and-unscale routine on the CPU; the combined
+ * flag equals the flag of the whole unsharded gradient. */
+float orc_unscale_check(float *g, int64_t n, float inv_scale)
+{
+    float found = 0.0f;
+    for (int64_t k = 0; k < n; ++k) {
+        if (isinf(g[k]) || isnan(g[k])) found = 1.0f;
+        g[k] = g[k] * inv_scale;
+    }
+    return found;
+}
+
+/* combine of the per-rank flags: every rank ends up with the maximum */
+float orc_found_inf_combine(const float *flags, int32_t W)
+{
+    float m = 0.0f;
+    for (int32_t w = 0; w < W; ++w)
+        if (flags[w] > m) m = flags[w];
+    return m;
+}
+
+/* Scale update of dynamic loss scaling (the gradient scaler the paper cites):
+ * after a step with a non-finite gradient the scale is multiplied by backoff
+ * and the streak of good steps restarts; after growth_interval good steps in a
+ * row it is multiplied by growth.
+ * Pin: torch's scale-update routine on the CPU, over a random flag sequence. */
+void orc_scaler_update(float *scale, int32_t *growth_tracker, float found_inf,
+                       float growth, float backoff, int32_t growth_interval)
+{
+    if (found_inf != 0.0f) {
+        *scale = *scale * backoff;
+        *growth_tracker = 0;
+    } else {
+        int32_t t = *growth_tracker + 1;
+        if (t == growth_interval) {
+            *scale = *scale * growth;
+            t = 0;
+        }
+        *growth_tracker = t;
+    }
+}
+
 /* ------------------------------------------------------------------ Adam */
 
 /* Sec. 5.4 names Adam with its two optimizer states per parameter, kept

@@ -10,6 +10,7 @@ import pytest
 import oracle
 import test_oracle_adam as t_adam
 import test_oracle_cast as t_cast
+import test_oracle_fp16_scaler as t_f16
 import test_oracle_hybrid_accum as t_hyb
 import test_oracle_layout as t_layout
 import test_oracle_reduce as t_reduce
@@ -46,6 +47,20 @@ MUTANTS = [
     ("hybrid_post_per_group", "outer = (i == 0) ? inner : outer + inner;", "outer = (i == 0) ? inner / post : outer + inner / post;"),
     ("accumulate_overwrites", "acc[k] = acc[k] + add[k];", "acc[k] = add[k];"),
     ("accumulate_bf16_shift", "acc[k] = acc[k] + bf16_to_f32(add[k]);", "acc[k] = acc[k] + (float)add[k];"),
+    ("f16_half_up", "if (rem > 0x1000u || (rem == 0x1000u && (h & 1u))) h += 1;   /* a carry", "if (rem >= 0x1000u) h += 1;   /* a carry"),
+    ("f16_truncates", "if (rem > 0x1000u || (rem == 0x1000u && (h & 1u))) h += 1;   /* a carry", "/* a carry"),
+    ("f16_subnormal_shift", "int32_t shift = -1 - e;", "int32_t shift = -2 - e;"),
+    ("f16_flushes_subnormals", "uint32_t m = man | 0x00800000u;", "return (uint16_t)sign; uint32_t m = man | 0x00800000u;"),
+    ("f16_overflow_saturates", "if (e > 15) return (uint16_t)(sign | 0x7C00u);", "if (e > 15) return (uint16_t)(sign | 0x7BFFu);"),
+    ("f16_upcast_bias", "u = sign | ((exp + 112u) << 23) | (man << 13);", "u = sign | ((exp + 111u) << 23) | (man << 13);"),
+    ("f16_upcast_subnormal", "u = sign | ((uint32_t)(112 - e) << 23) | ((man & 0x03FFu) << 13);", "u = sign | ((uint32_t)(113 - e) << 23) | ((man & 0x03FFu) << 13);"),
+    ("unscale_no_check", "if (isinf(g[k]) || isnan(g[k])) found = 1.0f;", ""),
+    ("unscale_misses_nan", "if (isinf(g[k]) || isnan(g[k])) found = 1.0f;", "if (isinf(g[k])) found = 1.0f;"),
+    ("unscale_divides_by_inv", "g[k] = g[k] * inv_scale;", "g[k] = g[k] / inv_scale;"),
+    ("combine_takes_first_rank", "if (flags[w] > m) m = flags[w];", "if (w == 0) m = flags[w];"),
+    ("scaler_backoff_growth_swapped", "*scale = *scale * backoff;", "*scale = *scale * growth;"),
+    ("scaler_tracker_not_reset", "*scale = *scale * backoff;\n        *growth_tracker = 0;", "*scale = *scale * backoff;"),
+    ("scaler_grows_every_step", "if (t == growth_interval) {", "if (t >= 1) {"),
     ("adam_eps_inside_sqrt", "sqrtf(vk) / sqrt_bc2 + eps;", "sqrtf(vk + eps) / sqrt_bc2;"),
     ("adam_no_bias_correction2", "float sqrt_bc2 = sqrtf(bc2);", "float sqrt_bc2 = 1.0f;"),
     ("adam_no_bias_correction1", "float step_size = lr / bc1;", "float step_size = lr;"),
@@ -85,6 +100,13 @@ def _pins():
         t_hyb.test_hybrid_bf16_upcast_exact,
         t_hyb.test_accumulate_is_float32_addition,
         t_hyb.test_accumulation_with_and_without_communication_agree_on_integers,
+        t_f16.test_f16_hand_vectors,
+        t_f16.test_f16_nearest_neighbour_exact,
+        t_f16.test_f16_upcast_all_patterns_against_numpy,
+        t_f16.test_f16_reduce_is_upcast_then_fp32_reduce,
+        t_f16.test_unscale_check_against_torch,
+        t_f16.test_sharded_flag_equals_flag_of_the_whole_gradient,
+        t_f16.test_scaler_update_against_torch,
         t_adam.test_closed_form_first_step_from_zero_state,
         lambda: t_adam.test_single_step_matches_torch_adam_float64(5),
         t_adam.test_checkpoint_resume,
@@ -95,9 +117,8 @@ def _pins():
 
 def _load(path):
     lib = ctypes.CDLL(path)
-    lib.orc_bf16_rne.restype = ctypes.c_uint16
-    lib.orc_bf16_rne.argtypes = [ctypes.c_uint32]
     lib.orc_num_threads.restype = ctypes.c_int
+    oracle._configure(lib)
     return lib
 
 
