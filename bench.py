@@ -304,19 +304,29 @@ def next_rows(args, wl, F, torch, workloads):
     lay = F.fsdp_layout_init(unit.shapes, W)
     S, P, N = lay.shard, lay.padded, lay.numel
     G = 2 if 2 * W <= 64 else 1
-    nsets = max(1, min(3, int(100e9 // (W * G * P * gb + 4 * P))))   # rotate buffer sets while HBM allows
+    nsets = max(1, min(3, int(100e9 // (W * G * P * gb + 2 * W * P + 14 * P))))   # rotate buffer sets while HBM allows
     pre, post = F.fsdp_default_divide_factors(W * G)
+    pre_w, post_w = F.fsdp_default_divide_factors(W)
     sets = []
     for i in range(nsets):
         grads = [workloads.gen_rank_grad(P, N, w, i, wl.grad_dtype, device="cuda") for w in range(W * G)]
-        sets.append({"grads": F.PtrArray(grads), "flat": F.PtrArray(grads[:W]),
-                     "out": torch.zeros(S, device="cuda"), "acc": torch.zeros(P, device="cuda")})
+        d = {"grads": F.PtrArray(grads), "flat": F.PtrArray(grads[:W]),
+             "out": torch.zeros(S, device="cuda"), "acc": torch.zeros(P, device="cuda")}
+        # FP16 path (Sec. 4.4): fp16 gradient buffers of the W ranks, fp32 shards, an fp16 flat buffer, the scaler flag
+        d["g16"] = F.PtrArray([g.to(torch.float16) for g in grads[:W]])
+        d["shards"] = F.PtrArray([torch.randn(S, device="cuda") * 0.02 for _ in range(W)])
+        d["flat16"] = torch.empty(P, dtype=torch.float16, device="cuda")
+        d["flag"] = torch.zeros(1, device="cuda")
+        sets.append(d)
     rows = {
         "reduce_scatter_hybrid": (lambda d: F.fsdp_reduce_scatter_hybrid(lay, d["grads"], G, 0, pre, post, d["out"]),
                                   gb * S * W * G + 4 * S),
         "reduce_scatter_accumulate": (lambda d: F.fsdp_reduce_scatter_accumulate(lay, d["flat"], 0, pre, post, d["out"]),
                                       gb * P + 8 * S),
         "grad_accumulate": (lambda d: F.fsdp_grad_accumulate(lay, d["acc"], d["flat"].tensors[0]), (8 + gb) * P),
+        "unshard_fp16": (lambda d: F.fsdp_unshard(lay, d["shards"], d["flat16"]), 6 * P),
+        "reduce_scatter_unscale_fp16": (lambda d: F.fsdp_reduce_scatter_unscale(
+            lay, d["g16"], 0, pre_w, post_w, 1.0 / 1024.0, d["out"], d["flag"]), 2 * P + 4 * S),
     }
     out = {}
     reps = 30

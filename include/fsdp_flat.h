@@ -36,7 +36,8 @@ extern "C" {
 
 typedef struct fsdp_layout fsdp_layout_t;   /* opaque, library-owned, host memory */
 
-typedef enum { FSDP_F32 = 0, FSDP_BF16 = 1 } fsdp_dtype_t;
+/* FSDP_F16 is IEEE binary16; both 16-bit kinds travel as uint16_t bit patterns. */
+typedef enum { FSDP_F32 = 0, FSDP_BF16 = 1, FSDP_F16 = 2 } fsdp_dtype_t;
 
 typedef enum {
     FSDP_OK = 0,
@@ -96,7 +97,9 @@ int fsdp_flatten_shard(const fsdp_layout_t* layout, const void* const* param_ptr
  * flat_out:   dev, P elements of out_dtype (written, pad included).
  * FSDP_BF16: flat_out[w * S + k] = bf16_rne(shard_w[k]) -- round to nearest,
  * ties to even; NaN keeps sign and top payload bits and is made quiet;
- * denormals are rounded, not flushed.  FSDP_F32: plain gather copy. */
+ * denormals are rounded, not flushed.  FSDP_F16: the same with IEEE binary16
+ * (overflow gives Inf, small results land on the subnormal grid).
+ * FSDP_F32: plain gather copy. */
 int fsdp_unshard(const fsdp_layout_t* layout, const float* const* shard_ptrs, void* flat_out,
                  fsdp_dtype_t out_dtype, void* hip_stream);
 
@@ -106,7 +109,7 @@ int fsdp_unshard(const fsdp_layout_t* layout, const float* const* shard_ptrs, vo
  *            are read.
  * grad_shard_out: dev fp32 [S] (written).
  * out[k] = ((x_0 / pre) + (x_1 / pre) + ... + (x_{W-1} / pre)) / post with
- * x_w = (float) grad_w[rank * S + k] (bf16 upcast is exact); strictly in rank
+ * x_w = (float) grad_w[rank * S + k] (bf16 and fp16 upcasts are exact); strictly in rank
  * order, one binary32 division and addition per rank, no fused multiply-add,
  * accumulator initialised from rank 0's term.  pre, post: finite and > 0. */
 int fsdp_reduce_scatter_local(const fsdp_layout_t* layout, const void* const* grad_ptrs,
@@ -189,7 +192,7 @@ int fsdp_grad_accumulate(const fsdp_layout_t* layout, float* grad_acc, const voi
                          fsdp_dtype_t add_dtype, void* hip_stream);
 
 /* ---- Sec. 4.4: the low-precision copy of the local shard, kept per rank -----
- * fsdp_cast_shard: lp_shard_out[k] = bf16_rne(shard[k]) for the S elements of
+ * fsdp_cast_shard: lp_shard_out[k] = cast(shard[k]) (bf16 or fp16) for the S elements of
  * one fp32 shard (the "full-to-low-precision cast per FlatParameter").
  * fsdp_reduce_scatter_adam_fused can also write it (p_lp_out) while the updated
  * shard is still in registers, which saves this pass in every later iteration.
@@ -197,9 +200,44 @@ int fsdp_grad_accumulate(const fsdp_layout_t* layout, float* grad_acc, const voi
  * lp_shard_w[k]; lp_shard_ptrs: host [W] of dev bf16 shards (S each); flat_out:
  * dev bf16 [P].  Together they give exactly fsdp_unshard(..., FSDP_BF16). */
 int fsdp_cast_shard(const fsdp_layout_t* layout, const float* shard, void* lp_shard_out,
-                    void* hip_stream);
+                    fsdp_dtype_t lp_dtype /* FSDP_BF16 or FSDP_F16 */, void* hip_stream);
 int fsdp_unshard_lp(const fsdp_layout_t* layout, const void* const* lp_shard_ptrs, void* flat_out,
                     void* hip_stream);
+
+/* ---- Sec. 4.4: FP16 training and the sharded gradient scaler ----------------
+ * The loss is multiplied by `scale`, so gradients arrive scaled.  Each rank
+ * sees only its shard of the reduced gradient, so the non-finite check must be
+ * combined over all ranks before any rank steps (a local scaler would let some
+ * ranks step and others skip).  All state lives on the device; nothing here
+ * needs a host round trip.
+ *
+ * fsdp_reduce_scatter_unscale: fsdp_reduce_scatter_local, then for each element
+ * of the result: if it is Inf or NaN, *found_inf = 1.0f (the flag is only ever
+ * set, the caller clears it before the first unit); then it is multiplied by
+ * inv_scale (= 1 / scale, finite, > 0) and stored.  found_inf: dev, one float.
+ * Requires W <= FSDP_MAX_RANKS_PER_LAUNCH.
+ * fsdp_found_inf_combine: the all-reduce (max) of the ranks' flags:
+ * found_inf_ptrs is a host array of num_ranks (<= 64) dev flags, each of which
+ * receives the maximum.  (Simulated ranks may also simply share one flag.)
+ * fsdp_shard_adam_step_guarded: fsdp_shard_adam_step that reads *found_inf on
+ * the device and leaves p, m, v untouched when it is non-zero.
+ * fsdp_grad_scaler_update: dynamic loss scaling on the device: *found_inf != 0
+ * -> *scale *= backoff_factor, *growth_tracker = 0; otherwise the tracker is
+ * incremented and, on reaching growth_interval, *scale *= growth_factor and the
+ * tracker restarts.  Requires growth_factor > 1, 0 < backoff_factor < 1,
+ * growth_interval >= 1. */
+int fsdp_reduce_scatter_unscale(const fsdp_layout_t* layout, const void* const* grad_ptrs,
+                                fsdp_dtype_t grad_dtype, int32_t rank, float pre_div, float post_div,
+                                float inv_scale, float* grad_shard_out, float* found_inf,
+                                void* hip_stream);
+int fsdp_found_inf_combine(float* const* found_inf_ptrs, int32_t num_ranks, void* hip_stream);
+int fsdp_shard_adam_step_guarded(const fsdp_layout_t* layout, float* p_shard, const float* g_shard,
+                                 float* exp_avg, float* exp_avg_sq, int64_t step, float lr,
+                                 float beta1, float beta2, float eps, const float* found_inf,
+                                 void* hip_stream);
+int fsdp_grad_scaler_update(float* scale, int32_t* growth_tracker, const float* found_inf,
+                            float growth_factor, float backoff_factor, int32_t growth_interval,
+                            void* hip_stream);
 
 /* Last hipError_t seen by this thread inside the library (0 if none). */
 int fsdp_last_hip_error(void);

@@ -6,6 +6,7 @@ memory and streams only.
 """
 from .binding import (  # noqa: F401
     FSDP_BF16,
+    FSDP_F16,
     FSDP_F32,
     FsdpError,
     Layout,
@@ -13,6 +14,8 @@ from .binding import (  # noqa: F401
     fsdp_cast_shard,
     fsdp_default_divide_factors,
     fsdp_flatten_shard,
+    fsdp_found_inf_combine,
+    fsdp_grad_scaler_update,
     fsdp_layout_init,
     fsdp_reduce_scatter_adam_fused,
     fsdp_reduce_scatter_adam_prefetch_unshard,
@@ -20,7 +23,9 @@ from .binding import (  # noqa: F401
     fsdp_reduce_scatter_accumulate,
     fsdp_reduce_scatter_hybrid,
     fsdp_reduce_scatter_local,
+    fsdp_reduce_scatter_unscale,
     fsdp_shard_adam_step,
+    fsdp_shard_adam_step_guarded,
     fsdp_unshard,
     fsdp_unshard_lp,
     fsdp_view_ptr,

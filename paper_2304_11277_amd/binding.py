@@ -16,6 +16,7 @@ import torch
 
 FSDP_F32 = 0
 FSDP_BF16 = 1
+FSDP_F16 = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfsdp_flat.so")
@@ -64,7 +65,11 @@ _SIGNATURES = {
     "fsdp_reduce_scatter_hybrid": [_vp, _pp, ctypes.c_int, _i32, _i32, _f32, _f32, _vp, _vp],
     "fsdp_reduce_scatter_accumulate": [_vp, _pp, ctypes.c_int, _i32, _f32, _f32, _vp, _vp],
     "fsdp_grad_accumulate": [_vp, _vp, _vp, ctypes.c_int, _vp],
-    "fsdp_cast_shard": [_vp, _vp, _vp, _vp],
+    "fsdp_cast_shard": [_vp, _vp, _vp, ctypes.c_int, _vp],
+    "fsdp_reduce_scatter_unscale": [_vp, _pp, ctypes.c_int, _i32, _f32, _f32, _f32, _vp, _vp, _vp],
+    "fsdp_found_inf_combine": [_pp, _i32, _vp],
+    "fsdp_shard_adam_step_guarded": [_vp, _vp, _vp, _vp, _vp, _i64, _f32, _f32, _f32, _f32, _vp, _vp],
+    "fsdp_grad_scaler_update": [_vp, _vp, _vp, _f32, _f32, _i32, _vp],
     "fsdp_unshard_lp": [_vp, _pp, _vp, _vp],
     "fsdp_last_hip_error": [],
 }
@@ -199,12 +204,14 @@ def fsdp_default_divide_factors(world_size: int) -> Tuple[float, float]:
     return pre.value, post.value
 
 
+_DTYPES = {torch.float32: FSDP_F32, torch.bfloat16: FSDP_BF16, torch.float16: FSDP_F16}
+
+
 def _flat_dtype(t: torch.Tensor) -> int:
-    if t.dtype == torch.float32:
-        return FSDP_F32
-    if t.dtype == torch.bfloat16:
-        return FSDP_BF16
-    raise TypeError(f"unsupported dtype {t.dtype}")
+    try:
+        return _DTYPES[t.dtype]
+    except KeyError:
+        raise TypeError(f"unsupported dtype {t.dtype}") from None
 
 
 def fsdp_view_ptr(layout: Layout, flat_base: torch.Tensor, i: int) -> int:
@@ -248,10 +255,10 @@ def _grad_table(layout: Layout, grad_ptrs, num_groups: int = 1) -> Tuple[PtrArra
     else:
         grad_ptrs = list(grad_ptrs)
         gdt = grad_ptrs[0].dtype
-    if gdt not in (torch.float32, torch.bfloat16):
+    if gdt not in _DTYPES:
         raise TypeError(f"grad dtype {gdt} not supported")
     tab = _ptr_table(grad_ptrs, gdt, layout.padded, layout.world_size * num_groups, "grad_ptrs")
-    return tab, (FSDP_F32 if gdt == torch.float32 else FSDP_BF16)
+    return tab, _DTYPES[gdt]
 
 
 def fsdp_reduce_scatter_local(layout: Layout, grad_ptrs, rank: int, pre_div: float, post_div: float,
@@ -341,13 +348,62 @@ def fsdp_grad_accumulate(layout: Layout, grad_acc: torch.Tensor, grad_add: torch
 
 def fsdp_cast_shard(layout: Layout, shard: torch.Tensor, lp_shard_out: torch.Tensor, stream=None) -> None:
     _dev_tensor(shard, torch.float32, layout.shard, "shard")
-    _dev_tensor(lp_shard_out, torch.bfloat16, layout.shard, "lp_shard_out")
+    if lp_shard_out.dtype not in (torch.bfloat16, torch.float16):
+        raise TypeError("lp_shard_out must be bfloat16 or float16")
+    _dev_tensor(lp_shard_out, lp_shard_out.dtype, layout.shard, "lp_shard_out")
     _check("fsdp_cast_shard", lib().fsdp_cast_shard(layout.handle, _vp(shard.data_ptr()),
-                                                   _vp(lp_shard_out.data_ptr()), _stream_handle(stream)))
+                                                   _vp(lp_shard_out.data_ptr()), _flat_dtype(lp_shard_out),
+                                                   _stream_handle(stream)))
 
 
 def fsdp_unshard_lp(layout: Layout, lp_shard_ptrs, flat_out: torch.Tensor, stream=None) -> None:
-    shards = _ptr_table(lp_shard_ptrs, torch.bfloat16, layout.shard, layout.world_size, "lp_shard_ptrs")
-    _dev_tensor(flat_out, torch.bfloat16, layout.padded, "flat_out")
+    if flat_out.dtype not in (torch.bfloat16, torch.float16):
+        raise TypeError("flat_out must be bfloat16 or float16")
+    shards = _ptr_table(lp_shard_ptrs, flat_out.dtype, layout.shard, layout.world_size, "lp_shard_ptrs")
+    _dev_tensor(flat_out, flat_out.dtype, layout.padded, "flat_out")
     _check("fsdp_unshard_lp", lib().fsdp_unshard_lp(layout.handle, shards.array, _vp(flat_out.data_ptr()),
                                                    _stream_handle(stream)))
+
+
+def fsdp_reduce_scatter_unscale(layout: Layout, grad_ptrs, rank: int, pre_div: float, post_div: float,
+                                inv_scale: float, grad_shard_out: torch.Tensor, found_inf: torch.Tensor,
+                                stream=None) -> None:
+    tab, gdt = _grad_table(layout, grad_ptrs)
+    _dev_tensor(grad_shard_out, torch.float32, layout.shard, "grad_shard_out")
+    _dev_tensor(found_inf, torch.float32, 1, "found_inf")
+    _check("fsdp_reduce_scatter_unscale",
+           lib().fsdp_reduce_scatter_unscale(layout.handle, tab.array, gdt, int(rank), float(pre_div), float(post_div),
+                                             float(inv_scale), _vp(grad_shard_out.data_ptr()),
+                                             _vp(found_inf.data_ptr()), _stream_handle(stream)))
+
+
+def fsdp_found_inf_combine(found_inf_ptrs, stream=None) -> None:
+    flags = list(found_inf_ptrs)
+    for i, f in enumerate(flags):
+        _dev_tensor(f, torch.float32, 1, f"found_inf_ptrs[{i}]")
+    tab = PtrArray(flags)
+    _check("fsdp_found_inf_combine", lib().fsdp_found_inf_combine(tab.array, len(flags), _stream_handle(stream)))
+
+
+def fsdp_shard_adam_step_guarded(layout: Layout, p_shard, g_shard, exp_avg, exp_avg_sq, step: int, lr: float,
+                                 beta1: float, beta2: float, eps: float, found_inf: torch.Tensor, stream=None) -> None:
+    S = layout.shard
+    ptrs = [_dev_tensor(t, torch.float32, S, n) for t, n in
+            ((p_shard, "p_shard"), (g_shard, "g_shard"), (exp_avg, "exp_avg"), (exp_avg_sq, "exp_avg_sq"))]
+    _dev_tensor(found_inf, torch.float32, 1, "found_inf")
+    _check("fsdp_shard_adam_step_guarded",
+           lib().fsdp_shard_adam_step_guarded(layout.handle, *[_vp(x) for x in ptrs], int(step), float(lr),
+                                              float(beta1), float(beta2), float(eps), _vp(found_inf.data_ptr()),
+                                              _stream_handle(stream)))
+
+
+def fsdp_grad_scaler_update(scale: torch.Tensor, growth_tracker: torch.Tensor, found_inf: torch.Tensor,
+                            growth_factor: float = 2.0, backoff_factor: float = 0.5, growth_interval: int = 2000,
+                            stream=None) -> None:
+    _dev_tensor(scale, torch.float32, 1, "scale")
+    _dev_tensor(growth_tracker, torch.int32, 1, "growth_tracker")
+    _dev_tensor(found_inf, torch.float32, 1, "found_inf")
+    _check("fsdp_grad_scaler_update",
+           lib().fsdp_grad_scaler_update(_vp(scale.data_ptr()), _vp(growth_tracker.data_ptr()),
+                                         _vp(found_inf.data_ptr()), float(growth_factor), float(backoff_factor),
+                                         int(growth_interval), _stream_handle(stream)))

@@ -65,6 +65,50 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return bf16_rne(f2u(lo)) | (bf16_rne(f2u(hi)) << 16);
 }
 
+// fp32 -> fp16 (IEEE binary16), round to nearest even: the hardware conversion
+// (overflow to Inf, subnormal results rounded, not flushed), except that NaN is
+// mapped by rule: sign kept, top ten payload bits kept, made quiet.
+__device__ __forceinline__ uint32_t f16_rne(uint32_t u)
+{
+    const bool is_nan = (u & 0x7FFFFFFFu) > 0x7F800000u;
+    const _Float16 h = static_cast<_Float16>(u2f(u));
+    const uint32_t r = static_cast<uint32_t>(__builtin_bit_cast(uint16_t, h));
+    return is_nan ? (((u >> 16) & 0x8000u) | 0x7E00u | ((u >> 13) & 0x03FFu)) : r;
+}
+// exact fp16 -> fp32
+__device__ __forceinline__ float f16_to_f32(uint32_t h16)
+{
+    return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h16)));
+}
+
+// element kinds of 16-bit / 32-bit buffers (values of fsdp_dtype_t)
+constexpr int kF32 = FSDP_F32, kBF16 = FSDP_BF16, kF16 = FSDP_F16;
+
+template <int LP>   // LP = kBF16 or kF16
+__device__ __forceinline__ uint32_t cast_lp(float x)
+{
+    if constexpr (LP == kF16) return f16_rne(f2u(x));
+    else return bf16_rne(f2u(x));
+}
+template <int LP>
+__device__ __forceinline__ uint32_t pack_lp2(float lo, float hi)
+{
+    return cast_lp<LP>(lo) | (cast_lp<LP>(hi) << 16);
+}
+// exact upcast of the low / high half of a packed pair of 16-bit values
+template <int GT>
+__device__ __forceinline__ float up_lo(uint32_t pair)
+{
+    if constexpr (GT == kF16) return f16_to_f32(pair & 0xFFFFu);
+    else return u2f(pair << 16);
+}
+template <int GT>
+__device__ __forceinline__ float up_hi(uint32_t pair)
+{
+    if constexpr (GT == kF16) return f16_to_f32(pair >> 16);
+    else return u2f(pair & 0xFFFF0000u);
+}
+
 // number of elements (of esize bytes) from p up to the next 16-byte boundary
 __device__ __forceinline__ int64_t head_elems(const void* p, int esize, int64_t n)
 {
@@ -79,7 +123,8 @@ __device__ __forceinline__ int64_t head_elems(const void* p, int esize, int64_t 
 // tile b % tiles.  A tile is kBlock * U destination vectors of 16 bytes.
 // ---------------------------------------------------------------------------
 // bid = index of the workgroup among the unshard workgroups of the launch
-__device__ __forceinline__ void unshard_bf16_body(const PtrTable& shards, int64_t S, uint16_t* __restrict__ out_base,
+template <int LP>
+__device__ __forceinline__ void unshard_lp_body(const PtrTable& shards, int64_t S, uint16_t* __restrict__ out_base,
                                                   int32_t tiles_per_shard, uint32_t bid)
 {
     const int32_t w = bid / tiles_per_shard;
@@ -95,26 +140,27 @@ __device__ __forceinline__ void unshard_bf16_body(const PtrTable& shards, int64_
         const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(s));
         const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(s + 4));
         u32x4 o;
-        o.x = pack_bf16x2(a.x, a.y);
-        o.y = pack_bf16x2(a.z, a.w);
-        o.z = pack_bf16x2(b.x, b.y);
-        o.w = pack_bf16x2(b.z, b.w);
+        o.x = pack_lp2<LP>(a.x, a.y);
+        o.y = pack_lp2<LP>(a.z, a.w);
+        o.z = pack_lp2<LP>(b.x, b.y);
+        o.w = pack_lp2<LP>(b.z, b.w);
         __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(dst + head + (c << 3)));
     }
     if (tile == 0) {   // ragged head and tail of this shard: at most 7 elements each
         const int64_t tail0 = head + (nvec << 3);
         const int64_t ntail = S - tail0;
         const int t = threadIdx.x;
-        if (t < head) dst[t] = static_cast<uint16_t>(bf16_rne(f2u(src[t])));
-        if (t >= 64 && t - 64 < ntail) dst[tail0 + t - 64] = static_cast<uint16_t>(bf16_rne(f2u(src[tail0 + t - 64])));
+        if (t < head) dst[t] = static_cast<uint16_t>(cast_lp<LP>(src[t]));
+        if (t >= 64 && t - 64 < ntail) dst[tail0 + t - 64] = static_cast<uint16_t>(cast_lp<LP>(src[tail0 + t - 64]));
     }
 }
 
-__global__ __launch_bounds__(kBlock) void unshard_bf16_kernel(PtrTable shards, int64_t S,
-                                                               uint16_t* __restrict__ out_base,
-                                                               int32_t tiles_per_shard)
+template <int LP>
+__global__ __launch_bounds__(kBlock) void unshard_lp_kernel(PtrTable shards, int64_t S,
+                                                             uint16_t* __restrict__ out_base,
+                                                             int32_t tiles_per_shard)
 {
-    unshard_bf16_body(shards, S, out_base, tiles_per_shard, blockIdx.x);
+    unshard_lp_body<LP>(shards, S, out_base, tiles_per_shard, blockIdx.x);
 }
 
 __global__ __launch_bounds__(kBlock) void unshard_f32_kernel(PtrTable shards, int64_t S,
@@ -297,11 +343,11 @@ __device__ __forceinline__ void adam_update4(f32x4& p, const float* g, f32x4& m,
     v = f32x4{vv[0], vv[1], vv[2], vv[3]};
 }
 
-template <bool BF16>
+template <int GT>
 __device__ __forceinline__ float load_grad(const void* base, int64_t k)
 {
-    if (BF16) return u2f(static_cast<uint32_t>(static_cast<const uint16_t*>(base)[k]) << 16);
-    return static_cast<const float*>(base)[k];
+    if constexpr (GT == kF32) return static_cast<const float*>(base)[k];
+    else return up_lo<GT>(static_cast<uint32_t>(static_cast<const uint16_t*>(base)[k]));
 }
 
 struct RsArgs {
@@ -312,6 +358,9 @@ struct RsArgs {
     int32_t group;        // hybrid sharding: ranks per sharded group (inner sums are folded into an
                           // outer sum after every `group` ranks); 0 = one flat sum
     int32_t accum;        // 1: gradient accumulation, the result is added to what out[] holds
+    int32_t unscale;      // 1: gradient scaler: flag non-finite results in *found_inf, then multiply by inv_scale
+    float inv_scale;
+    float* found_inf;     // one float, set to 1.0f (never cleared) when a non-finite value is seen
     float pre_c;          // pre (kPreDiv) or 1/pre (kPreMul)
     float post_c;         // post, or 1/post when post_mul
     int64_t S;
@@ -334,12 +383,12 @@ __device__ __forceinline__ float post_scale(float x, const RsArgs& a)
 // pointer, so the loads need no predicate; the adds of the padding are skipped.
 constexpr int kGroup = 8;
 
-template <bool BF16>
+template <int GT>
 __device__ __forceinline__ void load_ranks(const PtrTable& grads, int32_t w0, int64_t k, u32x4 (&x)[kGroup])
 {
 #pragma unroll
     for (int j = 0; j < kGroup; ++j) {
-        if constexpr (BF16)
+        if constexpr (GT != kF32)
             x[j] = __builtin_nontemporal_load(
                 reinterpret_cast<const u32x4_a2*>(static_cast<const uint16_t*>(grads.p[w0 + j]) + k));
         else
@@ -372,7 +421,7 @@ __device__ __forceinline__ void fold_group(RankSum<E>& s, int32_t group)
 }
 
 // adds x[0..n) in rank order; E = 4 elements per vector for fp32 gradients, 8 for bf16
-template <bool BF16, int PRE, int E>
+template <int GT, int PRE, int E>
 __device__ __forceinline__ void add_ranks(const u32x4 (&x)[kGroup], int32_t n, float pre_c, int32_t group,
                                           RankSum<E>& s)
 {
@@ -380,11 +429,11 @@ __device__ __forceinline__ void add_ranks(const u32x4 (&x)[kGroup], int32_t n, f
     for (int j = 0; j < kGroup; ++j) {
         if (j < n) {   // uniform
             float t[E];
-            if constexpr (BF16) {   // exact upcast: the bf16 pattern is the top half of the fp32 one
-                t[0] = u2f(x[j].x << 16); t[1] = u2f(x[j].x & 0xFFFF0000u);
-                t[2] = u2f(x[j].y << 16); t[3] = u2f(x[j].y & 0xFFFF0000u);
-                t[4] = u2f(x[j].z << 16); t[5] = u2f(x[j].z & 0xFFFF0000u);
-                t[6] = u2f(x[j].w << 16); t[7] = u2f(x[j].w & 0xFFFF0000u);
+            if constexpr (GT != kF32) {   // exact upcast of eight 16-bit gradients
+                t[0] = up_lo<GT>(x[j].x); t[1] = up_hi<GT>(x[j].x);
+                t[2] = up_lo<GT>(x[j].y); t[3] = up_hi<GT>(x[j].y);
+                t[4] = up_lo<GT>(x[j].z); t[5] = up_hi<GT>(x[j].z);
+                t[6] = up_lo<GT>(x[j].w); t[7] = up_hi<GT>(x[j].w);
             } else {
                 t[0] = u2f(x[j].x); t[1] = u2f(x[j].y); t[2] = u2f(x[j].z); t[3] = u2f(x[j].w);
             }
@@ -404,10 +453,10 @@ __device__ __forceinline__ void add_ranks(const u32x4 (&x)[kGroup], int32_t n, f
 // In the fused form the chunk's Adam state is fetched before the rank loop so
 // that the lane pays one memory latency, not two.  Everything a live lane does
 // sits under one branch, so the loads of a group issue back to back.
-template <bool BF16, int PRE, bool FUSED, bool PIPE, int B>
+template <int GT, int PRE, bool FUSED, bool PIPE, int B>
 __device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs& a, uint32_t bid)
 {
-    constexpr int E = BF16 ? 8 : 4;
+    constexpr int E = GT != kF32 ? 8 : 4;
     constexpr int Q = E / 4;
     // The chunk grid is aligned on the primary fp32 output.
     float* __restrict__ master = FUSED ? a.p : a.out;
@@ -454,19 +503,19 @@ __device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs&
             // before the current group's adds wait for their data
             u32x4 xa[kGroup], xb[kGroup];
             const int32_t ngroups = (W + kGroup - 1) / kGroup;
-            load_ranks<BF16>(grads, 0, k, xa);
+            load_ranks<GT>(grads, 0, k, xa);
             for (int32_t g = 0; g < ngroups; g += 2) {
                 const bool has_b = g + 1 < ngroups;
-                if (has_b) load_ranks<BF16>(grads, (g + 1) * kGroup, k, xb);
-                add_ranks<BF16, PRE, E>(xa, W - g * kGroup, a.pre_c, a.group, rs);
-                if (g + 2 < ngroups) load_ranks<BF16>(grads, (g + 2) * kGroup, k, xa);
-                if (has_b) add_ranks<BF16, PRE, E>(xb, W - (g + 1) * kGroup, a.pre_c, a.group, rs);
+                if (has_b) load_ranks<GT>(grads, (g + 1) * kGroup, k, xb);
+                add_ranks<GT, PRE, E>(xa, W - g * kGroup, a.pre_c, a.group, rs);
+                if (g + 2 < ngroups) load_ranks<GT>(grads, (g + 2) * kGroup, k, xa);
+                if (has_b) add_ranks<GT, PRE, E>(xb, W - (g + 1) * kGroup, a.pre_c, a.group, rs);
             }
         } else {
             // W <= kGroup: one group, fewer registers
             u32x4 xa[kGroup];
-            load_ranks<BF16>(grads, 0, k, xa);
-            add_ranks<BF16, PRE, E>(xa, W, a.pre_c, a.group, rs);
+            load_ranks<GT>(grads, 0, k, xa);
+            add_ranks<GT, PRE, E>(xa, W, a.pre_c, a.group, rs);
         }
         if (a.group > 0) {   // every sharded group has been folded: the outer sum is the result
 #pragma unroll
@@ -485,6 +534,15 @@ __device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs&
                 acc[4 * q + 2] = old[q].z + acc[4 * q + 2];
                 acc[4 * q + 3] = old[q].w + acc[4 * q + 3];
             }
+        }
+        if (a.unscale) {   // sharded gradient scaler (Sec. 4.4): check, then unscale
+            bool bad = false;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                bad |= (f2u(acc[e]) & 0x7F800000u) == 0x7F800000u;
+                acc[e] = acc[e] * a.inv_scale;
+            }
+            if (bad) *a.found_inf = 1.0f;
         }
         if (a.out != nullptr) {
 #pragma unroll
@@ -528,7 +586,7 @@ __device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs&
             float outer_r = -0.0f;
             int32_t cnt = 0;
             for (int32_t w = 0; w < W; ++w) {
-                r = r + pre_scale<PRE>(load_grad<BF16>(grads.p[w], k), a.pre_c);
+                r = r + pre_scale<PRE>(load_grad<GT>(grads.p[w], k), a.pre_c);
                 if (a.group > 0 && ++cnt == a.group) {
                     outer_r = outer_r + r;
                     r = -0.0f;
@@ -538,6 +596,10 @@ __device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs&
             if (a.group > 0) r = outer_r;
             if (a.last) r = post_scale(r, a);
             if (a.accum) r = old_r + r;
+            if (a.unscale) {
+                if ((f2u(r) & 0x7F800000u) == 0x7F800000u) *a.found_inf = 1.0f;
+                r = r * a.inv_scale;
+            }
             if (a.out != nullptr) a.out[k] = r;
             if constexpr (FUSED) {
                 float pk = a.p[k], mk = a.m[k], vk = a.v[k];
@@ -549,10 +611,10 @@ __device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs&
     }
 }
 
-template <bool BF16, int PRE, bool FUSED, bool PIPE, int B>
+template <int GT, int PRE, bool FUSED, bool PIPE, int B>
 __global__ __launch_bounds__(B) void reduce_kernel(PtrTable grads, RsArgs a)
 {
-    reduce_body<BF16, PRE, FUSED, PIPE, B>(grads, a, blockIdx.x);
+    reduce_body<GT, PRE, FUSED, PIPE, B>(grads, a, blockIdx.x);
 }
 
 // Backward prefetching (Sec. 3.3.2) as one launch: the first n_reduce
@@ -560,25 +622,28 @@ __global__ __launch_bounds__(B) void reduce_kernel(PtrTable grads, RsArgs a)
 // unshard of another unit.  The two do not depend on each other, so sharing a
 // grid lets the drain of one overlap the ramp of the other without any
 // cross-queue synchronisation.
-template <bool BF16, int PRE, bool PIPE>
+template <int GT, int PRE, bool PIPE>
 __global__ __launch_bounds__(kBlock) void reduce_adam_unshard_kernel(PtrTable grads, RsArgs a, uint32_t n_reduce,
                                                                       PtrTable shards, int64_t S_next,
                                                                       uint16_t* __restrict__ out_base,
                                                                       int32_t tiles_per_shard)
 {
     if (blockIdx.x < n_reduce)
-        reduce_body<BF16, PRE, true, PIPE, kBlock>(grads, a, blockIdx.x);
+        reduce_body<GT, PRE, true, PIPE, kBlock>(grads, a, blockIdx.x);
     else
-        unshard_bf16_body(shards, S_next, out_base, tiles_per_shard, blockIdx.x - n_reduce);
+        unshard_lp_body<kBF16>(shards, S_next, out_base, tiles_per_shard, blockIdx.x - n_reduce);
 }
 
 // ---------------------------------------------------------------------------
 // Adam on the shard (Sec. 5.4; state sharded as in Sec. 3)
 // ---------------------------------------------------------------------------
+// skip: optional device flag of the gradient scaler (Sec. 4.4); when it holds a
+// non-zero value the step is skipped and p, m, v stay as they are.
 __global__ __launch_bounds__(kBlock) void adam_kernel(float* __restrict__ p, const float* __restrict__ g,
                                                        float* __restrict__ m, float* __restrict__ v,
-                                                       int64_t S, AdamConsts c)
+                                                       int64_t S, AdamConsts c, const float* __restrict__ skip)
 {
+    if (skip != nullptr && *skip != 0.0f) return;     // uniform over the whole grid
     const int64_t head = head_elems(p, 4, S);
     const int64_t nvec = (S - head) >> 2;
     const int64_t cidx = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
@@ -611,7 +676,7 @@ __global__ __launch_bounds__(kBlock) void adam_kernel(float* __restrict__ p, con
 // gradient accumulation without communication (Sec. 3.3.4): acc[k] += add[k]
 // over the unsharded buffer; one binary32 addition per element
 // ---------------------------------------------------------------------------
-template <bool BF16>
+template <int GT>
 __global__ __launch_bounds__(kBlock) void accumulate_kernel(float* __restrict__ acc, const void* __restrict__ add,
                                                              int64_t n)
 {
@@ -622,10 +687,10 @@ __global__ __launch_bounds__(kBlock) void accumulate_kernel(float* __restrict__ 
         const int64_t k = head + (c << 2);
         f32x4 a = *reinterpret_cast<const f32x4*>(acc + k);
         f32x4 b;
-        if constexpr (BF16) {
+        if constexpr (GT != kF32) {
             const u32x2 h = __builtin_nontemporal_load(
                 reinterpret_cast<const u32x2_a2*>(static_cast<const uint16_t*>(add) + k));
-            b = f32x4{u2f(h.x << 16), u2f(h.x & 0xFFFF0000u), u2f(h.y << 16), u2f(h.y & 0xFFFF0000u)};
+            b = f32x4{up_lo<GT>(h.x), up_hi<GT>(h.x), up_lo<GT>(h.y), up_hi<GT>(h.y)};
         } else {
             b = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(static_cast<const float*>(add) + k));
         }
@@ -638,8 +703,45 @@ __global__ __launch_bounds__(kBlock) void accumulate_kernel(float* __restrict__ 
         const int t = threadIdx.x;
         if (t < nrag) {
             const int64_t k = t < head ? t : tail0 + (t - head);
-            acc[k] = acc[k] + load_grad<BF16>(add, k);
+            acc[k] = acc[k] + load_grad<GT>(add, k);
         }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// gradient scaler bookkeeping (Sec. 4.4): tiny single-lane kernels so that no
+// host round trip is needed between the reduce-scatter and the optimizer step
+// ---------------------------------------------------------------------------
+struct FlagTable {
+    float* p[kMaxRanks];
+};
+
+// every rank's flag becomes the maximum of all flags (the all-reduce of found_inf)
+__global__ void found_inf_combine_kernel(FlagTable flags, int32_t n)
+{
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    float m = 0.0f;
+    for (int32_t i = 0; i < n; ++i) {
+        const float f = *flags.p[i];
+        if (f > m) m = f;
+    }
+    for (int32_t i = 0; i < n; ++i) *flags.p[i] = m;
+}
+
+__global__ void scaler_update_kernel(float* scale, int32_t* growth_tracker, const float* found_inf, float growth,
+                                     float backoff, int32_t growth_interval)
+{
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    if (*found_inf != 0.0f) {
+        *scale = *scale * backoff;
+        *growth_tracker = 0;
+    } else {
+        int32_t t = *growth_tracker + 1;
+        if (t == growth_interval) {
+            *scale = *scale * growth;
+            t = 0;
+        }
+        *growth_tracker = t;
     }
 }
 
@@ -707,39 +809,50 @@ void pad_rank_table(PtrTable& tab, int32_t n)
     for (int32_t j = n; j % kGroup != 0; ++j) tab.p[j] = tab.p[n - 1];
 }
 
-template <bool BF16, int PRE, bool FUSED>
+template <int GT, int PRE, bool FUSED>
 void launch_reduce(const PtrTable& tab, const RsArgs& a, hipStream_t st)
 {
-    constexpr int E = BF16 ? 8 : 4;
+    constexpr int E = GT != kF32 ? 8 : 4;
     constexpr int B = kReduceBlock;
     const int64_t blocks = ceil_div(a.S / E + 1, B);
     if (a.W > kGroup)
-        hipLaunchKernelGGL((reduce_kernel<BF16, PRE, FUSED, true, B>), dim3(static_cast<uint32_t>(blocks)), dim3(B), 0,
+        hipLaunchKernelGGL((reduce_kernel<GT, PRE, FUSED, true, B>), dim3(static_cast<uint32_t>(blocks)), dim3(B), 0,
                            st, tab, a);
     else
-        hipLaunchKernelGGL((reduce_kernel<BF16, PRE, FUSED, false, B>), dim3(static_cast<uint32_t>(blocks)), dim3(B),
+        hipLaunchKernelGGL((reduce_kernel<GT, PRE, FUSED, false, B>), dim3(static_cast<uint32_t>(blocks)), dim3(B),
                            0, st, tab, a);
 }
 
-template <bool BF16, bool FUSED>
+template <int GT, bool FUSED>
 void launch_reduce_pre(int pre_mode, const PtrTable& tab, const RsArgs& a, hipStream_t st)
 {
-    if (pre_mode == kPreNone) launch_reduce<BF16, kPreNone, FUSED>(tab, a, st);
-    else if (pre_mode == kPreMul) launch_reduce<BF16, kPreMul, FUSED>(tab, a, st);
-    else launch_reduce<BF16, kPreDiv, FUSED>(tab, a, st);
+    if (pre_mode == kPreNone) launch_reduce<GT, kPreNone, FUSED>(tab, a, st);
+    else if (pre_mode == kPreMul) launch_reduce<GT, kPreMul, FUSED>(tab, a, st);
+    else launch_reduce<GT, kPreDiv, FUSED>(tab, a, st);
 }
 
+inline bool valid_dtype(fsdp_dtype_t d) { return d == FSDP_F32 || d == FSDP_BF16 || d == FSDP_F16; }
+inline int64_t dtype_size(fsdp_dtype_t d) { return d == FSDP_F32 ? 4 : 2; }
+
 // shared driver of fsdp_reduce_scatter_local and fsdp_reduce_scatter_adam_fused
+struct ReduceOpts {
+    int32_t num_groups = 1;      // hybrid sharding: sharded groups of L->world_size ranks, table group-major
+    bool accumulate = false;     // add the result to what the output buffer holds
+    bool unscale = false;        // gradient scaler: non-finite check + multiply by inv_scale
+    float inv_scale = 1.0f;
+    float* found_inf = nullptr;
+};
+
+// shared driver of the reduce-scatter entry points
 int reduce_driver(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dtype_t grad_dtype, int32_t rank,
                   float pre, float post, float* out, bool fused, float* p, float* m, float* v, uint16_t* p_lp,
-                  const AdamConsts& adam, hipStream_t st, int32_t num_groups = 1, bool accumulate = false)
+                  const AdamConsts& adam, hipStream_t st, const ReduceOpts& opt = ReduceOpts())
 {
-    // hybrid sharding: num_groups sharded groups of L->world_size ranks each, table group-major
-    const int32_t W = L->world_size * num_groups;
-    if ((num_groups > 1 || accumulate) && W > kMaxRanks) return FSDP_ERR_INVALID_ARG;
+    const int32_t W = L->world_size * opt.num_groups;
+    // these variants keep their state in one launch
+    if ((opt.num_groups > 1 || opt.accumulate || opt.unscale) && W > kMaxRanks) return FSDP_ERR_INVALID_ARG;
     const int64_t S = L->S;
-    const bool bf16 = grad_dtype == FSDP_BF16;
-    const int64_t esz = bf16 ? 2 : 4;
+    const int64_t esz = dtype_size(grad_dtype);
     if (!grid_ok(ceil_div(S / 4 + 1, kBlock))) return FSDP_ERR_OVERFLOW;
 
     float pre_c = pre;
@@ -761,8 +874,11 @@ int reduce_driver(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dty
         a.W = nw;
         a.cont = w0 > 0;
         a.last = w0 + nw == W;
-        a.group = num_groups > 1 ? L->world_size : 0;
-        a.accum = accumulate ? 1 : 0;
+        a.group = opt.num_groups > 1 ? L->world_size : 0;
+        a.accum = opt.accumulate ? 1 : 0;
+        a.unscale = opt.unscale ? 1 : 0;
+        a.inv_scale = opt.inv_scale;
+        a.found_inf = opt.found_inf;
         a.pre_c = pre_c;
         a.post_mul = post_mul;
         a.post_c = post_c;
@@ -771,12 +887,15 @@ int reduce_driver(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dty
         a.p = p; a.m = m; a.v = v; a.p_lp = p_lp;
         a.adam = adam;
         const bool fuse_now = fused && a.last;
-        if (bf16) {
-            if (fuse_now) launch_reduce_pre<true, true>(pre_mode, tab, a, st);
-            else launch_reduce_pre<true, false>(pre_mode, tab, a, st);
+        if (grad_dtype == FSDP_BF16) {
+            if (fuse_now) launch_reduce_pre<kBF16, true>(pre_mode, tab, a, st);
+            else launch_reduce_pre<kBF16, false>(pre_mode, tab, a, st);
+        } else if (grad_dtype == FSDP_F16) {
+            if (fuse_now) launch_reduce_pre<kF16, true>(pre_mode, tab, a, st);
+            else launch_reduce_pre<kF16, false>(pre_mode, tab, a, st);
         } else {
-            if (fuse_now) launch_reduce_pre<false, true>(pre_mode, tab, a, st);
-            else launch_reduce_pre<false, false>(pre_mode, tab, a, st);
+            if (fuse_now) launch_reduce_pre<kF32, true>(pre_mode, tab, a, st);
+            else launch_reduce_pre<kF32, false>(pre_mode, tab, a, st);
         }
         const int rc = launch_status();
         if (rc != FSDP_OK) return rc;
@@ -789,10 +908,10 @@ int check_reduce_args(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp
 {
     if (!L || !grad_ptrs) return FSDP_ERR_NULL_PTR;
     if (num_groups < 1) return FSDP_ERR_INVALID_ARG;
-    if (grad_dtype != FSDP_F32 && grad_dtype != FSDP_BF16) return FSDP_ERR_BAD_DTYPE;
+    if (!valid_dtype(grad_dtype)) return FSDP_ERR_BAD_DTYPE;
     if (rank < 0 || rank >= L->world_size) return FSDP_ERR_RANK_RANGE;
     if (!std::isfinite(pre) || !std::isfinite(post) || !(pre > 0.0f) || !(post > 0.0f)) return FSDP_ERR_INVALID_ARG;
-    const uintptr_t al = grad_dtype == FSDP_BF16 ? 2 : 4;
+    const uintptr_t al = static_cast<uintptr_t>(dtype_size(grad_dtype));
     const int64_t nptr = static_cast<int64_t>(L->world_size) * num_groups;
     if (nptr > 0x7FFFFFFF) return FSDP_ERR_OVERFLOW;
     for (int64_t w = 0; w < nptr; ++w) {
@@ -875,18 +994,18 @@ int fsdp_unshard(const fsdp_layout_t* L, const float* const* shard_ptrs, void* f
                  void* hip_stream)
 {
     if (!L || !shard_ptrs || !flat_out) return FSDP_ERR_NULL_PTR;
-    if (out_dtype != FSDP_F32 && out_dtype != FSDP_BF16) return FSDP_ERR_BAD_DTYPE;
+    if (!valid_dtype(out_dtype)) return FSDP_ERR_BAD_DTYPE;
     const int32_t W = L->world_size;
     const int64_t S = L->S;
     for (int32_t w = 0; w < W; ++w) {
         if (!shard_ptrs[w]) return FSDP_ERR_NULL_PTR;
         if (misaligned(shard_ptrs[w], 4)) return FSDP_ERR_INVALID_ARG;
     }
-    const bool bf16 = out_dtype == FSDP_BF16;
-    if (misaligned(flat_out, bf16 ? 2 : 4)) return FSDP_ERR_INVALID_ARG;
+    const bool lp = out_dtype != FSDP_F32;
+    if (misaligned(flat_out, lp ? 2 : 4)) return FSDP_ERR_INVALID_ARG;
     // One destination vector per lane measured fastest on MI355X for the cast
     // (more, shorter workgroups hide the ramp of small units better).
-    const int64_t vec = bf16 ? 8 : 4;
+    const int64_t vec = lp ? 8 : 4;
     const int64_t tiles = ceil_div(S / vec + 1, kBlock);
     if (!grid_ok(tiles * kMaxRanks)) return FSDP_ERR_OVERFLOW;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -896,10 +1015,14 @@ int fsdp_unshard(const fsdp_layout_t* L, const float* const* shard_ptrs, void* f
         PtrTable tab = {};
         for (int32_t j = 0; j < nw; ++j) tab.p[j] = shard_ptrs[w0 + j];
         const dim3 grid(static_cast<uint32_t>(tiles * nw));
-        if (bf16) {
+        if (lp) {
             uint16_t* base = static_cast<uint16_t*>(flat_out) + static_cast<int64_t>(w0) * S;
-            hipLaunchKernelGGL(unshard_bf16_kernel, grid, dim3(kBlock), 0, st, tab, S, base,
-                               static_cast<int32_t>(tiles));
+            if (out_dtype == FSDP_F16)
+                hipLaunchKernelGGL(unshard_lp_kernel<kF16>, grid, dim3(kBlock), 0, st, tab, S, base,
+                                   static_cast<int32_t>(tiles));
+            else
+                hipLaunchKernelGGL(unshard_lp_kernel<kBF16>, grid, dim3(kBlock), 0, st, tab, S, base,
+                                   static_cast<int32_t>(tiles));
         } else {
             float* base = static_cast<float*>(flat_out) + static_cast<int64_t>(w0) * S;
             hipLaunchKernelGGL(unshard_f32_kernel, grid, dim3(kBlock), 0, st, tab, S, base,
@@ -923,21 +1046,38 @@ int fsdp_reduce_scatter_local(const fsdp_layout_t* L, const void* const* grad_pt
                          nullptr, nullptr, none, static_cast<hipStream_t>(hip_stream));
 }
 
-int fsdp_shard_adam_step(const fsdp_layout_t* L, float* p_shard, const float* g_shard, float* exp_avg,
-                         float* exp_avg_sq, int64_t step, float lr, float beta1, float beta2, float eps,
-                         void* hip_stream)
+static int adam_step_impl(const fsdp_layout_t* L, float* p_shard, const float* g_shard, float* exp_avg,
+                          float* exp_avg_sq, int64_t step, float lr, float beta1, float beta2, float eps,
+                          const float* skip, void* hip_stream)
 {
     if (!L || !p_shard || !g_shard || !exp_avg || !exp_avg_sq) return FSDP_ERR_NULL_PTR;
     int rc = check_adam_args(step, lr, beta1, beta2, eps);
     if (rc != FSDP_OK) return rc;
-    if (misaligned(p_shard, 4) || misaligned(g_shard, 4) || misaligned(exp_avg, 4) || misaligned(exp_avg_sq, 4))
+    if (misaligned(p_shard, 4) || misaligned(g_shard, 4) || misaligned(exp_avg, 4) || misaligned(exp_avg_sq, 4) ||
+        (skip && misaligned(skip, 4)))
         return FSDP_ERR_INVALID_ARG;
     const int64_t blocks = ceil_div(L->S / 4 + 1, kBlock);
     if (!grid_ok(blocks)) return FSDP_ERR_OVERFLOW;
     const AdamConsts c = make_adam_consts(step, lr, beta1, beta2, eps);
     hipLaunchKernelGGL(adam_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kBlock), 0,
-                       static_cast<hipStream_t>(hip_stream), p_shard, g_shard, exp_avg, exp_avg_sq, L->S, c);
+                       static_cast<hipStream_t>(hip_stream), p_shard, g_shard, exp_avg, exp_avg_sq, L->S, c, skip);
     return launch_status();
+}
+
+int fsdp_shard_adam_step(const fsdp_layout_t* L, float* p_shard, const float* g_shard, float* exp_avg,
+                         float* exp_avg_sq, int64_t step, float lr, float beta1, float beta2, float eps,
+                         void* hip_stream)
+{
+    return adam_step_impl(L, p_shard, g_shard, exp_avg, exp_avg_sq, step, lr, beta1, beta2, eps, nullptr, hip_stream);
+}
+
+int fsdp_shard_adam_step_guarded(const fsdp_layout_t* L, float* p_shard, const float* g_shard, float* exp_avg,
+                                 float* exp_avg_sq, int64_t step, float lr, float beta1, float beta2, float eps,
+                                 const float* found_inf, void* hip_stream)
+{
+    if (!found_inf) return FSDP_ERR_NULL_PTR;
+    return adam_step_impl(L, p_shard, g_shard, exp_avg, exp_avg_sq, step, lr, beta1, beta2, eps, found_inf,
+                          hip_stream);
 }
 
 int fsdp_reduce_scatter_adam_fused(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dtype_t grad_dtype,
@@ -979,21 +1119,21 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* L, const void
         return FSDP_ERR_INVALID_ARG;
     const fsdp_layout_t* N = next_layout;
     if (!N || !next_shard_ptrs || !next_flat_out) return FSDP_ERR_NULL_PTR;
-    if (next_out_dtype != FSDP_F32 && next_out_dtype != FSDP_BF16) return FSDP_ERR_BAD_DTYPE;
+    if (!valid_dtype(next_out_dtype)) return FSDP_ERR_BAD_DTYPE;
     for (int32_t w = 0; w < N->world_size; ++w) {
         if (!next_shard_ptrs[w]) return FSDP_ERR_NULL_PTR;
         if (misaligned(next_shard_ptrs[w], 4)) return FSDP_ERR_INVALID_ARG;
     }
-    if (misaligned(next_flat_out, next_out_dtype == FSDP_BF16 ? 2 : 4)) return FSDP_ERR_INVALID_ARG;
+    if (misaligned(next_flat_out, static_cast<uintptr_t>(dtype_size(next_out_dtype)))) return FSDP_ERR_INVALID_ARG;
 
-    const int64_t E = grad_dtype == FSDP_BF16 ? 8 : 4;
+    const int64_t E = grad_dtype == FSDP_F32 ? 4 : 8;
     const int64_t n_reduce = ceil_div(L->S / E + 1, kBlock);
     const int64_t tiles = ceil_div(N->S / 8 + 1, kBlock);
     const int64_t n_unshard = tiles * N->world_size;
     // Sharing a grid pays while the fixed cost of a launch (about 2 us of ramp
     // and drain) is visible next to the smaller half; for large halves the
     // shared kernel's register budget costs the unshard more than it saves.
-    const int64_t reduce_bytes = (grad_dtype == FSDP_BF16 ? 2 : 4) * L->P + 24 * L->S;
+    const int64_t reduce_bytes = dtype_size(grad_dtype) * L->P + 24 * L->S;
     const int64_t unshard_bytes = 6 * N->P;
     const bool small_half = (reduce_bytes < unshard_bytes ? reduce_bytes : unshard_bytes) <= kOneLaunchMaxBytes;
     const bool one_launch = small_half && L->world_size <= kMaxRanks && N->world_size <= kMaxRanks &&
@@ -1005,7 +1145,7 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* L, const void
         return fsdp_unshard(N, next_shard_ptrs, next_flat_out, next_out_dtype, hip_stream);
     }
 
-    const int64_t esz = grad_dtype == FSDP_BF16 ? 2 : 4;
+    const int64_t esz = dtype_size(grad_dtype);
     PtrTable gtab = {}, stab = {};
     for (int32_t w = 0; w < L->world_size; ++w)
         gtab.p[w] = static_cast<const char*>(grad_ptrs[w]) + static_cast<int64_t>(rank) * L->S * esz;
@@ -1041,13 +1181,17 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* L, const void
                                nr, stab, N->S, out_base, tl);                                                      \
     } while (0)
     if (grad_dtype == FSDP_BF16) {
-        if (pre_mode == kPreNone) FSDP_LAUNCH_COMBINED(true, kPreNone);
-        else if (pre_mode == kPreMul) FSDP_LAUNCH_COMBINED(true, kPreMul);
-        else FSDP_LAUNCH_COMBINED(true, kPreDiv);
+        if (pre_mode == kPreNone) FSDP_LAUNCH_COMBINED(kBF16, kPreNone);
+        else if (pre_mode == kPreMul) FSDP_LAUNCH_COMBINED(kBF16, kPreMul);
+        else FSDP_LAUNCH_COMBINED(kBF16, kPreDiv);
+    } else if (grad_dtype == FSDP_F16) {
+        if (pre_mode == kPreNone) FSDP_LAUNCH_COMBINED(kF16, kPreNone);
+        else if (pre_mode == kPreMul) FSDP_LAUNCH_COMBINED(kF16, kPreMul);
+        else FSDP_LAUNCH_COMBINED(kF16, kPreDiv);
     } else {
-        if (pre_mode == kPreNone) FSDP_LAUNCH_COMBINED(false, kPreNone);
-        else if (pre_mode == kPreMul) FSDP_LAUNCH_COMBINED(false, kPreMul);
-        else FSDP_LAUNCH_COMBINED(false, kPreDiv);
+        if (pre_mode == kPreNone) FSDP_LAUNCH_COMBINED(kF32, kPreNone);
+        else if (pre_mode == kPreMul) FSDP_LAUNCH_COMBINED(kF32, kPreMul);
+        else FSDP_LAUNCH_COMBINED(kF32, kPreDiv);
     }
 #undef FSDP_LAUNCH_COMBINED
     return launch_status();
@@ -1062,8 +1206,10 @@ int fsdp_reduce_scatter_hybrid(const fsdp_layout_t* L, const void* const* grad_p
     if (!grad_shard_out) return FSDP_ERR_NULL_PTR;
     if (misaligned(grad_shard_out, 4)) return FSDP_ERR_INVALID_ARG;
     const AdamConsts none = {};
+    ReduceOpts opt;
+    opt.num_groups = num_groups;
     return reduce_driver(L, grad_ptrs, grad_dtype, rank, pre_div, post_div, grad_shard_out, false, nullptr, nullptr,
-                         nullptr, nullptr, none, static_cast<hipStream_t>(hip_stream), num_groups, false);
+                         nullptr, nullptr, none, static_cast<hipStream_t>(hip_stream), opt);
 }
 
 int fsdp_reduce_scatter_accumulate(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dtype_t grad_dtype,
@@ -1075,39 +1221,49 @@ int fsdp_reduce_scatter_accumulate(const fsdp_layout_t* L, const void* const* gr
     if (!grad_shard_acc) return FSDP_ERR_NULL_PTR;
     if (misaligned(grad_shard_acc, 4)) return FSDP_ERR_INVALID_ARG;
     const AdamConsts none = {};
+    ReduceOpts opt;
+    opt.accumulate = true;
     return reduce_driver(L, grad_ptrs, grad_dtype, rank, pre_div, post_div, grad_shard_acc, false, nullptr, nullptr,
-                         nullptr, nullptr, none, static_cast<hipStream_t>(hip_stream), 1, true);
+                         nullptr, nullptr, none, static_cast<hipStream_t>(hip_stream), opt);
 }
 
 int fsdp_grad_accumulate(const fsdp_layout_t* L, float* grad_acc, const void* grad_add, fsdp_dtype_t add_dtype,
                          void* hip_stream)
 {
     if (!L || !grad_acc || !grad_add) return FSDP_ERR_NULL_PTR;
-    if (add_dtype != FSDP_F32 && add_dtype != FSDP_BF16) return FSDP_ERR_BAD_DTYPE;
-    if (misaligned(grad_acc, 4) || misaligned(grad_add, add_dtype == FSDP_BF16 ? 2 : 4)) return FSDP_ERR_INVALID_ARG;
+    if (!valid_dtype(add_dtype)) return FSDP_ERR_BAD_DTYPE;
+    if (misaligned(grad_acc, 4) || misaligned(grad_add, static_cast<uintptr_t>(dtype_size(add_dtype))))
+        return FSDP_ERR_INVALID_ARG;
     const int64_t blocks = ceil_div(L->P / 4 + 1, kBlock);
     if (!grid_ok(blocks)) return FSDP_ERR_OVERFLOW;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const dim3 grid(static_cast<uint32_t>(blocks));
     if (add_dtype == FSDP_BF16)
-        hipLaunchKernelGGL(accumulate_kernel<true>, dim3(static_cast<uint32_t>(blocks)), dim3(kBlock), 0, st, grad_acc,
-                           grad_add, L->P);
+        hipLaunchKernelGGL(accumulate_kernel<kBF16>, grid, dim3(kBlock), 0, st, grad_acc, grad_add, L->P);
+    else if (add_dtype == FSDP_F16)
+        hipLaunchKernelGGL(accumulate_kernel<kF16>, grid, dim3(kBlock), 0, st, grad_acc, grad_add, L->P);
     else
-        hipLaunchKernelGGL(accumulate_kernel<false>, dim3(static_cast<uint32_t>(blocks)), dim3(kBlock), 0, st,
-                           grad_acc, grad_add, L->P);
+        hipLaunchKernelGGL(accumulate_kernel<kF32>, grid, dim3(kBlock), 0, st, grad_acc, grad_add, L->P);
     return launch_status();
 }
 
-int fsdp_cast_shard(const fsdp_layout_t* L, const float* shard, void* lp_shard_out, void* hip_stream)
+int fsdp_cast_shard(const fsdp_layout_t* L, const float* shard, void* lp_shard_out, fsdp_dtype_t lp_dtype,
+                    void* hip_stream)
 {
     if (!L || !shard || !lp_shard_out) return FSDP_ERR_NULL_PTR;
+    if (lp_dtype != FSDP_BF16 && lp_dtype != FSDP_F16) return FSDP_ERR_BAD_DTYPE;
     if (misaligned(shard, 4) || misaligned(lp_shard_out, 2)) return FSDP_ERR_INVALID_ARG;
     const int64_t tiles = ceil_div(L->S / 8 + 1, kBlock);
     if (!grid_ok(tiles)) return FSDP_ERR_OVERFLOW;
     PtrTable tab = {};
     tab.p[0] = shard;
-    hipLaunchKernelGGL(unshard_bf16_kernel, dim3(static_cast<uint32_t>(tiles)), dim3(kBlock), 0,
-                       static_cast<hipStream_t>(hip_stream), tab, L->S, static_cast<uint16_t*>(lp_shard_out),
-                       static_cast<int32_t>(tiles));
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (lp_dtype == FSDP_F16)
+        hipLaunchKernelGGL(unshard_lp_kernel<kF16>, dim3(static_cast<uint32_t>(tiles)), dim3(kBlock), 0, st, tab, L->S,
+                           static_cast<uint16_t*>(lp_shard_out), static_cast<int32_t>(tiles));
+    else
+        hipLaunchKernelGGL(unshard_lp_kernel<kBF16>, dim3(static_cast<uint32_t>(tiles)), dim3(kBlock), 0, st, tab,
+                           L->S, static_cast<uint16_t*>(lp_shard_out), static_cast<int32_t>(tiles));
     return launch_status();
 }
 
@@ -1135,6 +1291,52 @@ int fsdp_unshard_lp(const fsdp_layout_t* L, const void* const* lp_shard_ptrs, vo
         if (rc != FSDP_OK) return rc;
     }
     return FSDP_OK;
+}
+
+int fsdp_reduce_scatter_unscale(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dtype_t grad_dtype,
+                                int32_t rank, float pre_div, float post_div, float inv_scale, float* grad_shard_out,
+                                float* found_inf, void* hip_stream)
+{
+    int rc = check_reduce_args(L, grad_ptrs, grad_dtype, rank, pre_div, post_div);
+    if (rc != FSDP_OK) return rc;
+    if (!grad_shard_out || !found_inf) return FSDP_ERR_NULL_PTR;
+    if (misaligned(grad_shard_out, 4) || misaligned(found_inf, 4)) return FSDP_ERR_INVALID_ARG;
+    if (!std::isfinite(inv_scale) || !(inv_scale > 0.0f)) return FSDP_ERR_INVALID_ARG;
+    const AdamConsts none = {};
+    ReduceOpts opt;
+    opt.unscale = true;
+    opt.inv_scale = inv_scale;
+    opt.found_inf = found_inf;
+    return reduce_driver(L, grad_ptrs, grad_dtype, rank, pre_div, post_div, grad_shard_out, false, nullptr, nullptr,
+                         nullptr, nullptr, none, static_cast<hipStream_t>(hip_stream), opt);
+}
+
+int fsdp_found_inf_combine(float* const* found_inf_ptrs, int32_t num_ranks, void* hip_stream)
+{
+    if (!found_inf_ptrs) return FSDP_ERR_NULL_PTR;
+    if (num_ranks <= 0 || num_ranks > kMaxRanks) return FSDP_ERR_INVALID_ARG;
+    FlagTable tab = {};
+    for (int32_t i = 0; i < num_ranks; ++i) {
+        if (!found_inf_ptrs[i]) return FSDP_ERR_NULL_PTR;
+        if (misaligned(found_inf_ptrs[i], 4)) return FSDP_ERR_INVALID_ARG;
+        tab.p[i] = found_inf_ptrs[i];
+    }
+    hipLaunchKernelGGL(found_inf_combine_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), tab,
+                       num_ranks);
+    return launch_status();
+}
+
+int fsdp_grad_scaler_update(float* scale, int32_t* growth_tracker, const float* found_inf, float growth_factor,
+                            float backoff_factor, int32_t growth_interval, void* hip_stream)
+{
+    if (!scale || !growth_tracker || !found_inf) return FSDP_ERR_NULL_PTR;
+    if (misaligned(scale, 4) || misaligned(growth_tracker, 4) || misaligned(found_inf, 4)) return FSDP_ERR_INVALID_ARG;
+    if (!(growth_factor > 1.0f) || !std::isfinite(growth_factor) || !(backoff_factor > 0.0f) ||
+        !(backoff_factor < 1.0f) || growth_interval < 1)
+        return FSDP_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(scaler_update_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), scale,
+                       growth_tracker, found_inf, growth_factor, backoff_factor, growth_interval);
+    return launch_status();
 }
 
 }  // extern "C"

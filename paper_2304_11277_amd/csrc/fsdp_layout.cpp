@@ -139,7 +139,7 @@ int fsdp_layout_param(const fsdp_layout_t* L, int32_t i, int64_t* offset, int64_
 int fsdp_view_ptr(const fsdp_layout_t* L, void* flat_base, fsdp_dtype_t dtype, int32_t i, void** out)
 {
     if (!L || !flat_base || !out) return FSDP_ERR_NULL_PTR;
-    if (dtype != FSDP_F32 && dtype != FSDP_BF16) return FSDP_ERR_BAD_DTYPE;
+    if (dtype != FSDP_F32 && dtype != FSDP_BF16 && dtype != FSDP_F16) return FSDP_ERR_BAD_DTYPE;
     if (i < 0 || i >= L->num_params) return FSDP_ERR_RANK_RANGE;
     const int64_t esize = dtype == FSDP_F32 ? 4 : 2;
     *out = static_cast<char*>(flat_base) + L->off[i] * esize;

@@ -19,7 +19,7 @@ def np_bits(t: torch.Tensor) -> np.ndarray:
     """Device or host tensor -> numpy array of raw bit patterns (uint32 for
     fp32, uint16 for bf16)."""
     t = t.detach().contiguous().cpu()
-    if t.dtype == torch.bfloat16:
+    if t.dtype in (torch.bfloat16, torch.float16):
         return t.view(torch.int16).numpy().view(np.uint16)
     if t.dtype == torch.float32:
         return t.numpy().view(np.uint32)
@@ -32,7 +32,7 @@ def np_f32(t: torch.Tensor) -> np.ndarray:
 
 def np_grad(t: torch.Tensor) -> np.ndarray:
     """Gradient buffer -> what the oracle takes (float32 array or uint16 bf16 bits)."""
-    return np_bits(t) if t.dtype == torch.bfloat16 else np_f32(t)
+    return np_bits(t) if t.dtype in (torch.bfloat16, torch.float16) else np_f32(t)
 
 
 def same_bits(a: np.ndarray, b: np.ndarray) -> bool:
@@ -58,7 +58,7 @@ def carve(n: int, dtype, elem_offset: int, device="cuda", fill=None) -> torch.Te
     aligned) base plus elem_offset elements."""
     base = torch.empty(n + elem_offset + 64, dtype=dtype, device=device)
     if fill is not None:
-        base.view(torch.int16 if dtype == torch.bfloat16 else torch.int32).fill_(fill)
+        base.view(torch.int16 if dtype in (torch.bfloat16, torch.float16) else torch.int32).fill_(fill)
     return base[elem_offset:elem_offset + n]
 
 

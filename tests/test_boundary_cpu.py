@@ -117,7 +117,8 @@ def test_query_errors(L):
     base = ctypes.c_void_p(0x1000)
     assert raw.fsdp_view_ptr(h, base, 1, 1, ctypes.byref(out)) == OK and out.value == 0x1000 + 12 * 2
     assert raw.fsdp_view_ptr(h, base, 0, 1, ctypes.byref(out)) == OK and out.value == 0x1000 + 12 * 4
-    assert raw.fsdp_view_ptr(h, base, 2, 1, ctypes.byref(out)) == BAD_DTYPE
+    assert raw.fsdp_view_ptr(h, base, 2, 1, ctypes.byref(out)) == OK and out.value == 0x1000 + 12 * 2
+    assert raw.fsdp_view_ptr(h, base, 3, 1, ctypes.byref(out)) == BAD_DTYPE
     assert raw.fsdp_view_ptr(h, base, 0, 5, ctypes.byref(out)) == RANK_RANGE
     assert raw.fsdp_view_ptr(h, None, 0, 0, ctypes.byref(out)) == NULL
     assert raw.fsdp_view_ptr(h, base, 0, 0, None) == NULL
@@ -156,7 +157,7 @@ def test_compute_entry_points_reject_bad_arguments_before_launch(L):
     assert raw.fsdp_unshard(h, None, buf, 1, st) == NULL
     assert raw.fsdp_unshard(h, good4, None, 1, st) == NULL
     assert raw.fsdp_unshard(h, with_null, buf, 1, st) == NULL
-    assert raw.fsdp_unshard(h, good4, buf, 2, st) == BAD_DTYPE
+    assert raw.fsdp_unshard(h, good4, buf, 3, st) == BAD_DTYPE
     assert raw.fsdp_unshard(h, good4, buf, -1, st) == BAD_DTYPE
     assert raw.fsdp_unshard(h, odd, buf, 1, st) == INVALID
     assert raw.fsdp_unshard(h, good4, ctypes.c_void_p(0x30001), 1, st) == INVALID
@@ -208,7 +209,7 @@ def test_compute_entry_points_reject_bad_arguments_before_launch(L):
     assert pf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, hn, None, buf, 1, st) == NULL
     assert pf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, hn, good4, None, 1, st) == NULL
     assert pf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, hn, with_null, buf, 1, st) == NULL
-    assert pf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, hn, good4, buf, 3, st) == BAD_DTYPE
+    assert pf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, hn, good4, buf, 4, st) == BAD_DTYPE
     assert pf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, hn, odd, buf, 1, st) == INVALID
     assert pf(h, good4, 0, 4, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, hn, good4, buf, 1, st) == RANK_RANGE
     assert pf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(0), *ok_h, None, hn, good4, buf, 1, st) == INVALID
@@ -228,11 +229,36 @@ def test_compute_entry_points_reject_bad_arguments_before_launch(L):
     assert ra(h, good4, 0, 0, f(2), f(2), None, st) == NULL
     assert ra(h, good4, 0, 9, f(2), f(2), buf, st) == RANK_RANGE
     assert ra(h, good4, 0, 0, f(0), f(2), buf, st) == INVALID
-    assert raw.fsdp_cast_shard(None, buf, buf, st) == NULL
-    assert raw.fsdp_cast_shard(h, None, buf, st) == NULL
-    assert raw.fsdp_cast_shard(h, buf, None, st) == NULL
-    assert raw.fsdp_cast_shard(h, ctypes.c_void_p(0x30002), buf, st) == INVALID
-    assert raw.fsdp_cast_shard(h, buf, ctypes.c_void_p(0x30001), st) == INVALID
+    assert raw.fsdp_cast_shard(None, buf, buf, 1, st) == NULL
+    assert raw.fsdp_cast_shard(h, None, buf, 1, st) == NULL
+    assert raw.fsdp_cast_shard(h, buf, None, 2, st) == NULL
+    assert raw.fsdp_cast_shard(h, buf, buf, 0, st) == BAD_DTYPE
+    assert raw.fsdp_cast_shard(h, buf, buf, 3, st) == BAD_DTYPE
+    assert raw.fsdp_cast_shard(h, ctypes.c_void_p(0x30002), buf, 1, st) == INVALID
+    assert raw.fsdp_cast_shard(h, buf, ctypes.c_void_p(0x30001), 2, st) == INVALID
+    # gradient scaler
+    flag = ctypes.c_void_p(0x60000)
+    us = raw.fsdp_reduce_scatter_unscale
+    assert us(h, good4, 2, 0, f(2), f(2), f(0.5), buf, None, st) == NULL
+    assert us(h, good4, 2, 0, f(2), f(2), f(0.5), None, flag, st) == NULL
+    assert us(h, good4, 2, 0, f(2), f(2), f(0.0), buf, flag, st) == INVALID
+    assert us(h, good4, 2, 0, f(2), f(2), f(float("inf")), buf, flag, st) == INVALID
+    assert us(h, good4, 3, 0, f(2), f(2), f(0.5), buf, flag, st) == BAD_DTYPE
+    assert us(h, good4, 2, 0, f(2), f(2), f(0.5), buf, ctypes.c_void_p(0x60002), st) == INVALID
+    assert raw.fsdp_found_inf_combine(None, 4, st) == NULL
+    assert raw.fsdp_found_inf_combine(good4, 0, st) == INVALID
+    assert raw.fsdp_found_inf_combine(many68, 65, st) == INVALID
+    assert raw.fsdp_found_inf_combine(with_null, 4, st) == NULL
+    assert raw.fsdp_shard_adam_step_guarded(h, p, g, m, v, i64(1), *ok_h, None, st) == NULL
+    assert raw.fsdp_shard_adam_step_guarded(h, p, g, m, v, i64(0), *ok_h, flag, st) == INVALID
+    gsu = raw.fsdp_grad_scaler_update
+    i32p = ctypes.c_void_p(0x61000)
+    assert gsu(None, i32p, flag, f(2), f(0.5), 2000, st) == NULL
+    assert gsu(flag, None, flag, f(2), f(0.5), 2000, st) == NULL
+    assert gsu(flag, i32p, None, f(2), f(0.5), 2000, st) == NULL
+    assert gsu(flag, i32p, flag, f(1.0), f(0.5), 2000, st) == INVALID
+    assert gsu(flag, i32p, flag, f(2.0), f(1.0), 2000, st) == INVALID
+    assert gsu(flag, i32p, flag, f(2.0), f(0.5), 0, st) == INVALID
     assert raw.fsdp_unshard_lp(None, good4, buf, st) == NULL
     assert raw.fsdp_unshard_lp(h, None, buf, st) == NULL
     assert raw.fsdp_unshard_lp(h, good4, None, st) == NULL
@@ -242,7 +268,7 @@ def test_compute_entry_points_reject_bad_arguments_before_launch(L):
     assert ga(None, buf, buf, 0, st) == NULL
     assert ga(h, None, buf, 0, st) == NULL
     assert ga(h, buf, None, 0, st) == NULL
-    assert ga(h, buf, buf, 2, st) == BAD_DTYPE
+    assert ga(h, buf, buf, 3, st) == BAD_DTYPE
     assert ga(h, ctypes.c_void_p(0x30002), buf, 0, st) == INVALID
     assert ga(h, buf, ctypes.c_void_p(0x30001), 1, st) == INVALID
     raw.fsdp_layout_destroy(h)
