@@ -36,8 +36,11 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="index into BASELINE.json configs (default 1)")
     ap.add_argument("--max-units", type=int, default=0, help="limit the number of units (0 = all)")
-    ap.add_argument("--mode", choices=["prefetch", "fused", "separate", "lp"], default="prefetch",
-                    help="prefetch: unit i's fused reduce-scatter+Adam shares one launch with unit i+1's unshard "
+    ap.add_argument("--depth", type=int, default=3, help="units per batch in --mode batch (prefetch depth)")
+    ap.add_argument("--mode", choices=["batch", "prefetch", "fused", "separate", "lp"], default="batch",
+                    help="batch: the updates of `depth` units and the prefetched unshards of the next `depth` units "
+                         "are independent and share one launch (fsdp_batch_*); "
+                         "prefetch: unit i's fused reduce-scatter+Adam shares one launch with unit i+1's unshard "
                          "(backward prefetching); fused: reduce-scatter + Adam in one launch, unshard in another; "
                          "separate: the three required entry points, one launch each; lp: every rank keeps a bf16 "
                          "copy of its shard (written by the fused Adam), the unshard gathers bf16 (Sec. 4.4)")
@@ -148,7 +151,8 @@ def main():
 
     # The unsharded flat parameter is transient (Sec. 3.2.1: peak memory is the
     # largest unit); two buffers alternate, as with at most two unshards in flight.
-    flats = [flat, torch.empty_like(flat)]
+    nflat = 2 * args.depth if args.mode == "batch" else 2
+    flats = [flat] + [torch.empty_like(flat) for _ in range(nflat - 1)]
 
     def unshard(s, buf):
         F.fsdp_unshard(s.lay, s.shard_tab, buf[:s.P])
@@ -164,8 +168,31 @@ def main():
     # One step as a list of launches: (kernel kind, callable(t), algorithmic bytes).
     launches = []
     n = len(states)
+    if args.mode == "batch":
+        d = args.depth
+        groups = [list(range(i, min(i + d, n))) for i in range(0, n, d)]
+
+        def make_batch(red, uns):
+            b = F.Batch()
+            for i in red:
+                s = states[i]
+                b.add_reduce_scatter_adam(s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m, s.v, *hp, None)
+            for i in uns:
+                s = states[i]
+                b.add_unshard(s.lay, s.shard_tab, flats[i % nflat][:s.P])
+            nbytes = sum(states[i].b_reduce + states[i].b_adam for i in red) + sum(states[i].b_unshard for i in uns)
+            return b, nbytes
+
+        b0, nb0 = make_batch([], groups[0])
+        launches.append(("batch", (lambda t, b=b0: b.launch(t)), nb0))
+        for j, grp in enumerate(groups):
+            nxt = groups[j + 1] if j + 1 < len(groups) else []
+            bj, nbj = make_batch(grp, nxt)
+            launches.append(("batch", (lambda t, b=bj: b.launch(t)), nbj))
     for i, s in enumerate(states):
         buf = flats[i % 2]
+        if args.mode == "batch":
+            break
         if args.mode == "prefetch":
             if i == 0:
                 launches.append(("unshard", (lambda t, s=s, buf=buf: unshard(s, buf)), s.b_unshard))
@@ -286,6 +313,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "units": len(states), "world_size": wl.world_size,
                    "grad_dtype": wl.grad_dtype, "unshard_dtype": "bf16", "rank": rank, "mode": args.mode,
+                   "prefetch_depth": args.depth if args.mode == "batch" else (1 if args.mode == "prefetch" else 0),
                    "hip_graph": use_graph, "launches_per_step": len(launches), "alg_bytes_per_step": step_bytes},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "roofline": roofline, "cpu_baseline": cpu, "kernels": per_kernel,

@@ -35,6 +35,7 @@ extern "C" {
 #endif
 
 typedef struct fsdp_layout fsdp_layout_t;   /* opaque, library-owned, host memory */
+typedef struct fsdp_batch fsdp_batch_t;     /* opaque, library-owned, host memory */
 
 /* FSDP_F16 is IEEE binary16; both 16-bit kinds travel as uint16_t bit patterns. */
 typedef enum { FSDP_F32 = 0, FSDP_BF16 = 1, FSDP_F16 = 2 } fsdp_dtype_t;
@@ -238,6 +239,36 @@ int fsdp_shard_adam_step_guarded(const fsdp_layout_t* layout, float* p_shard, co
 int fsdp_grad_scaler_update(float* scale, int32_t* growth_tracker, const float* found_inf,
                             float growth_factor, float backoff_factor, int32_t growth_interval,
                             void* hip_stream);
+
+/* ---- batches of independent operations in few launches ----------------------
+ * For units as small as a transformer block one kernel launch costs about as
+ * much as a third of the data movement (an empty kernel takes ~2 us back to
+ * back on MI355X), which is the paper's point about many small collectives
+ * (Sec. 3.2.1).  A batch records fused reduce-scatter + Adam operations and
+ * unshards that do NOT depend on each other (e.g. the updates of units i..i+2
+ * and the prefetched unshards of units i+3..i+5, Sec. 3.3.2 / 3.3.3) and issues
+ * them in as few grids as possible: up to 3 + 3 operations share one grid.
+ * Results are bit-identical to issuing the operations one by one.  Operations
+ * that cannot share a grid (W > 32, fp32 / fp16 unshard output, more than one
+ * operation above 128 MiB, different gradient dtype or divide mode) are issued
+ * through their own entry points, in order.
+ * The batch copies the pointer tables; layouts and device buffers must stay
+ * valid while the batch is used.  A batch may be launched any number of times;
+ * `step` is the Adam step count (after increment) of every update in it.  A
+ * batch is not thread-safe while it is being modified; launching an unmodified
+ * batch from several threads is. */
+int  fsdp_batch_create(fsdp_batch_t** out);
+void fsdp_batch_destroy(fsdp_batch_t* batch);                /* NULL is a no-op */
+int  fsdp_batch_clear(fsdp_batch_t* batch);
+int  fsdp_batch_add_unshard(fsdp_batch_t* batch, const fsdp_layout_t* layout,
+                            const float* const* shard_ptrs, void* flat_out, fsdp_dtype_t out_dtype);
+int  fsdp_batch_add_reduce_scatter_adam(fsdp_batch_t* batch, const fsdp_layout_t* layout,
+                                        const void* const* grad_ptrs, fsdp_dtype_t grad_dtype,
+                                        int32_t rank, float pre_div, float post_div,
+                                        float* grad_shard_out /* may be NULL */, float* p_shard,
+                                        float* exp_avg, float* exp_avg_sq, float lr, float beta1,
+                                        float beta2, float eps, void* p_lp_out /* may be NULL */);
+int  fsdp_batch_launch(const fsdp_batch_t* batch, int64_t step, void* hip_stream);
 
 /* Last hipError_t seen by this thread inside the library (0 if none). */
 int fsdp_last_hip_error(void);

@@ -5,6 +5,7 @@ thin ctypes binding with the same entry-point names.  PyTorch supplies device
 memory and streams only.
 """
 from .binding import (  # noqa: F401
+    Batch,
     FSDP_BF16,
     FSDP_F16,
     FSDP_F32,

@@ -71,6 +71,12 @@ _SIGNATURES = {
     "fsdp_shard_adam_step_guarded": [_vp, _vp, _vp, _vp, _vp, _i64, _f32, _f32, _f32, _f32, _vp, _vp],
     "fsdp_grad_scaler_update": [_vp, _vp, _vp, _f32, _f32, _i32, _vp],
     "fsdp_unshard_lp": [_vp, _pp, _vp, _vp],
+    "fsdp_batch_create": [ctypes.POINTER(_vp)],
+    "fsdp_batch_clear": [_vp],
+    "fsdp_batch_add_unshard": [_vp, _vp, _pp, _vp, ctypes.c_int],
+    "fsdp_batch_add_reduce_scatter_adam": [_vp, _vp, _pp, ctypes.c_int, _i32, _f32, _f32, _vp, _vp, _vp, _vp,
+                                           _f32, _f32, _f32, _f32, _vp],
+    "fsdp_batch_launch": [_vp, _i64, _vp],
     "fsdp_last_hip_error": [],
 }
 
@@ -90,6 +96,8 @@ def lib() -> ctypes.CDLL:
             fn.restype = ctypes.c_int
         l.fsdp_layout_destroy.argtypes = [_vp]
         l.fsdp_layout_destroy.restype = None
+        l.fsdp_batch_destroy.argtypes = [_vp]
+        l.fsdp_batch_destroy.restype = None
         l.fsdp_status_string.argtypes = [ctypes.c_int]
         l.fsdp_status_string.restype = ctypes.c_char_p
         _lib = l
@@ -407,3 +415,58 @@ def fsdp_grad_scaler_update(scale: torch.Tensor, growth_tracker: torch.Tensor, f
            lib().fsdp_grad_scaler_update(_vp(scale.data_ptr()), _vp(growth_tracker.data_ptr()),
                                          _vp(found_inf.data_ptr()), float(growth_factor), float(backoff_factor),
                                          int(growth_interval), _stream_handle(stream)))
+
+
+class Batch:
+    """Owner of a fsdp_batch_t: independent operations issued in few launches.
+    Keeps the tensors and layouts it was given alive."""
+
+    def __init__(self):
+        h = _vp()
+        _check("fsdp_batch_create", lib().fsdp_batch_create(ctypes.byref(h)))
+        self._h = h
+        self._keep = []
+
+    def clear(self) -> None:
+        _check("fsdp_batch_clear", lib().fsdp_batch_clear(self._h))
+        self._keep = []
+
+    def add_unshard(self, layout: Layout, shard_ptrs, flat_out: torch.Tensor) -> None:
+        shards = _ptr_table(shard_ptrs, torch.float32, layout.shard, layout.world_size, "shard_ptrs")
+        dt = _flat_dtype(flat_out)
+        _dev_tensor(flat_out, flat_out.dtype, layout.padded, "flat_out")
+        _check("fsdp_batch_add_unshard",
+               lib().fsdp_batch_add_unshard(self._h, layout.handle, shards.array, _vp(flat_out.data_ptr()), dt))
+        self._keep += [layout, shards, flat_out]
+
+    def add_reduce_scatter_adam(self, layout: Layout, grad_ptrs, rank: int, pre_div: float, post_div: float,
+                                grad_shard_out: Optional[torch.Tensor], p_shard, exp_avg, exp_avg_sq, lr: float,
+                                beta1: float, beta2: float, eps: float,
+                                p_lp_out: Optional[torch.Tensor] = None) -> None:
+        tab, gdt = _grad_table(layout, grad_ptrs)
+        S = layout.shard
+        g_out = _dev_tensor(grad_shard_out, torch.float32, S, "grad_shard_out") if grad_shard_out is not None else None
+        lp = _dev_tensor(p_lp_out, torch.bfloat16, S, "p_lp_out") if p_lp_out is not None else None
+        ptrs = [_dev_tensor(t, torch.float32, S, n) for t, n in
+                ((p_shard, "p_shard"), (exp_avg, "exp_avg"), (exp_avg_sq, "exp_avg_sq"))]
+        _check("fsdp_batch_add_reduce_scatter_adam",
+               lib().fsdp_batch_add_reduce_scatter_adam(self._h, layout.handle, tab.array, gdt, int(rank),
+                                                        float(pre_div), float(post_div), _vp(g_out),
+                                                        *[_vp(x) for x in ptrs], float(lr), float(beta1),
+                                                        float(beta2), float(eps), _vp(lp)))
+        self._keep += [layout, tab, grad_shard_out, p_shard, exp_avg, exp_avg_sq, p_lp_out]
+
+    def launch(self, step: int, stream=None) -> None:
+        _check("fsdp_batch_launch", lib().fsdp_batch_launch(self._h, int(step), _stream_handle(stream)))
+
+    def close(self) -> None:
+        if self._h is not None:
+            lib().fsdp_batch_destroy(self._h)
+            self._h = None
+            self._keep = []
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

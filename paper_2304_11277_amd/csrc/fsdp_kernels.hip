@@ -15,6 +15,8 @@
 
 #include <cmath>
 #include <cstdint>
+#include <new>
+#include <vector>
 
 #include "fsdp_internal.h"
 
@@ -124,12 +126,12 @@ __device__ __forceinline__ int64_t head_elems(const void* p, int esize, int64_t 
 // ---------------------------------------------------------------------------
 // bid = index of the workgroup among the unshard workgroups of the launch
 template <int LP>
-__device__ __forceinline__ void unshard_lp_body(const PtrTable& shards, int64_t S, uint16_t* __restrict__ out_base,
-                                                  int32_t tiles_per_shard, uint32_t bid)
+__device__ __forceinline__ void unshard_lp_body(const void* const* shards, int64_t S, uint16_t* __restrict__ out_base,
+                                                int32_t tiles_per_shard, uint32_t bid)
 {
     const int32_t w = bid / tiles_per_shard;
     const int32_t tile = bid - w * tiles_per_shard;
-    const float* __restrict__ src = static_cast<const float*>(shards.p[w]);
+    const float* __restrict__ src = static_cast<const float*>(shards[w]);
     uint16_t* __restrict__ dst = out_base + static_cast<int64_t>(w) * S;
 
     const int64_t head = head_elems(dst, 2, S);
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(kBlock) void unshard_lp_kernel(PtrTable shards, int
                                                              uint16_t* __restrict__ out_base,
                                                              int32_t tiles_per_shard)
 {
-    unshard_lp_body<LP>(shards, S, out_base, tiles_per_shard, blockIdx.x);
+    unshard_lp_body<LP>(shards.p, S, out_base, tiles_per_shard, blockIdx.x);
 }
 
 __global__ __launch_bounds__(kBlock) void unshard_f32_kernel(PtrTable shards, int64_t S,
@@ -384,16 +386,16 @@ __device__ __forceinline__ float post_scale(float x, const RsArgs& a)
 constexpr int kGroup = 8;
 
 template <int GT>
-__device__ __forceinline__ void load_ranks(const PtrTable& grads, int32_t w0, int64_t k, u32x4 (&x)[kGroup])
+__device__ __forceinline__ void load_ranks(const void* const* grads, int32_t w0, int64_t k, u32x4 (&x)[kGroup])
 {
 #pragma unroll
     for (int j = 0; j < kGroup; ++j) {
         if constexpr (GT != kF32)
             x[j] = __builtin_nontemporal_load(
-                reinterpret_cast<const u32x4_a2*>(static_cast<const uint16_t*>(grads.p[w0 + j]) + k));
+                reinterpret_cast<const u32x4_a2*>(static_cast<const uint16_t*>(grads[w0 + j]) + k));
         else
             x[j] = __builtin_nontemporal_load(
-                reinterpret_cast<const u32x4_a4*>(static_cast<const float*>(grads.p[w0 + j]) + k));
+                reinterpret_cast<const u32x4_a4*>(static_cast<const float*>(grads[w0 + j]) + k));
     }
 }
 
@@ -454,7 +456,7 @@ __device__ __forceinline__ void add_ranks(const u32x4 (&x)[kGroup], int32_t n, f
 // that the lane pays one memory latency, not two.  Everything a live lane does
 // sits under one branch, so the loads of a group issue back to back.
 template <int GT, int PRE, bool FUSED, bool PIPE, int B>
-__device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs& a, uint32_t bid)
+__device__ __forceinline__ void reduce_body(const void* const* grads, const RsArgs& a, uint32_t bid)
 {
     constexpr int E = GT != kF32 ? 8 : 4;
     constexpr int Q = E / 4;
@@ -586,7 +588,7 @@ __device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs&
             float outer_r = -0.0f;
             int32_t cnt = 0;
             for (int32_t w = 0; w < W; ++w) {
-                r = r + pre_scale<PRE>(load_grad<GT>(grads.p[w], k), a.pre_c);
+                r = r + pre_scale<PRE>(load_grad<GT>(grads[w], k), a.pre_c);
                 if (a.group > 0 && ++cnt == a.group) {
                     outer_r = outer_r + r;
                     r = -0.0f;
@@ -614,7 +616,7 @@ __device__ __forceinline__ void reduce_body(const PtrTable& grads, const RsArgs&
 template <int GT, int PRE, bool FUSED, bool PIPE, int B>
 __global__ __launch_bounds__(B) void reduce_kernel(PtrTable grads, RsArgs a)
 {
-    reduce_body<GT, PRE, FUSED, PIPE, B>(grads, a, blockIdx.x);
+    reduce_body<GT, PRE, FUSED, PIPE, B>(grads.p, a, blockIdx.x);
 }
 
 // Backward prefetching (Sec. 3.3.2) as one launch: the first n_reduce
@@ -629,9 +631,57 @@ __global__ __launch_bounds__(kBlock) void reduce_adam_unshard_kernel(PtrTable gr
                                                                       int32_t tiles_per_shard)
 {
     if (blockIdx.x < n_reduce)
-        reduce_body<GT, PRE, true, PIPE, kBlock>(grads, a, blockIdx.x);
+        reduce_body<GT, PRE, true, PIPE, kBlock>(grads.p, a, blockIdx.x);
     else
-        unshard_lp_body<kBF16>(shards, S_next, out_base, tiles_per_shard, blockIdx.x - n_reduce);
+        unshard_lp_body<kBF16>(shards.p, S_next, out_base, tiles_per_shard, blockIdx.x - n_reduce);
+}
+
+// ---------------------------------------------------------------------------
+// Batches of independent operations in one grid: up to kBatchOps fused
+// reduce-scatter + Adam operations and up to kBatchOps unshards of other units.
+// One launch floor for the whole batch, and the ramp and drain of the members
+// overlap.  Workgroups [0, r_end[n_reduce-1]) serve the reduce operations in
+// order, the rest the unshards.
+// ---------------------------------------------------------------------------
+constexpr int kBatchOps = 3;
+constexpr int kBatchRanks = 32;    // rank pointers per batched operation
+
+struct BatchReduceOp {
+    const void* grads[kBatchRanks];
+    RsArgs a;
+};
+struct BatchUnshardOp {
+    const void* shards[kBatchRanks];
+    int64_t S;
+    uint16_t* out;
+    int32_t tiles;
+    int32_t pad_;
+};
+struct BatchArgs {
+    int32_t n_reduce, n_unshard;
+    uint32_t r_end[kBatchOps];     // exclusive end of each reduce operation's workgroup range
+    uint32_t u_end[kBatchOps];     // same for the unshards, counted from the end of the reduce ranges
+    BatchReduceOp r[kBatchOps];
+    BatchUnshardOp u[kBatchOps];
+};
+
+template <int GT, int PRE, bool PIPE>
+__global__ __launch_bounds__(kBlock) void batch_kernel(BatchArgs b)
+{
+    uint32_t bid = blockIdx.x;
+    const uint32_t n_red_blocks = b.n_reduce > 0 ? b.r_end[b.n_reduce - 1] : 0u;
+    if (bid < n_red_blocks) {
+        int32_t i = 0;
+        uint32_t start = 0;
+        while (bid >= b.r_end[i]) { start = b.r_end[i]; ++i; }     // uniform, at most kBatchOps - 1 steps
+        reduce_body<GT, PRE, true, PIPE, kBlock>(b.r[i].grads, b.r[i].a, bid - start);
+    } else {
+        bid -= n_red_blocks;
+        int32_t i = 0;
+        uint32_t start = 0;
+        while (bid >= b.u_end[i]) { start = b.u_end[i]; ++i; }
+        unshard_lp_body<kBF16>(b.u[i].shards, b.u[i].S, b.u[i].out, b.u[i].tiles, bid - start);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -1337,6 +1387,260 @@ int fsdp_grad_scaler_update(float* scale, int32_t* growth_tracker, const float* 
     hipLaunchKernelGGL(scaler_update_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), scale,
                        growth_tracker, found_inf, growth_factor, backoff_factor, growth_interval);
     return launch_status();
+}
+
+}  // extern "C"
+
+// ---- batches ----------------------------------------------------------------
+
+struct fsdp_batch {
+    struct ReduceRec {
+        const fsdp_layout_t* L;
+        std::vector<const void*> grads;      // already advanced to the rank's slice
+        fsdp_dtype_t dtype;
+        int32_t rank;
+        float pre, post;
+        float *out, *p, *m, *v;
+        uint16_t* p_lp;
+        float lr, beta1, beta2, eps;
+        std::vector<const void*> raw;        // the caller's table, for the single-operation fallback
+    };
+    struct UnshardRec {
+        const fsdp_layout_t* L;
+        std::vector<const float*> shards;
+        void* out;
+        fsdp_dtype_t dtype;
+    };
+    struct Op {
+        bool is_reduce;
+        size_t index;
+    };
+    std::vector<ReduceRec> reduces;
+    std::vector<UnshardRec> unshards;
+    std::vector<Op> order;
+};
+
+namespace {
+
+struct ReduceKind {
+    int gt, pre_mode;
+    bool pipe;
+    bool operator==(const ReduceKind& o) const { return gt == o.gt && pre_mode == o.pre_mode && pipe == o.pipe; }
+};
+
+int pre_mode_of(float pre) {
+    float r;
+    if (pre == 1.0f) return kPreNone;
+    return is_pow2_float(pre, &r) ? kPreMul : kPreDiv;
+}
+
+template <int GT, int PRE>
+void launch_batch_pipe(bool pipe, const BatchArgs& b, uint32_t blocks, hipStream_t st)
+{
+    if (pipe) hipLaunchKernelGGL((batch_kernel<GT, PRE, true>), dim3(blocks), dim3(kBlock), 0, st, b);
+    else hipLaunchKernelGGL((batch_kernel<GT, PRE, false>), dim3(blocks), dim3(kBlock), 0, st, b);
+}
+template <int GT>
+void launch_batch_pre(const ReduceKind& k, const BatchArgs& b, uint32_t blocks, hipStream_t st)
+{
+    if (k.pre_mode == kPreNone) launch_batch_pipe<GT, kPreNone>(k.pipe, b, blocks, st);
+    else if (k.pre_mode == kPreMul) launch_batch_pipe<GT, kPreMul>(k.pipe, b, blocks, st);
+    else launch_batch_pipe<GT, kPreDiv>(k.pipe, b, blocks, st);
+}
+void launch_batch_grid(const ReduceKind& k, const BatchArgs& b, uint32_t blocks, hipStream_t st)
+{
+    if (k.gt == kBF16) launch_batch_pre<kBF16>(k, b, blocks, st);
+    else if (k.gt == kF16) launch_batch_pre<kF16>(k, b, blocks, st);
+    else launch_batch_pre<kF32>(k, b, blocks, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int fsdp_batch_create(fsdp_batch_t** out)
+{
+    if (!out) return FSDP_ERR_NULL_PTR;
+    *out = new (std::nothrow) fsdp_batch;
+    return *out ? FSDP_OK : FSDP_ERR_OOM;
+}
+
+void fsdp_batch_destroy(fsdp_batch_t* b) { delete b; }
+
+int fsdp_batch_clear(fsdp_batch_t* b)
+{
+    if (!b) return FSDP_ERR_NULL_PTR;
+    b->reduces.clear();
+    b->unshards.clear();
+    b->order.clear();
+    return FSDP_OK;
+}
+
+int fsdp_batch_add_unshard(fsdp_batch_t* b, const fsdp_layout_t* L, const float* const* shard_ptrs, void* flat_out,
+                           fsdp_dtype_t out_dtype)
+{
+    if (!b || !L || !shard_ptrs || !flat_out) return FSDP_ERR_NULL_PTR;
+    if (!valid_dtype(out_dtype)) return FSDP_ERR_BAD_DTYPE;
+    for (int32_t w = 0; w < L->world_size; ++w) {
+        if (!shard_ptrs[w]) return FSDP_ERR_NULL_PTR;
+        if (misaligned(shard_ptrs[w], 4)) return FSDP_ERR_INVALID_ARG;
+    }
+    if (misaligned(flat_out, static_cast<uintptr_t>(dtype_size(out_dtype)))) return FSDP_ERR_INVALID_ARG;
+    try {
+        fsdp_batch::UnshardRec r;
+        r.L = L;
+        r.shards.assign(shard_ptrs, shard_ptrs + L->world_size);
+        r.out = flat_out;
+        r.dtype = out_dtype;
+        b->unshards.push_back(std::move(r));
+        b->order.push_back({false, b->unshards.size() - 1});
+    } catch (const std::bad_alloc&) {
+        return FSDP_ERR_OOM;
+    }
+    return FSDP_OK;
+}
+
+int fsdp_batch_add_reduce_scatter_adam(fsdp_batch_t* b, const fsdp_layout_t* L, const void* const* grad_ptrs,
+                                       fsdp_dtype_t grad_dtype, int32_t rank, float pre_div, float post_div,
+                                       float* grad_shard_out, float* p_shard, float* exp_avg, float* exp_avg_sq,
+                                       float lr, float beta1, float beta2, float eps, void* p_lp_out)
+{
+    if (!b) return FSDP_ERR_NULL_PTR;
+    int rc = check_reduce_args(L, grad_ptrs, grad_dtype, rank, pre_div, post_div);
+    if (rc != FSDP_OK) return rc;
+    if (!p_shard || !exp_avg || !exp_avg_sq) return FSDP_ERR_NULL_PTR;
+    rc = check_adam_args(1, lr, beta1, beta2, eps);
+    if (rc != FSDP_OK) return rc;
+    if (L->world_size > kMaxRanks && !grad_shard_out) return FSDP_ERR_NULL_PTR;
+    if (misaligned(p_shard, 4) || misaligned(exp_avg, 4) || misaligned(exp_avg_sq, 4) ||
+        (grad_shard_out && misaligned(grad_shard_out, 4)) || (p_lp_out && misaligned(p_lp_out, 2)))
+        return FSDP_ERR_INVALID_ARG;
+    try {
+        fsdp_batch::ReduceRec r;
+        r.L = L;
+        r.raw.assign(grad_ptrs, grad_ptrs + L->world_size);
+        const int64_t off = static_cast<int64_t>(rank) * L->S * dtype_size(grad_dtype);
+        for (int32_t w = 0; w < L->world_size; ++w) r.grads.push_back(static_cast<const char*>(grad_ptrs[w]) + off);
+        r.dtype = grad_dtype;
+        r.rank = rank;
+        r.pre = pre_div;
+        r.post = post_div;
+        r.out = grad_shard_out;
+        r.p = p_shard; r.m = exp_avg; r.v = exp_avg_sq;
+        r.p_lp = static_cast<uint16_t*>(p_lp_out);
+        r.lr = lr; r.beta1 = beta1; r.beta2 = beta2; r.eps = eps;
+        b->reduces.push_back(std::move(r));
+        b->order.push_back({true, b->reduces.size() - 1});
+    } catch (const std::bad_alloc&) {
+        return FSDP_ERR_OOM;
+    }
+    return FSDP_OK;
+}
+
+int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
+{
+    if (!b) return FSDP_ERR_NULL_PTR;
+    if (step < 1) return FSDP_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+    // Greedy grouping in insertion order.  A grid takes up to kBatchOps reduce
+    // operations of one kernel kind and up to kBatchOps bf16 unshards, each with
+    // at most kBatchRanks ranks, and at most one operation above
+    // kOneLaunchMaxBytes (see the prefetch entry point).  Anything else is
+    // issued through its own entry point.
+    BatchArgs g = {};
+    ReduceKind kind = {kF32, kPreNone, false};
+    bool have_kind = false;
+    int large = 0;
+    uint32_t r_blocks = 0, u_blocks = 0;
+
+    auto flush = [&]() -> int {
+        if (g.n_reduce == 0 && g.n_unshard == 0) return FSDP_OK;
+        int rc = FSDP_OK;
+        // a grid without reduce operations never enters the reduce code, so any instantiation serves
+        if (g.n_reduce == 0) kind = ReduceKind{kF32, kPreNone, false};
+        launch_batch_grid(kind, g, r_blocks + u_blocks, st);
+        rc = launch_status();
+        g = BatchArgs{};
+        have_kind = false;
+        large = 0;
+        r_blocks = u_blocks = 0;
+        return rc;
+    };
+
+    for (const fsdp_batch::Op& op : b->order) {
+        if (op.is_reduce) {
+            const fsdp_batch::ReduceRec& r = b->reduces[op.index];
+            const int32_t W = r.L->world_size;
+            const int64_t bytes = dtype_size(r.dtype) * r.L->P + 24 * r.L->S;
+            const int64_t E = r.dtype == FSDP_F32 ? 4 : 8;
+            const int64_t nb = ceil_div(r.L->S / E + 1, kBlock);
+            const bool batchable = W <= kBatchRanks && grid_ok(nb + r_blocks + u_blocks);
+            if (!batchable) {
+                int rc = flush();
+                if (rc != FSDP_OK) return rc;
+                rc = fsdp_reduce_scatter_adam_fused(r.L, r.raw.data(), r.dtype, r.rank, r.pre, r.post, r.out, r.p, r.m, r.v,
+                                                    step, r.lr, r.beta1, r.beta2, r.eps, r.p_lp, hip_stream);
+                if (rc != FSDP_OK) return rc;
+                continue;
+            }
+            const ReduceKind k = {static_cast<int>(r.dtype), pre_mode_of(r.pre), W > kGroup};
+            const bool is_large = bytes > kOneLaunchMaxBytes;
+            if (g.n_reduce == kBatchOps || (have_kind && !(k == kind)) || (is_large && large > 0)) {
+                const int rc = flush();
+                if (rc != FSDP_OK) return rc;
+            }
+            kind = k;
+            have_kind = true;
+            large += is_large ? 1 : 0;
+            BatchReduceOp& o = g.r[g.n_reduce];
+            for (int32_t w = 0; w < kBatchRanks; ++w) o.grads[w] = r.grads[w < W ? w : W - 1];   // padded for whole groups
+            RsArgs& a = o.a;
+            a = RsArgs{};
+            float recip;
+            a.pre_c = r.pre;
+            if (k.pre_mode == kPreMul) { is_pow2_float(r.pre, &recip); a.pre_c = recip; }
+            a.post_c = r.post;
+            if (is_pow2_float(r.post, &recip)) { a.post_mul = 1; a.post_c = recip; }
+            a.W = W;
+            a.last = 1;
+            a.S = r.L->S;
+            a.out = r.out;
+            a.p = r.p; a.m = r.m; a.v = r.v; a.p_lp = r.p_lp;
+            a.adam = make_adam_consts(step, r.lr, r.beta1, r.beta2, r.eps);
+            r_blocks += static_cast<uint32_t>(nb);
+            g.r_end[g.n_reduce] = r_blocks;
+            ++g.n_reduce;
+        } else {
+            const fsdp_batch::UnshardRec& u = b->unshards[op.index];
+            const int32_t W = u.L->world_size;
+            const int64_t bytes = 6 * u.L->P;
+            const int64_t tiles = ceil_div(u.L->S / 8 + 1, kBlock);
+            const bool batchable = W <= kBatchRanks && u.dtype == FSDP_BF16 && grid_ok(tiles * W + r_blocks + u_blocks);
+            if (!batchable) {
+                int rc = flush();
+                if (rc != FSDP_OK) return rc;
+                rc = fsdp_unshard(u.L, u.shards.data(), u.out, u.dtype, hip_stream);
+                if (rc != FSDP_OK) return rc;
+                continue;
+            }
+            const bool is_large = bytes > kOneLaunchMaxBytes;
+            if (g.n_unshard == kBatchOps || (is_large && large > 0)) {
+                const int rc = flush();
+                if (rc != FSDP_OK) return rc;
+            }
+            large += is_large ? 1 : 0;
+            BatchUnshardOp& o = g.u[g.n_unshard];
+            for (int32_t w = 0; w < kBatchRanks; ++w) o.shards[w] = u.shards[w < W ? w : W - 1];
+            o.S = u.L->S;
+            o.out = static_cast<uint16_t*>(u.out);
+            o.tiles = static_cast<int32_t>(tiles);
+            u_blocks += static_cast<uint32_t>(tiles * W);
+            g.u_end[g.n_unshard] = u_blocks;
+            ++g.n_unshard;
+        }
+    }
+    return flush();
 }
 
 }  // extern "C"

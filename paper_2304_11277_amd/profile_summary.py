@@ -17,7 +17,8 @@ import csv
 import json
 import sys
 
-LIB_KERNELS = (("reduce_adam_unshard_kernel", "reduce_adam+unshard"), ("unshard", "unshard"),
+LIB_KERNELS = (("batch_kernel", "batch"), ("reduce_adam_unshard_kernel", "reduce_adam+unshard"),
+               ("unshard_lp_kernel", "unshard"), ("gather_lp_kernel", "unshard_lp"), ("accumulate_kernel", "grad_accumulate"), ("unshard", "unshard"),
                ("reduce_kernel", "reduce_adam"), ("adam_kernel", "adam"),
                ("pack_kernel", "pack"), ("fsdp_probe_copy", "probe_copy"))
 

@@ -264,6 +264,26 @@ def test_compute_entry_points_reject_bad_arguments_before_launch(L):
     assert raw.fsdp_unshard_lp(h, good4, None, st) == NULL
     assert raw.fsdp_unshard_lp(h, with_null, buf, st) == NULL
     assert raw.fsdp_unshard_lp(h, _table([0x10000, 0x10041, 0x10080, 0x100C0]), buf, st) == INVALID
+    # batches
+    bh = ctypes.c_void_p()
+    assert raw.fsdp_batch_create(None) == NULL
+    assert raw.fsdp_batch_create(ctypes.byref(bh)) == OK
+    assert raw.fsdp_batch_clear(None) == NULL
+    assert raw.fsdp_batch_add_unshard(None, h, good4, buf, 1) == NULL
+    assert raw.fsdp_batch_add_unshard(bh, None, good4, buf, 1) == NULL
+    assert raw.fsdp_batch_add_unshard(bh, h, with_null, buf, 1) == NULL
+    assert raw.fsdp_batch_add_unshard(bh, h, good4, buf, 7) == BAD_DTYPE
+    assert raw.fsdp_batch_add_unshard(bh, h, odd, buf, 1) == INVALID
+    add_r = raw.fsdp_batch_add_reduce_scatter_adam
+    assert add_r(bh, h, good4, 0, 9, f(2), f(2), None, p, m, v, *ok_h, None) == RANK_RANGE
+    assert add_r(bh, h, good4, 0, 0, f(2), f(2), None, None, m, v, *ok_h, None) == NULL
+    assert add_r(bh, h, good4, 0, 0, f(0), f(2), None, p, m, v, *ok_h, None) == INVALID
+    assert add_r(bh, h, good4, 0, 0, f(2), f(2), None, p, m, v, f(1e-4), f(1.5), f(0.999), f(1e-8), None) == INVALID
+    assert raw.fsdp_batch_launch(None, i64(1), st) == NULL
+    assert raw.fsdp_batch_launch(bh, i64(0), st) == INVALID
+    assert raw.fsdp_batch_launch(bh, i64(1), st) == OK          # an empty batch launches nothing
+    raw.fsdp_batch_destroy(bh)
+    raw.fsdp_batch_destroy(None)
     ga = raw.fsdp_grad_accumulate
     assert ga(None, buf, buf, 0, st) == NULL
     assert ga(h, None, buf, 0, st) == NULL

@@ -366,3 +366,68 @@ def test_prefetch_launch_equals_separate_calls(F, gdt, W, W_next, out_dt):
     h_sh = [np_f32(x) for x in shards_b]
     ref_flat = oracle.unshard_bf16(h_sh) if out_dt == torch.bfloat16 else oracle.unshard_f32(h_sh).view(np.uint32)
     assert same_bits(np_bits(flat2), ref_flat)
+
+
+@pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
+def test_batch_of_independent_operations_equals_single_calls(F, gdt):
+    """Three updates (W = 3, 8, 12, one of them with extra outputs) and four
+    unshards (one W = 100 and one fp32 output, which cannot share a grid) in one
+    batch: bit-identical to the single entry points, and the batch can be
+    launched again with another step count."""
+    specs = [(big_unit(), 3), (workloads.ragged_unit(), 8), (big_unit(), 12)]
+    reds = []
+    for i, (unit, W) in enumerate(specs):
+        lay = F.fsdp_layout_init(unit.shapes, W)
+        grads = make_grads(W, lay.padded, lay.numel, gdt, 800 + i)
+        p, _, m, v = _adam_state(lay.shard, 3, 31 + i, (i % 2, 0, 1, 0))
+        reds.append({"lay": lay, "grads": grads, "W": W, "r": W - 1, "p": p, "m": m, "v": v,
+                     "g": carve(lay.shard, torch.float32, 0, fill=POISON32) if i == 1 else None,
+                     "lp": carve(lay.shard, torch.bfloat16, 1, fill=POISON16) if i == 1 else None})
+    uns = []
+    for i, (W, dt) in enumerate([(8, torch.bfloat16), (100, torch.bfloat16), (5, torch.float32), (12, torch.bfloat16)]):
+        unit = workloads.Unit(f"u{i}", ((513 + i, 65), (7,), (20001,), (3, 3)))
+        lay = F.fsdp_layout_init(unit.shapes, W)
+        params = make_params(unit, 90 + i, misalign=True)
+        shards, _ = alloc_shards(W, lay.shard, "contig_odd")
+        F.fsdp_flatten_shard(lay, params, shards)
+        uns.append({"lay": lay, "shards": shards, "dt": dt})
+    batch = F.Batch()
+    flats_b, flats_s = [], []
+    for u in uns:
+        poison = POISON16 if u["dt"] == torch.bfloat16 else POISON32
+        flats_b.append(carve(u["lay"].padded, u["dt"], 1, fill=poison))
+        flats_s.append(carve(u["lay"].padded, u["dt"], 1, fill=poison))
+    order = [("u", 0), ("r", 0), ("u", 1), ("r", 1), ("r", 2), ("u", 2), ("u", 3)]
+    for kind, i in order:
+        if kind == "u":
+            batch.add_unshard(uns[i]["lay"], uns[i]["shards"], flats_b[i])
+        else:
+            d = reds[i]
+            pre, post = F.fsdp_default_divide_factors(d["W"])
+            batch.add_reduce_scatter_adam(d["lay"], d["grads"], d["r"], pre, post, d["g"], d["p"], d["m"], d["v"],
+                                          LR, B1, B2, EPS, d["lp"])
+    for step in (3, 4):
+        snap = [(d["p"].clone(), d["m"].clone(), d["v"].clone()) for d in reds]
+        batch.launch(step)
+        torch.cuda.synchronize()
+        for d, (p0, m0, v0) in zip(reds, snap):
+            pre, post = F.fsdp_default_divide_factors(d["W"])
+            gs = torch.empty(d["lay"].shard, dtype=torch.float32, device="cuda")
+            F.fsdp_reduce_scatter_adam_fused(d["lay"], d["grads"], d["r"], pre, post, gs, p0, m0, v0, step, LR, B1, B2,
+                                             EPS, None)
+            torch.cuda.synchronize()
+            for a, b, name in ((d["p"], p0, "p"), (d["m"], m0, "m"), (d["v"], v0, "v")):
+                assert same_bits(np_bits(a), np_bits(b)), f"step {step} {name}: {first_diff(np_bits(a), np_bits(b))}"
+            if d["g"] is not None:
+                assert same_bits(np_bits(d["g"]), np_bits(gs))
+                assert same_bits(np_bits(d["lp"]), oracle.cast_bf16(np_f32(d["p"])))
+            ref_g = oracle.reduce_scatter([np_grad(g) for g in d["grads"]], d["r"], pre, post)
+            assert same_bits(np_bits(gs), ref_g.view(np.uint32))
+        for u, fb, fs in zip(uns, flats_b, flats_s):
+            F.fsdp_unshard(u["lay"], u["shards"], fs)
+            torch.cuda.synchronize()
+            assert same_bits(np_bits(fb), np_bits(fs))
+            h = [np_f32(x) for x in u["shards"]]
+            ref = oracle.unshard_bf16(h) if u["dt"] == torch.bfloat16 else oracle.unshard_f32(h).view(np.uint32)
+            assert same_bits(np_bits(fb), ref)
+    batch.close()
