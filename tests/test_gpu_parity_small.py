@@ -431,3 +431,46 @@ def test_batch_of_independent_operations_equals_single_calls(F, gdt):
             ref = oracle.unshard_bf16(h) if u["dt"] == torch.bfloat16 else oracle.unshard_f32(h).view(np.uint32)
             assert same_bits(np_bits(fb), ref)
     batch.close()
+
+
+def test_fig3_worked_example_on_gpu(F):
+    """Sec. 3.2.1 / Fig. 3: a 4x3 Linear (12 weights + 3 biases) over 16 ranks:
+    one element per rank, the last rank holds the pad.  The whole path at S = 1."""
+    W = 16
+    shapes = [(3, 4), (3,)]
+    lay = F.fsdp_layout_init(shapes, W)
+    assert (lay.numel, lay.shard, lay.padded, lay.pad) == (15, 1, 16, 1)
+    w = torch.arange(1, 13, dtype=torch.float32, device="cuda").view(3, 4)
+    b = torch.arange(13, 16, dtype=torch.float32, device="cuda")
+    base = carve(W, torch.float32, 1, fill=POISON32)
+    shards = [base[i:i + 1] for i in range(W)]
+    F.fsdp_flatten_shard(lay, [w, b], shards)
+    torch.cuda.synchronize()
+    assert base.tolist() == [float(i) for i in range(1, 16)] + [0.0]
+    assert np_bits(shards[15])[0] == 0                                  # the pad is +0.0f on the last rank
+    flat = carve(16, torch.bfloat16, 3, fill=POISON16)
+    F.fsdp_unshard(lay, shards, flat)
+    grads = [torch.full((16,), float(r + 1), device="cuda") for r in range(W)]
+    for g in grads:
+        g[15] = 0.0                                                     # nothing is ever written to the pad's gradient
+    h_shards = [np_f32(s) for s in shards]
+    for r in range(W):
+        gs = torch.empty(1, device="cuda")
+        F.fsdp_reduce_scatter_local(lay, grads, r, 4.0, 4.0, gs)
+        m = torch.zeros(1, device="cuda")
+        v = torch.zeros(1, device="cuda")
+        F.fsdp_shard_adam_step(lay, shards[r], gs, m, v, 1, LR, B1, B2, EPS)
+        torch.cuda.synchronize()
+        ref_g = oracle.reduce_scatter([np_f32(g) for g in grads], r, 4.0, 4.0)
+        assert same_bits(np_bits(gs), ref_g.view(np.uint32))
+        assert float(gs[0]) == (8.5 if r < 15 else 0.0)                 # mean of 1..16
+        z = np.zeros(1, np.float32)
+        rp, rm, rv = oracle.adam_f32(h_shards[r], ref_g, z, z, 1, LR, B1, B2, EPS)
+        ok, bad = adam_close(np_f32(shards[r]), np_f32(m), np_f32(v), rp, rm, rv, h_shards[r])
+        assert ok, (r, bad)
+    torch.cuda.synchronize()
+    assert same_bits(np_bits(flat), oracle.unshard_bf16(h_shards))
+    assert float(shards[15][0]) == 0.0                                  # the pad stays zero through Adam
+    views = F.fsdp_views(lay, flat)
+    assert tuple(views[0].shape) == (3, 4) and tuple(views[1].shape) == (3,)
+    assert views[0].float().flatten().tolist() == [float(i) for i in range(1, 13)]
