@@ -383,7 +383,7 @@ __device__ __forceinline__ float post_scale(float x, const RsArgs& a)
 // loads issued back to back), then added strictly in rank order.  The host pads
 // the pointer table up to a multiple of kGroup with copies of the last rank's
 // pointer, so the loads need no predicate; the adds of the padding are skipped.
-constexpr int kGroup = 8;
+constexpr int kGroup = 4;   // 4 measured slightly ahead of 8 and 16 (fewer registers, more waves in flight)
 
 template <int GT>
 __device__ __forceinline__ void load_ranks(const void* const* grads, int32_t w0, int64_t k, u32x4 (&x)[kGroup])
@@ -450,8 +450,8 @@ __device__ __forceinline__ void add_ranks(const u32x4 (&x)[kGroup], int32_t n, f
 // rank).  The accumulator starts at -0.0f, the identity of IEEE addition
 // ((-0) + x == x bit for bit, signed zeros included), which is the same as
 // initialising it from rank 0's term; a later launch of a split W starts from
-// the carried partial sum instead.  Ranks are walked in groups of eight, two
-// groups in flight.
+// the carried partial sum instead.  Ranks are walked in groups of kGroup, two
+// groups in flight (W <= kGroup: one group).
 // In the fused form the chunk's Adam state is fetched before the rank loop so
 // that the lane pays one memory latency, not two.  Everything a live lane does
 // sits under one branch, so the loads of a group issue back to back.
