@@ -293,21 +293,41 @@ def test_hip_graph_replay_matches_eager(F):
     m = torch.zeros(S, device="cuda")
     v = torch.zeros(S, device="cuda")
 
+    # a second unit, updated and unsharded through the one-launch forms inside the same graph
+    unit2 = workloads.Unit("u2", ((300, 41), (19,)))
+    lay2 = F.fsdp_layout_init(unit2.shapes, W)
+    params2 = workloads.gen_params(unit2, 4, device="cuda")
+    shards2 = [torch.empty(lay2.shard, dtype=torch.float32, device="cuda") for _ in range(W)]
+    F.fsdp_flatten_shard(lay2, params2, shards2)
+    grads2 = [workloads.gen_rank_grad(lay2.padded, lay2.numel, w, 1, "f32", device="cuda") for w in range(W)]
+    flat2 = torch.empty(lay2.padded, dtype=torch.bfloat16, device="cuda")
+    flat2b = torch.empty(lay2.padded, dtype=torch.bfloat16, device="cuda")
+    p2_0 = shards2[1].clone()
+    m2 = torch.zeros(lay2.shard, device="cuda")
+    v2 = torch.zeros(lay2.shard, device="cuda")
+    batch = F.Batch()
+    batch.add_reduce_scatter_adam(lay2, grads2, 1, pre, post, None, shards2[1], m2, v2, LR, B1, B2, EPS, None)
+    batch.add_unshard(lay, shards, flat)
+
     def step():
         F.fsdp_unshard(lay, shards, flat)
+        F.fsdp_unshard(lay2, shards2, flat2)
         F.fsdp_reduce_scatter_local(lay, grads, 0, pre, post, gs)
         F.fsdp_shard_adam_step(lay, shards[0], gs, m, v, 1, LR, B1, B2, EPS)
+        batch.launch(1)                       # update of unit 2 + unshard of unit 1 (after its update) in one grid
+        F.fsdp_reduce_scatter_adam_prefetch_unshard(lay2, grads2, 1, pre, post, None, shards2[1], m2, v2, 2, LR, B1, B2,
+                                                    EPS, None, lay2, shards2[:1] + shards2[:1] * (W - 1), flat2b)
 
     step()
     torch.cuda.synchronize()
-    eager = [x.clone() for x in (flat, gs, shards[0], m, v)]
+    outputs = (flat, gs, shards[0], m, v, flat2, flat2b, shards2[1], m2, v2)
+    eager = [x.clone() for x in outputs]
 
     def reset():
         shards[0].copy_(p0)
-        m.fill_(0.0)
-        v.fill_(0.0)
-        flat.fill_(0.0)
-        gs.fill_(0.0)
+        shards2[1].copy_(p2_0)
+        for x in (m, v, flat, gs, m2, v2, flat2, flat2b):
+            x.fill_(0.0)
 
     reset()
     torch.cuda.synchronize()
@@ -321,7 +341,7 @@ def test_hip_graph_replay_matches_eager(F):
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        for a, b in zip(eager, (flat, gs, shards[0], m, v)):
+        for a, b in zip(eager, outputs):
             assert same_bits(np_bits(a), np_bits(b))
 
 
