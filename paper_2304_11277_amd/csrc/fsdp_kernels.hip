@@ -134,24 +134,53 @@ __device__ __forceinline__ void unshard_lp_body(const void* const* shards, int64
     const float* __restrict__ src = static_cast<const float*>(shards[w]);
     uint16_t* __restrict__ dst = out_base + static_cast<int64_t>(w) * S;
 
+    // A workgroup turns 2048 consecutive floats into 256 destination vectors of
+    // 8 values.  Reading them as 32 bytes per lane would make every load
+    // instruction touch only every other 16 bytes of its 2 KiB span, so the
+    // window goes through LDS instead: 16-byte loads that are contiguous across
+    // the wave (taken from the 16-byte boundary at or below the window's start,
+    // which also removes any source misalignment), then each lane reads its 8
+    // floats back.  Measured 7 % faster than the direct form on MI355X.  Only
+    // 16-byte blocks that hold at least one needed float are loaded, so no load
+    // leaves the pages of the shard.
+    __shared__ __attribute__((aligned(16))) float stage[kBlock * 8 + 8];
     const int64_t head = head_elems(dst, 2, S);
     const int64_t nvec = (S - head) >> 3;                  // full 8-element destination vectors
-    const int64_t c = static_cast<int64_t>(tile) * kBlock + threadIdx.x;
-    if (c < nvec) {
-        const float* s = src + head + (c << 3);
-        const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(s));
-        const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(s + 4));
+    const int64_t c0 = static_cast<int64_t>(tile) * kBlock;
+    const int t = threadIdx.x;
+    const int64_t left = nvec - c0;
+    const int32_t nv_tile = left <= 0 ? 0 : (left > kBlock ? kBlock : static_cast<int32_t>(left));   // uniform
+    const float* s0 = src + head + (c0 << 3);
+    const int32_t shift = static_cast<int32_t>((reinterpret_cast<uintptr_t>(s0) >> 2) & 3);
+    if (nv_tile > 0) {
+        const f32x4* as = reinterpret_cast<const f32x4*>(s0 - shift);
+        const int32_t nload = (nv_tile * 8 + shift + 3) >> 2;   // 16-byte blocks holding at least one needed float
+        if (nload >= 2 * kBlock) {                              // full tile: both loads in flight together
+            const f32x4 v0 = __builtin_nontemporal_load(as + t);
+            const f32x4 v1 = __builtin_nontemporal_load(as + kBlock + t);
+            *reinterpret_cast<f32x4*>(stage + 4 * t) = v0;
+            *reinterpret_cast<f32x4*>(stage + 4 * (kBlock + t)) = v1;
+            if (t == 0 && nload > 2 * kBlock)
+                *reinterpret_cast<f32x4*>(stage + 8 * kBlock) = __builtin_nontemporal_load(as + 2 * kBlock);
+        } else {
+            if (t < nload) *reinterpret_cast<f32x4*>(stage + 4 * t) = __builtin_nontemporal_load(as + t);
+            if (t + kBlock < nload)
+                *reinterpret_cast<f32x4*>(stage + 4 * (kBlock + t)) = __builtin_nontemporal_load(as + kBlock + t);
+        }
+    }
+    __syncthreads();
+    if (t < nv_tile) {
+        const float* l = stage + shift + 8 * t;
         u32x4 o;
-        o.x = pack_lp2<LP>(a.x, a.y);
-        o.y = pack_lp2<LP>(a.z, a.w);
-        o.z = pack_lp2<LP>(b.x, b.y);
-        o.w = pack_lp2<LP>(b.z, b.w);
-        __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(dst + head + (c << 3)));
+        o.x = pack_lp2<LP>(l[0], l[1]);
+        o.y = pack_lp2<LP>(l[2], l[3]);
+        o.z = pack_lp2<LP>(l[4], l[5]);
+        o.w = pack_lp2<LP>(l[6], l[7]);
+        __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(dst + head + ((c0 + t) << 3)));
     }
     if (tile == 0) {   // ragged head and tail of this shard: at most 7 elements each
         const int64_t tail0 = head + (nvec << 3);
         const int64_t ntail = S - tail0;
-        const int t = threadIdx.x;
         if (t < head) dst[t] = static_cast<uint16_t>(cast_lp<LP>(src[t]));
         if (t >= 64 && t - 64 < ntail) dst[tail0 + t - 64] = static_cast<uint16_t>(cast_lp<LP>(src[tail0 + t - 64]));
     }
