@@ -2,11 +2,18 @@
 //
 // Every step of the FlatParameter data path (arXiv 2304.11277, Sec. 3.2.1,
 // 3.2.3, 4.4, eq. (1), Sec. 5.4) is a streaming pass over HBM, so the kernels
-// share one shape: each lane moves 16-byte vectors, a 256-lane workgroup owns
-// a contiguous tile, the destination side is always 16-byte aligned (ragged
-// heads and tails are peeled off and handled element-wise) and sources that
-// are only element-aligned are read through under-aligned vector types.
-// Nothing here is a contraction, so there is no MFMA.
+// share one shape: each lane moves 16-byte vectors, every load and store
+// instruction covers one contiguous span across the wave, a 256-lane workgroup
+// owns a contiguous tile, the destination side is always 16-byte aligned
+// (ragged heads and tails are peeled off and handled element-wise) and sources
+// that are only element-aligned are read through under-aligned vector types or
+// realigned through LDS.  Nothing here is a contraction, so there is no MFMA.
+//
+// Layout of this file: device helpers (casts, vector types); unshard kernels;
+// the LDS-staged pack kernel; the reduce-scatter body with its Adam epilogue
+// and the kernels built from it (single, one-launch prefetch, batch); Adam;
+// gradient accumulation; gradient-scaler bookkeeping; then the host side:
+// argument checks, launch helpers and the extern "C" entry points.
 //
 // Build flags that matter for bit-exactness: -ffp-contract=off (no fused
 // multiply-add), IEEE-correct fp32 divide and sqrt (hipcc's default), fp32

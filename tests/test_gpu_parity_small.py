@@ -390,18 +390,18 @@ def test_prefetch_launch_equals_separate_calls(F, gdt, W, W_next, out_dt):
 
 @pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
 def test_batch_of_independent_operations_equals_single_calls(F, gdt):
-    """Three updates (W = 3, 8, 12, one of them with extra outputs) and four
-    unshards (one W = 100 and one fp32 output, which cannot share a grid) in one
-    batch: bit-identical to the single entry points, and the batch can be
+    """Four updates (W = 3, 8, 12 and 70, which is launched on its own; one with
+    extra outputs) and four unshards (one W = 100 and one fp32 output, which
+    cannot share a grid) in one batch: bit-identical to the single entry points, and the batch can be
     launched again with another step count."""
-    specs = [(big_unit(), 3), (workloads.ragged_unit(), 8), (big_unit(), 12)]
+    specs = [(big_unit(), 3), (workloads.ragged_unit(), 8), (big_unit(), 12), (workloads.ragged_unit(), 70)]
     reds = []
     for i, (unit, W) in enumerate(specs):
         lay = F.fsdp_layout_init(unit.shapes, W)
         grads = make_grads(W, lay.padded, lay.numel, gdt, 800 + i)
         p, _, m, v = _adam_state(lay.shard, 3, 31 + i, (i % 2, 0, 1, 0))
         reds.append({"lay": lay, "grads": grads, "W": W, "r": W - 1, "p": p, "m": m, "v": v,
-                     "g": carve(lay.shard, torch.float32, 0, fill=POISON32) if i == 1 else None,
+                     "g": carve(lay.shard, torch.float32, 0, fill=POISON32) if i in (1, 3) else None,   # W > 64 needs it
                      "lp": carve(lay.shard, torch.bfloat16, 1, fill=POISON16) if i == 1 else None})
     uns = []
     for i, (W, dt) in enumerate([(8, torch.bfloat16), (100, torch.bfloat16), (5, torch.float32), (12, torch.bfloat16)]):
@@ -417,7 +417,7 @@ def test_batch_of_independent_operations_equals_single_calls(F, gdt):
         poison = POISON16 if u["dt"] == torch.bfloat16 else POISON32
         flats_b.append(carve(u["lay"].padded, u["dt"], 1, fill=poison))
         flats_s.append(carve(u["lay"].padded, u["dt"], 1, fill=poison))
-    order = [("u", 0), ("r", 0), ("u", 1), ("r", 1), ("r", 2), ("u", 2), ("u", 3)]
+    order = [("u", 0), ("r", 0), ("u", 1), ("r", 1), ("r", 3), ("r", 2), ("u", 2), ("u", 3)]
     for kind, i in order:
         if kind == "u":
             batch.add_unshard(uns[i]["lay"], uns[i]["shards"], flats_b[i])
@@ -440,6 +440,7 @@ def test_batch_of_independent_operations_equals_single_calls(F, gdt):
                 assert same_bits(np_bits(a), np_bits(b)), f"step {step} {name}: {first_diff(np_bits(a), np_bits(b))}"
             if d["g"] is not None:
                 assert same_bits(np_bits(d["g"]), np_bits(gs))
+            if d["lp"] is not None:
                 assert same_bits(np_bits(d["lp"]), oracle.cast_bf16(np_f32(d["p"])))
             ref_g = oracle.reduce_scatter([np_grad(g) for g in d["grads"]], d["r"], pre, post)
             assert same_bits(np_bits(gs), ref_g.view(np.uint32))
