@@ -51,6 +51,8 @@ def parse_args():
     ap.add_argument("--next-rows", action="store_true",
                     help="measure the kernels beyond the hot path (hybrid-sharding reduce, gradient accumulation) "
                          "on the workload's largest unit and print their own JSON line")
+    ap.add_argument("--grad-sets", type=int, default=0,
+                    help="cap the number of distinct sets of gradient buffers per unit shape (0 = as many as fit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
@@ -136,8 +138,8 @@ def main():
     for i, u in enumerate(units):
         share = None
         need = wl.world_size * sum(workloads.numel(s) for s in u.shapes) * (4 if wl.grad_dtype == "f32" else 2)
-        if used + need > grad_budget:
-            same = [s for s in states if s.unit_shapes == u.shapes and s.owns_grads]
+        same = [s for s in states if s.unit_shapes == u.shapes and s.owns_grads]
+        if used + need > grad_budget or (args.grad_sets and len(same) >= args.grad_sets):
             share = same[len(states) % len(same)] if same else None
         st = UnitState(F, wl, u, i, torch, workloads, share_grads_with=share)
         st.unit_shapes, st.owns_grads = u.shapes, share is None

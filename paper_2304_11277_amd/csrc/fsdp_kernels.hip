@@ -415,198 +415,220 @@ __device__ __forceinline__ float post_scale(float x, const RsArgs& a)
     return a.post_mul ? x * a.post_c : x / a.post_c;
 }
 
-// Rank groups: kGroup ranks are loaded together (one 16-byte vector each, all
-// loads issued back to back), then added strictly in rank order.  The host pads
-// the pointer table up to a multiple of kGroup with copies of the last rank's
-// pointer, so the loads need no predicate; the adds of the padding are skipped.
-constexpr int kGroup = 4;   // 4 measured slightly ahead of 8 and 16 (fewer registers, more waves in flight)
-
-template <int GT>
-__device__ __forceinline__ void load_ranks(const void* const* grads, int32_t w0, int64_t k, u32x4 (&x)[kGroup])
-{
-#pragma unroll
-    for (int j = 0; j < kGroup; ++j) {
-        if constexpr (GT != kF32)
-            x[j] = __builtin_nontemporal_load(
-                reinterpret_cast<const u32x4_a2*>(static_cast<const uint16_t*>(grads[w0 + j]) + k));
-        else
-            x[j] = __builtin_nontemporal_load(
-                reinterpret_cast<const u32x4_a4*>(static_cast<const float*>(grads[w0 + j]) + k));
-    }
-}
-
-// Two-level state of the rank walk.  Flat sum: `acc` only.  Hybrid sharding
-// (Sec. 3.2.2): `acc` is the inner sum of the current sharded group; after every
-// `group` ranks it is folded into `outer` and restarted at -0.0f.
-template <int E>
-struct RankSum {
-    float acc[E];
-    float outer[E];
-    int32_t cnt;      // ranks added to the current group (uniform)
+// Shape of the rank walk.  A lane owns C chunks of E consecutive elements (E = 4
+// for fp32 gradients, 8 for 16-bit ones: one 16-byte load per rank and chunk);
+// chunk j of a lane lies B chunks after chunk j-1, so every load instruction is
+// contiguous across the wave.  Ranks are taken G at a time, two such batches in
+// flight: the next batch's G*C loads are issued before the current batch's adds
+// wait for their data, and the adds run strictly in rank order.
+//   wide  (G = 4, C = 1): four rank streams per batch.  Best for up to 8 ranks
+//         and for small units (it makes the most workgroups).
+//   deep  (G = 1, C = 4 or 2): one rank stream at a time, four (two) chunks of
+//         it.  With many ranks the wide form loses bandwidth (6.5 TB/s at W = 8,
+//         5.3 TB/s at W = 48 on MI355X: too many streams open at once); the
+//         deep form holds 6.4-6.6 TB/s from W = 8 to W = 48.
+// The host pads the pointer table to a multiple of kWideRanks with copies of the
+// last pointer, so loads never need a predicate; the padding's adds are skipped.
+constexpr int kWideRanks = 4;
+template <int GT, bool DEEP>
+struct WalkShape {
+    static constexpr int E = GT != kF32 ? 8 : 4;
+    static constexpr int G = DEEP ? 1 : kWideRanks;
+    static constexpr int C = DEEP ? (GT != kF32 ? 2 : 4) : 1;
 };
 
-template <int E>
-__device__ __forceinline__ void fold_group(RankSum<E>& s, int32_t group)
+template <int GT, int G, int C>
+__device__ __forceinline__ void load_batch(const void* const* grads, int32_t w0, const int64_t (&k)[C],
+                                           u32x4 (&x)[G][C])
 {
-    if (group > 0 && ++s.cnt == group) {   // uniform
 #pragma unroll
-        for (int e = 0; e < E; ++e) {
-            s.outer[e] = s.outer[e] + s.acc[e];
-            s.acc[e] = -0.0f;
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+        for (int j = 0; j < C; ++j) {
+            if constexpr (GT != kF32)
+                x[g][j] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x4_a2*>(static_cast<const uint16_t*>(grads[w0 + g]) + k[j]));
+            else
+                x[g][j] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x4_a4*>(static_cast<const float*>(grads[w0 + g]) + k[j]));
         }
-        s.cnt = 0;
     }
 }
 
-// adds x[0..n) in rank order; E = 4 elements per vector for fp32 gradients, 8 for bf16
-template <int GT, int PRE, int E>
-__device__ __forceinline__ void add_ranks(const u32x4 (&x)[kGroup], int32_t n, float pre_c, int32_t group,
-                                          RankSum<E>& s)
+// Adds the first n ranks of a batch, in rank order, to every chunk.  Hybrid
+// sharding (Sec. 3.2.2): acc is the inner sum of the current sharded group;
+// after every `group` ranks it is folded into outer and restarted at -0.0f.
+template <int GT, int PRE, int G, int C, int E>
+__device__ __forceinline__ void add_batch(const u32x4 (&x)[G][C], int32_t n, float pre_c, int32_t group,
+                                          int32_t& cnt, float (&acc)[C][E], float (&outer)[C][E])
 {
 #pragma unroll
-    for (int j = 0; j < kGroup; ++j) {
-        if (j < n) {   // uniform
-            float t[E];
-            if constexpr (GT != kF32) {   // exact upcast of eight 16-bit gradients
-                t[0] = up_lo<GT>(x[j].x); t[1] = up_hi<GT>(x[j].x);
-                t[2] = up_lo<GT>(x[j].y); t[3] = up_hi<GT>(x[j].y);
-                t[4] = up_lo<GT>(x[j].z); t[5] = up_hi<GT>(x[j].z);
-                t[6] = up_lo<GT>(x[j].w); t[7] = up_hi<GT>(x[j].w);
-            } else {
-                t[0] = u2f(x[j].x); t[1] = u2f(x[j].y); t[2] = u2f(x[j].z); t[3] = u2f(x[j].w);
+    for (int g = 0; g < G; ++g) {
+        if (g < n) {   // uniform
+#pragma unroll
+            for (int j = 0; j < C; ++j) {
+                float t[E];
+                if constexpr (GT != kF32) {   // exact upcast of eight 16-bit gradients
+                    t[0] = up_lo<GT>(x[g][j].x); t[1] = up_hi<GT>(x[g][j].x);
+                    t[2] = up_lo<GT>(x[g][j].y); t[3] = up_hi<GT>(x[g][j].y);
+                    t[4] = up_lo<GT>(x[g][j].z); t[5] = up_hi<GT>(x[g][j].z);
+                    t[6] = up_lo<GT>(x[g][j].w); t[7] = up_hi<GT>(x[g][j].w);
+                } else {
+                    t[0] = u2f(x[g][j].x); t[1] = u2f(x[g][j].y); t[2] = u2f(x[g][j].z); t[3] = u2f(x[g][j].w);
+                }
+#pragma unroll
+                for (int e = 0; e < E; ++e) acc[j][e] = acc[j][e] + pre_scale<PRE>(t[e], pre_c);
             }
+            if (group > 0 && ++cnt == group) {   // uniform
 #pragma unroll
-            for (int e = 0; e < E; ++e) s.acc[e] = s.acc[e] + pre_scale<PRE>(t[e], pre_c);
-            fold_group<E>(s, group);
+                for (int j = 0; j < C; ++j) {
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        outer[j][e] = outer[j][e] + acc[j][e];
+                        acc[j][e] = -0.0f;
+                    }
+                }
+                cnt = 0;
+            }
         }
     }
 }
 
-// One lane owns one chunk of E consecutive elements (one 16-byte load per
-// rank).  The accumulator starts at -0.0f, the identity of IEEE addition
-// ((-0) + x == x bit for bit, signed zeros included), which is the same as
-// initialising it from rank 0's term; a later launch of a split W starts from
-// the carried partial sum instead.  Ranks are walked in groups of kGroup, two
-// groups in flight (W <= kGroup: one group).
-// In the fused form the chunk's Adam state is fetched before the rank loop so
-// that the lane pays one memory latency, not two.  Everything a live lane does
-// sits under one branch, so the loads of a group issue back to back.
-template <int GT, int PRE, bool FUSED, bool PIPE, int B>
+// The accumulator starts at -0.0f, the identity of IEEE addition ((-0) + x == x
+// bit for bit, signed zeros included), which is the same as initialising it
+// from rank 0's term; a later launch of a split W starts from the carried
+// partial sum instead.  A lane whose later chunks fall past the end computes
+// them on a copy of its first chunk (no predicated loads: predicates made the
+// compiler serialise them) and skips their stores.
+template <int GT, int PRE, bool FUSED, bool DEEP, int B>
 __device__ __forceinline__ void reduce_body(const void* const* grads, const RsArgs& a, uint32_t bid)
 {
-    constexpr int E = GT != kF32 ? 8 : 4;
+    using Shape = WalkShape<GT, DEEP>;
+    constexpr int E = Shape::E, G = Shape::G, C = Shape::C;
     constexpr int Q = E / 4;
     // The chunk grid is aligned on the primary fp32 output.
     float* __restrict__ master = FUSED ? a.p : a.out;
     const int64_t S = a.S;
     const int64_t head = head_elems(master, 4, S);
     const int64_t nvec = (S - head) / E;
-    const int64_t c = static_cast<int64_t>(bid) * B + threadIdx.x;
+    const int64_t c0 = static_cast<int64_t>(bid) * (B * C) + threadIdx.x;
     const int32_t W = a.W;
 
-    if (c < nvec) {
-        const int64_t k = head + c * E;
-        f32x4 pv[Q], mv[Q], vv[Q];
-        if constexpr (FUSED) {
+    if (c0 < nvec) {
+        int64_t k[C];
+        bool live[C];
 #pragma unroll
-            for (int q = 0; q < Q; ++q) {
-                pv[q] = *reinterpret_cast<const f32x4*>(a.p + k + 4 * q);
-                mv[q] = *reinterpret_cast<const f32x4_a4*>(a.m + k + 4 * q);
-                vv[q] = *reinterpret_cast<const f32x4_a4*>(a.v + k + 4 * q);
+        for (int j = 0; j < C; ++j) {
+            const int64_t cj = c0 + static_cast<int64_t>(j) * B;
+            live[j] = cj < nvec;
+            k[j] = head + (live[j] ? cj : c0) * E;
+        }
+        float acc[C][E], outer[C][E];
+        int32_t cnt = 0;
+#pragma unroll
+        for (int j = 0; j < C; ++j) {
+            if (a.cont) {
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    const f32x4 t = *reinterpret_cast<const f32x4_a4*>(a.out + k[j] + 4 * q);
+                    acc[j][4 * q] = t.x; acc[j][4 * q + 1] = t.y; acc[j][4 * q + 2] = t.z; acc[j][4 * q + 3] = t.w;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < E; ++e) acc[j][e] = -0.0f;
             }
-        }
-        f32x4 old[Q];
-        if (a.accum) {   // gradient accumulation: fetch the running sum early
 #pragma unroll
-            for (int q = 0; q < Q; ++q) old[q] = *reinterpret_cast<const f32x4_a4*>(a.out + k + 4 * q);
-        }
-        RankSum<E> rs;
-        rs.cnt = 0;
-        float (&acc)[E] = rs.acc;
-        if (a.cont) {
-#pragma unroll
-            for (int q = 0; q < Q; ++q) {
-                const f32x4 t = *reinterpret_cast<const f32x4_a4*>(a.out + k + 4 * q);
-                acc[4 * q] = t.x; acc[4 * q + 1] = t.y; acc[4 * q + 2] = t.z; acc[4 * q + 3] = t.w;
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < E; ++e) acc[e] = -0.0f;
-        }
-#pragma unroll
-        for (int e = 0; e < E; ++e) rs.outer[e] = -0.0f;
-
-        if constexpr (PIPE) {
-            // W > kGroup: two groups in flight, the next group's loads are issued
-            // before the current group's adds wait for their data
-            u32x4 xa[kGroup], xb[kGroup];
-            const int32_t ngroups = (W + kGroup - 1) / kGroup;
-            load_ranks<GT>(grads, 0, k, xa);
-            for (int32_t g = 0; g < ngroups; g += 2) {
-                const bool has_b = g + 1 < ngroups;
-                if (has_b) load_ranks<GT>(grads, (g + 1) * kGroup, k, xb);
-                add_ranks<GT, PRE, E>(xa, W - g * kGroup, a.pre_c, a.group, rs);
-                if (g + 2 < ngroups) load_ranks<GT>(grads, (g + 2) * kGroup, k, xa);
-                if (has_b) add_ranks<GT, PRE, E>(xb, W - (g + 1) * kGroup, a.pre_c, a.group, rs);
-            }
-        } else {
-            // W <= kGroup: one group, fewer registers
-            u32x4 xa[kGroup];
-            load_ranks<GT>(grads, 0, k, xa);
-            add_ranks<GT, PRE, E>(xa, W, a.pre_c, a.group, rs);
-        }
-        if (a.group > 0) {   // every sharded group has been folded: the outer sum is the result
-#pragma unroll
-            for (int e = 0; e < E; ++e) acc[e] = rs.outer[e];
+            for (int e = 0; e < E; ++e) outer[j][e] = -0.0f;
         }
 
-        if (a.last) {
+        // The optimizer state (and the accumulated gradient) of the lane's chunks.
+        // The wide shape has the registers to fetch it ahead of the rank walk, off
+        // the critical path of small launches; the deep shape fetches it after.
+        f32x4 pv[C][Q], mv[C][Q], vv[C][Q], old[C][Q];
+        auto fetch_state = [&]() {
 #pragma unroll
-            for (int e = 0; e < E; ++e) acc[e] = post_scale(acc[e], a);
-        }
-        if (a.accum) {
+            for (int j = 0; j < C; ++j) {
 #pragma unroll
-            for (int q = 0; q < Q; ++q) {
-                acc[4 * q] = old[q].x + acc[4 * q];
-                acc[4 * q + 1] = old[q].y + acc[4 * q + 1];
-                acc[4 * q + 2] = old[q].z + acc[4 * q + 2];
-                acc[4 * q + 3] = old[q].w + acc[4 * q + 3];
+                for (int q = 0; q < Q; ++q) {
+                    if constexpr (FUSED) {
+                        pv[j][q] = *reinterpret_cast<const f32x4*>(a.p + k[j] + 4 * q);
+                        mv[j][q] = *reinterpret_cast<const f32x4_a4*>(a.m + k[j] + 4 * q);
+                        vv[j][q] = *reinterpret_cast<const f32x4_a4*>(a.v + k[j] + 4 * q);
+                    }
+                    if (a.accum) old[j][q] = *reinterpret_cast<const f32x4_a4*>(a.out + k[j] + 4 * q);
+                }
             }
+        };
+        if constexpr (!DEEP) fetch_state();
+
+        u32x4 xa[G][C], xb[G][C];
+        const int32_t nbatch = (W + G - 1) / G;
+        load_batch<GT, G, C>(grads, 0, k, xa);
+        for (int32_t b = 0; b < nbatch; b += 2) {
+            const bool has_b = b + 1 < nbatch;
+            if (has_b) load_batch<GT, G, C>(grads, (b + 1) * G, k, xb);
+            add_batch<GT, PRE, G, C, E>(xa, W - b * G, a.pre_c, a.group, cnt, acc, outer);
+            if (b + 2 < nbatch) load_batch<GT, G, C>(grads, (b + 2) * G, k, xa);
+            if (has_b) add_batch<GT, PRE, G, C, E>(xb, W - (b + 1) * G, a.pre_c, a.group, cnt, acc, outer);
         }
-        if (a.unscale) {   // sharded gradient scaler (Sec. 4.4): check, then unscale
-            bool bad = false;
+
+        if constexpr (DEEP) fetch_state();
 #pragma unroll
-            for (int e = 0; e < E; ++e) {
-                bad |= (f2u(acc[e]) & 0x7F800000u) == 0x7F800000u;
-                acc[e] = acc[e] * a.inv_scale;
-            }
-            if (bad) *a.found_inf = 1.0f;
-        }
-        if (a.out != nullptr) {
+        for (int j = 0; j < C; ++j) {
+            if (!live[j]) continue;
+            float (&r)[E] = acc[j];
+            if (a.group > 0) {   // every sharded group has been folded: the outer sum is the result
 #pragma unroll
-            for (int q = 0; q < Q; ++q) {
-                f32x4 o = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-                *reinterpret_cast<f32x4_a4*>(a.out + k + 4 * q) = o;
+                for (int e = 0; e < E; ++e) r[e] = outer[j][e];
             }
-        }
-        if constexpr (FUSED) {
-            uint32_t lp[E / 2];
+            if (a.last) {
 #pragma unroll
-            for (int q = 0; q < Q; ++q) {
-                adam_update4(pv[q], &acc[4 * q], mv[q], vv[q], a.adam);
-                *reinterpret_cast<f32x4*>(a.p + k + 4 * q) = pv[q];
-                *reinterpret_cast<f32x4_a4*>(a.m + k + 4 * q) = mv[q];
-                *reinterpret_cast<f32x4_a4*>(a.v + k + 4 * q) = vv[q];
-                lp[2 * q] = pack_bf16x2(pv[q].x, pv[q].y);
-                lp[2 * q + 1] = pack_bf16x2(pv[q].z, pv[q].w);
+                for (int e = 0; e < E; ++e) r[e] = post_scale(r[e], a);
             }
-            if (a.p_lp != nullptr) {
-                if constexpr (E == 8) {
-                    u32x4 o = {lp[0], lp[1], lp[2], lp[3]};
-                    *reinterpret_cast<u32x4_a2*>(a.p_lp + k) = o;
-                } else {
-                    u32x2 o = {lp[0], lp[1]};
-                    *reinterpret_cast<u32x2_a2*>(a.p_lp + k) = o;
+            if (a.accum) {
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    r[4 * q] = old[j][q].x + r[4 * q];
+                    r[4 * q + 1] = old[j][q].y + r[4 * q + 1];
+                    r[4 * q + 2] = old[j][q].z + r[4 * q + 2];
+                    r[4 * q + 3] = old[j][q].w + r[4 * q + 3];
+                }
+            }
+            if (a.unscale) {   // sharded gradient scaler (Sec. 4.4): check, then unscale
+                bool bad = false;
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    bad |= (f2u(r[e]) & 0x7F800000u) == 0x7F800000u;
+                    r[e] = r[e] * a.inv_scale;
+                }
+                if (bad) *a.found_inf = 1.0f;
+            }
+            if (a.out != nullptr) {
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    f32x4 o = {r[4 * q], r[4 * q + 1], r[4 * q + 2], r[4 * q + 3]};
+                    *reinterpret_cast<f32x4_a4*>(a.out + k[j] + 4 * q) = o;
+                }
+            }
+            if constexpr (FUSED) {
+                uint32_t lp[E / 2];
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    adam_update4(pv[j][q], &r[4 * q], mv[j][q], vv[j][q], a.adam);
+                    *reinterpret_cast<f32x4*>(a.p + k[j] + 4 * q) = pv[j][q];
+                    *reinterpret_cast<f32x4_a4*>(a.m + k[j] + 4 * q) = mv[j][q];
+                    *reinterpret_cast<f32x4_a4*>(a.v + k[j] + 4 * q) = vv[j][q];
+                    lp[2 * q] = pack_bf16x2(pv[j][q].x, pv[j][q].y);
+                    lp[2 * q + 1] = pack_bf16x2(pv[j][q].z, pv[j][q].w);
+                }
+                if (a.p_lp != nullptr) {
+                    if constexpr (E == 8) {
+                        u32x4 o = {lp[0], lp[1], lp[2], lp[3]};
+                        *reinterpret_cast<u32x4_a2*>(a.p_lp + k[j]) = o;
+                    } else {
+                        u32x2 o = {lp[0], lp[1]};
+                        *reinterpret_cast<u32x2_a2*>(a.p_lp + k[j]) = o;
+                    }
                 }
             }
         }
@@ -649,10 +671,10 @@ __device__ __forceinline__ void reduce_body(const void* const* grads, const RsAr
     }
 }
 
-template <int GT, int PRE, bool FUSED, bool PIPE, int B>
+template <int GT, int PRE, bool FUSED, bool DEEP, int B>
 __global__ __launch_bounds__(B) void reduce_kernel(PtrTable grads, RsArgs a)
 {
-    reduce_body<GT, PRE, FUSED, PIPE, B>(grads.p, a, blockIdx.x);
+    reduce_body<GT, PRE, FUSED, DEEP, B>(grads.p, a, blockIdx.x);
 }
 
 // Backward prefetching (Sec. 3.3.2) as one launch: the first n_reduce
@@ -660,14 +682,14 @@ __global__ __launch_bounds__(B) void reduce_kernel(PtrTable grads, RsArgs a)
 // unshard of another unit.  The two do not depend on each other, so sharing a
 // grid lets the drain of one overlap the ramp of the other without any
 // cross-queue synchronisation.
-template <int GT, int PRE, bool PIPE>
+template <int GT, int PRE>
 __global__ __launch_bounds__(kBlock) void reduce_adam_unshard_kernel(PtrTable grads, RsArgs a, uint32_t n_reduce,
                                                                       PtrTable shards, int64_t S_next,
                                                                       uint16_t* __restrict__ out_base,
                                                                       int32_t tiles_per_shard)
 {
     if (blockIdx.x < n_reduce)
-        reduce_body<GT, PRE, true, PIPE, kBlock>(grads.p, a, blockIdx.x);
+        reduce_body<GT, PRE, true, false, kBlock>(grads.p, a, blockIdx.x);
     else
         unshard_lp_body<kBF16>(shards.p, S_next, out_base, tiles_per_shard, blockIdx.x - n_reduce);
 }
@@ -701,7 +723,7 @@ struct BatchArgs {
     BatchUnshardOp u[kBatchOps];
 };
 
-template <int GT, int PRE, bool PIPE>
+template <int GT, int PRE>
 __global__ __launch_bounds__(kBlock) void batch_kernel(BatchArgs b)
 {
     uint32_t bid = blockIdx.x;
@@ -710,7 +732,7 @@ __global__ __launch_bounds__(kBlock) void batch_kernel(BatchArgs b)
         int32_t i = 0;
         uint32_t start = 0;
         while (bid >= b.r_end[i]) { start = b.r_end[i]; ++i; }     // uniform, at most kBatchOps - 1 steps
-        reduce_body<GT, PRE, true, PIPE, kBlock>(b.r[i].grads, b.r[i].a, bid - start);
+        reduce_body<GT, PRE, true, false, kBlock>(b.r[i].grads, b.r[i].a, bid - start);
     } else {
         bid -= n_red_blocks;
         int32_t i = 0;
@@ -888,25 +910,33 @@ AdamConsts make_adam_consts(int64_t step, float lr, float b1, float b2, float ep
     return c;
 }
 
-// the reduce kernel loads whole groups of kGroup ranks: repeat the last pointer up to the group boundary
+// the wide rank walk loads whole batches of kWideRanks ranks: repeat the last pointer up to the batch boundary
 void pad_rank_table(PtrTable& tab, int32_t n)
 {
-    static_assert(kMaxRanks % kGroup == 0, "the padded table must fit");
-    for (int32_t j = n; j % kGroup != 0; ++j) tab.p[j] = tab.p[n - 1];
+    static_assert(kMaxRanks % kWideRanks == 0, "the padded table must fit");
+    for (int32_t j = n; j % kWideRanks != 0; ++j) tab.p[j] = tab.p[n - 1];
 }
+
+// The deep rank walk pays from about ten rank streams on, provided it still
+// makes at least four workgroups per compute unit (256 of them on MI355X):
+// with three it measured 6 % slower than the wide walk at 64 ranks.
+constexpr int32_t kDeepMinRanks = 10;
+constexpr int64_t kDeepMinBlocks = 4 * 256;
 
 template <int GT, int PRE, bool FUSED>
 void launch_reduce(const PtrTable& tab, const RsArgs& a, hipStream_t st)
 {
-    constexpr int E = GT != kF32 ? 8 : 4;
     constexpr int B = kReduceBlock;
-    const int64_t blocks = ceil_div(a.S / E + 1, B);
-    if (a.W > kGroup)
-        hipLaunchKernelGGL((reduce_kernel<GT, PRE, FUSED, true, B>), dim3(static_cast<uint32_t>(blocks)), dim3(B), 0,
-                           st, tab, a);
-    else
-        hipLaunchKernelGGL((reduce_kernel<GT, PRE, FUSED, false, B>), dim3(static_cast<uint32_t>(blocks)), dim3(B),
+    constexpr int E = WalkShape<GT, true>::E;
+    const int64_t deep_blocks = ceil_div(a.S / E + 1, B * WalkShape<GT, true>::C);
+    if (a.W >= kDeepMinRanks && deep_blocks >= kDeepMinBlocks) {
+        hipLaunchKernelGGL((reduce_kernel<GT, PRE, FUSED, true, B>), dim3(static_cast<uint32_t>(deep_blocks)), dim3(B),
                            0, st, tab, a);
+    } else {
+        const int64_t blocks = ceil_div(a.S / E + 1, B);
+        hipLaunchKernelGGL((reduce_kernel<GT, PRE, FUSED, false, B>), dim3(static_cast<uint32_t>(blocks)), dim3(B), 0,
+                           st, tab, a);
+    }
 }
 
 template <int GT, bool FUSED>
@@ -1257,15 +1287,9 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* L, const void
     const uint32_t nr = static_cast<uint32_t>(n_reduce);
     uint16_t* out_base = static_cast<uint16_t*>(next_flat_out);
     const int32_t tl = static_cast<int32_t>(tiles);
-#define FSDP_LAUNCH_COMBINED(BF, PRE)                                                                              \
-    do {                                                                                                           \
-        if (a.W > kGroup)                                                                                          \
-            hipLaunchKernelGGL((reduce_adam_unshard_kernel<BF, PRE, true>), grid, dim3(kBlock), 0, st, gtab, a, nr, \
-                               stab, N->S, out_base, tl);                                                          \
-        else                                                                                                       \
-            hipLaunchKernelGGL((reduce_adam_unshard_kernel<BF, PRE, false>), grid, dim3(kBlock), 0, st, gtab, a,    \
-                               nr, stab, N->S, out_base, tl);                                                      \
-    } while (0)
+#define FSDP_LAUNCH_COMBINED(BF, PRE) \
+    hipLaunchKernelGGL((reduce_adam_unshard_kernel<BF, PRE>), grid, dim3(kBlock), 0, st, gtab, a, nr, stab, N->S, \
+                       out_base, tl)
     if (grad_dtype == FSDP_BF16) {
         if (pre_mode == kPreNone) FSDP_LAUNCH_COMBINED(kBF16, kPreNone);
         else if (pre_mode == kPreMul) FSDP_LAUNCH_COMBINED(kBF16, kPreMul);
@@ -1460,8 +1484,7 @@ namespace {
 
 struct ReduceKind {
     int gt, pre_mode;
-    bool pipe;
-    bool operator==(const ReduceKind& o) const { return gt == o.gt && pre_mode == o.pre_mode && pipe == o.pipe; }
+    bool operator==(const ReduceKind& o) const { return gt == o.gt && pre_mode == o.pre_mode; }
 };
 
 int pre_mode_of(float pre) {
@@ -1470,18 +1493,15 @@ int pre_mode_of(float pre) {
     return is_pow2_float(pre, &r) ? kPreMul : kPreDiv;
 }
 
-template <int GT, int PRE>
-void launch_batch_pipe(bool pipe, const BatchArgs& b, uint32_t blocks, hipStream_t st)
-{
-    if (pipe) hipLaunchKernelGGL((batch_kernel<GT, PRE, true>), dim3(blocks), dim3(kBlock), 0, st, b);
-    else hipLaunchKernelGGL((batch_kernel<GT, PRE, false>), dim3(blocks), dim3(kBlock), 0, st, b);
-}
 template <int GT>
 void launch_batch_pre(const ReduceKind& k, const BatchArgs& b, uint32_t blocks, hipStream_t st)
 {
-    if (k.pre_mode == kPreNone) launch_batch_pipe<GT, kPreNone>(k.pipe, b, blocks, st);
-    else if (k.pre_mode == kPreMul) launch_batch_pipe<GT, kPreMul>(k.pipe, b, blocks, st);
-    else launch_batch_pipe<GT, kPreDiv>(k.pipe, b, blocks, st);
+    if (k.pre_mode == kPreNone)
+        hipLaunchKernelGGL((batch_kernel<GT, kPreNone>), dim3(blocks), dim3(kBlock), 0, st, b);
+    else if (k.pre_mode == kPreMul)
+        hipLaunchKernelGGL((batch_kernel<GT, kPreMul>), dim3(blocks), dim3(kBlock), 0, st, b);
+    else
+        hipLaunchKernelGGL((batch_kernel<GT, kPreDiv>), dim3(blocks), dim3(kBlock), 0, st, b);
 }
 void launch_batch_grid(const ReduceKind& k, const BatchArgs& b, uint32_t blocks, hipStream_t st)
 {
@@ -1585,7 +1605,7 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
     // kOneLaunchMaxBytes (see the prefetch entry point).  Anything else is
     // issued through its own entry point.
     BatchArgs g = {};
-    ReduceKind kind = {kF32, kPreNone, false};
+    ReduceKind kind = {kF32, kPreNone};
     bool have_kind = false;
     int large = 0;
     uint32_t r_blocks = 0, u_blocks = 0;
@@ -1594,7 +1614,7 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
         if (g.n_reduce == 0 && g.n_unshard == 0) return FSDP_OK;
         int rc = FSDP_OK;
         // a grid without reduce operations never enters the reduce code, so any instantiation serves
-        if (g.n_reduce == 0) kind = ReduceKind{kF32, kPreNone, false};
+        if (g.n_reduce == 0) kind = ReduceKind{kF32, kPreNone};
         launch_batch_grid(kind, g, r_blocks + u_blocks, st);
         rc = launch_status();
         g = BatchArgs{};
@@ -1620,7 +1640,7 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
                 if (rc != FSDP_OK) return rc;
                 continue;
             }
-            const ReduceKind k = {static_cast<int>(r.dtype), pre_mode_of(r.pre), W > kGroup};
+            const ReduceKind k = {static_cast<int>(r.dtype), pre_mode_of(r.pre)};
             const bool is_large = bytes > kOneLaunchMaxBytes;
             if (g.n_reduce == kBatchOps || (have_kind && !(k == kind)) || (is_large && large > 0)) {
                 const int rc = flush();
