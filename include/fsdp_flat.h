@@ -270,6 +270,20 @@ int  fsdp_batch_add_reduce_scatter_adam(fsdp_batch_t* batch, const fsdp_layout_t
                                         float beta2, float eps, void* p_lp_out /* may be NULL */);
 int  fsdp_batch_launch(const fsdp_batch_t* batch, int64_t step, void* hip_stream);
 
+/* Tuning and test knob: how the stand-alone reduce-scatter kernels
+ * (fsdp_reduce_scatter_local, _adam_fused, _hybrid, _accumulate, _unscale, and
+ * the two-launch form of _prefetch_unshard) walk the W rank buffers of the
+ * reduce-scatter of Sec. 3 / eq. (1).  Both walks add in rank order and give
+ * the same bits.
+ *   FSDP_WALK_WIDE: a lane owns one 16-byte chunk and loads four ranks at a time;
+ *   FSDP_WALK_DEEP: a lane owns several chunks and loads one rank at a time;
+ *   FSDP_WALK_AUTO (default): deep from ten ranks on when the shard is large
+ *                   enough to still fill the chip, else wide.
+ * Process-wide; takes effect for launches issued after the call returns.
+ * Returns FSDP_ERR_INVALID_ARG for any other value. */
+enum { FSDP_WALK_AUTO = 0, FSDP_WALK_WIDE = 1, FSDP_WALK_DEEP = 2 };
+int fsdp_set_reduce_walk(int32_t walk);
+
 /* Last hipError_t seen by this thread inside the library (0 if none). */
 int fsdp_last_hip_error(void);
 /* Static string for a fsdp_status_t. */

@@ -9,6 +9,9 @@ from .binding import (  # noqa: F401
     FSDP_BF16,
     FSDP_F16,
     FSDP_F32,
+    FSDP_WALK_AUTO,
+    FSDP_WALK_DEEP,
+    FSDP_WALK_WIDE,
     FsdpError,
     Layout,
     PtrArray,
@@ -25,6 +28,7 @@ from .binding import (  # noqa: F401
     fsdp_reduce_scatter_hybrid,
     fsdp_reduce_scatter_local,
     fsdp_reduce_scatter_unscale,
+    fsdp_set_reduce_walk,
     fsdp_shard_adam_step,
     fsdp_shard_adam_step_guarded,
     fsdp_unshard,

@@ -17,6 +17,9 @@ import torch
 FSDP_F32 = 0
 FSDP_BF16 = 1
 FSDP_F16 = 2
+FSDP_WALK_AUTO = 0
+FSDP_WALK_WIDE = 1
+FSDP_WALK_DEEP = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfsdp_flat.so")
@@ -77,6 +80,7 @@ _SIGNATURES = {
     "fsdp_batch_add_reduce_scatter_adam": [_vp, _vp, _pp, ctypes.c_int, _i32, _f32, _f32, _vp, _vp, _vp, _vp,
                                            _f32, _f32, _f32, _f32, _vp],
     "fsdp_batch_launch": [_vp, _i64, _vp],
+    "fsdp_set_reduce_walk": [_i32],
     "fsdp_last_hip_error": [],
 }
 
@@ -415,6 +419,11 @@ def fsdp_grad_scaler_update(scale: torch.Tensor, growth_tracker: torch.Tensor, f
            lib().fsdp_grad_scaler_update(_vp(scale.data_ptr()), _vp(growth_tracker.data_ptr()),
                                          _vp(found_inf.data_ptr()), float(growth_factor), float(backoff_factor),
                                          int(growth_interval), _stream_handle(stream)))
+
+
+def fsdp_set_reduce_walk(walk: int) -> None:
+    """Process-wide choice of the reduce-scatter kernels' rank walk (FSDP_WALK_AUTO / _WIDE / _DEEP)."""
+    _check("fsdp_set_reduce_walk", lib().fsdp_set_reduce_walk(int(walk)))
 
 
 class Batch:

@@ -20,6 +20,7 @@
 // denormals kept (gfx950's default).
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <new>
@@ -922,6 +923,7 @@ void pad_rank_table(PtrTable& tab, int32_t n)
 // with three it measured 6 % slower than the wide walk at 64 ranks.
 constexpr int32_t kDeepMinRanks = 10;
 constexpr int64_t kDeepMinBlocks = 4 * 256;
+std::atomic<int32_t> g_reduce_walk{FSDP_WALK_AUTO};      // fsdp_set_reduce_walk
 
 template <int GT, int PRE, bool FUSED>
 void launch_reduce(const PtrTable& tab, const RsArgs& a, hipStream_t st)
@@ -929,7 +931,10 @@ void launch_reduce(const PtrTable& tab, const RsArgs& a, hipStream_t st)
     constexpr int B = kReduceBlock;
     constexpr int E = WalkShape<GT, true>::E;
     const int64_t deep_blocks = ceil_div(a.S / E + 1, B * WalkShape<GT, true>::C);
-    if (a.W >= kDeepMinRanks && deep_blocks >= kDeepMinBlocks) {
+    const int32_t walk = g_reduce_walk.load(std::memory_order_relaxed);
+    const bool deep = walk == FSDP_WALK_AUTO ? a.W >= kDeepMinRanks && deep_blocks >= kDeepMinBlocks
+                                             : walk == FSDP_WALK_DEEP;
+    if (deep) {
         hipLaunchKernelGGL((reduce_kernel<GT, PRE, FUSED, true, B>), dim3(static_cast<uint32_t>(deep_blocks)), dim3(B),
                            0, st, tab, a);
     } else {
@@ -1040,6 +1045,13 @@ int check_reduce_args(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp
 }  // namespace
 
 extern "C" {
+
+int fsdp_set_reduce_walk(int32_t walk)
+{
+    if (walk != FSDP_WALK_AUTO && walk != FSDP_WALK_WIDE && walk != FSDP_WALK_DEEP) return FSDP_ERR_INVALID_ARG;
+    g_reduce_walk.store(walk, std::memory_order_relaxed);
+    return FSDP_OK;
+}
 
 int fsdp_flatten_shard(const fsdp_layout_t* L, const void* const* param_ptrs, float* const* shard_ptrs,
                        void* hip_stream)

@@ -1,4 +1,5 @@
 import os
+import re
 import sys
 
 import pytest
@@ -15,3 +16,32 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+# GPU tests whose names match run once per rank walk of the reduce-scatter
+# kernels: the library's own choice (wide at test sizes) and the deep walk
+# forced, so that the deep kernels see the ragged, misaligned, split-W, hybrid,
+# accumulate and unscale cases at small sizes too.
+_WALK_TESTS = re.compile(r"reduce|fused|hybrid|accumul|unscale|scaler|whole_path|graph|prefetch|fig3")
+
+
+def pytest_generate_tests(metafunc):
+    if metafunc.definition.get_closest_marker("gpu") is None and not any(
+            m.name == "gpu" for m in getattr(metafunc.module, "pytestmark", []) or []):
+        return
+    if "_reduce_walk" in metafunc.fixturenames and _WALK_TESTS.search(metafunc.function.__name__):
+        metafunc.parametrize("_reduce_walk", ["auto", "deep"], indirect=True)
+
+
+@pytest.fixture(autouse=True)
+def _reduce_walk(request):
+    walk = getattr(request, "param", None)
+    if walk is None:
+        yield
+        return
+    import paper_2304_11277_amd as F
+    F.fsdp_set_reduce_walk(F.FSDP_WALK_DEEP if walk == "deep" else F.FSDP_WALK_AUTO)
+    try:
+        yield
+    finally:
+        F.fsdp_set_reduce_walk(F.FSDP_WALK_AUTO)

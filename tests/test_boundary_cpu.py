@@ -308,3 +308,13 @@ def test_binding_rejects_host_tensors(L):
     with pytest.raises(TypeError):
         L.fsdp_unshard(lay, cpu, torch.zeros(16, dtype=torch.bfloat16))
     assert L.lib().fsdp_status_string(-6) == b"rank or parameter index out of range"
+
+
+def test_set_reduce_walk_accepts_only_its_three_values(L):
+    raw = L.lib()
+    for bad in (-1, 3, 100):
+        assert raw.fsdp_set_reduce_walk(bad) == INVALID
+    for ok in (L.FSDP_WALK_WIDE, L.FSDP_WALK_DEEP, L.FSDP_WALK_AUTO):
+        assert raw.fsdp_set_reduce_walk(ok) == OK
+    with pytest.raises(L.FsdpError):
+        L.fsdp_set_reduce_walk(7)
