@@ -51,6 +51,8 @@ def parse_args():
     ap.add_argument("--next-rows", action="store_true",
                     help="measure the kernels beyond the hot path (hybrid-sharding reduce, gradient accumulation) "
                          "on the workload's largest unit and print their own JSON line")
+    ap.add_argument("--walk", choices=["auto", "wide", "deep"], default="auto",
+                    help="rank walk of the stand-alone reduce-scatter kernels (fsdp_set_reduce_walk)")
     ap.add_argument("--grad-sets", type=int, default=0,
                     help="cap the number of distinct sets of gradient buffers per unit shape (0 = as many as fit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -123,6 +125,7 @@ def main():
     if args.probe_copy:
         probe_copy(args.probe_copy, torch, fbuild)
         return
+    F.fsdp_set_reduce_walk({"auto": F.FSDP_WALK_AUTO, "wide": F.FSDP_WALK_WIDE, "deep": F.FSDP_WALK_DEEP}[args.walk])
     wl = workloads.config(args.config)
     if args.next_rows:
         next_rows(args, wl, F, torch, workloads)

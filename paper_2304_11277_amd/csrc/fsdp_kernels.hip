@@ -422,12 +422,14 @@ __device__ __forceinline__ float post_scale(float x, const RsArgs& a)
 // contiguous across the wave.  Ranks are taken G at a time, two such batches in
 // flight: the next batch's G*C loads are issued before the current batch's adds
 // wait for their data, and the adds run strictly in rank order.
-//   wide  (G = 4, C = 1): four rank streams per batch.  Best for up to 8 ranks
-//         and for small units (it makes the most workgroups).
-//   deep  (G = 1, C = 4 or 2): one rank stream at a time, four (two) chunks of
-//         it.  With many ranks the wide form loses bandwidth (6.5 TB/s at W = 8,
-//         5.3 TB/s at W = 48 on MI355X: too many streams open at once); the
-//         deep form holds 6.4-6.6 TB/s from W = 8 to W = 48.
+//   wide  (G = 4, C = 1): four rank streams per batch.  Best for up to 8 ranks,
+//         for small units (it makes the most workgroups) and for 16-bit
+//         gradients at any rank count.
+//   deep  (G = 1, C = 4): one rank stream at a time, four chunks of it.  Used
+//         for fp32 gradients with many ranks, where the wide form loses
+//         bandwidth to the number of streams open at once (a lone kernel on
+//         MI355X: wide 6.5 TB/s at W = 8, 5.3 TB/s at W = 48; deep 6.4-6.6 TB/s
+//         throughout).
 // The host pads the pointer table to a multiple of kWideRanks with copies of the
 // last pointer, so loads never need a predicate; the padding's adds are skipped.
 constexpr int kWideRanks = 4;
@@ -435,7 +437,7 @@ template <int GT, bool DEEP>
 struct WalkShape {
     static constexpr int E = GT != kF32 ? 8 : 4;
     static constexpr int G = DEEP ? 1 : kWideRanks;
-    static constexpr int C = DEEP ? (GT != kF32 ? 2 : 4) : 1;
+    static constexpr int C = DEEP ? 4 : 1;
 };
 
 template <int GT, int G, int C>
@@ -918,9 +920,9 @@ void pad_rank_table(PtrTable& tab, int32_t n)
     for (int32_t j = n; j % kWideRanks != 0; ++j) tab.p[j] = tab.p[n - 1];
 }
 
-// The deep rank walk pays from about ten rank streams on, provided it still
-// makes at least four workgroups per compute unit (256 of them on MI355X):
-// with three it measured 6 % slower than the wide walk at 64 ranks.
+// The deep rank walk pays for fp32 gradients from about ten rank streams on
+// (4 % at 12 ranks), provided it still makes at least four workgroups per
+// compute unit (256 of them on MI355X).
 constexpr int32_t kDeepMinRanks = 10;
 constexpr int64_t kDeepMinBlocks = 4 * 256;
 std::atomic<int32_t> g_reduce_walk{FSDP_WALK_AUTO};      // fsdp_set_reduce_walk
@@ -929,19 +931,21 @@ template <int GT, int PRE, bool FUSED>
 void launch_reduce(const PtrTable& tab, const RsArgs& a, hipStream_t st)
 {
     constexpr int B = kReduceBlock;
-    constexpr int E = WalkShape<GT, true>::E;
-    const int64_t deep_blocks = ceil_div(a.S / E + 1, B * WalkShape<GT, true>::C);
-    const int32_t walk = g_reduce_walk.load(std::memory_order_relaxed);
-    const bool deep = walk == FSDP_WALK_AUTO ? a.W >= kDeepMinRanks && deep_blocks >= kDeepMinBlocks
-                                             : walk == FSDP_WALK_DEEP;
-    if (deep) {
-        hipLaunchKernelGGL((reduce_kernel<GT, PRE, FUSED, true, B>), dim3(static_cast<uint32_t>(deep_blocks)), dim3(B),
-                           0, st, tab, a);
-    } else {
-        const int64_t blocks = ceil_div(a.S / E + 1, B);
-        hipLaunchKernelGGL((reduce_kernel<GT, PRE, FUSED, false, B>), dim3(static_cast<uint32_t>(blocks)), dim3(B), 0,
-                           st, tab, a);
+    constexpr int E = WalkShape<GT, false>::E;
+    if constexpr (GT == kF32) {   // 16-bit gradients measured no gain from the deep walk (6 % slower at 64 ranks)
+        const int64_t deep_blocks = ceil_div(a.S / E + 1, B * WalkShape<GT, true>::C);
+        const int32_t walk = g_reduce_walk.load(std::memory_order_relaxed);
+        const bool deep = walk == FSDP_WALK_AUTO ? a.W >= kDeepMinRanks && deep_blocks >= kDeepMinBlocks
+                                                 : walk == FSDP_WALK_DEEP;
+        if (deep) {
+            hipLaunchKernelGGL((reduce_kernel<GT, PRE, FUSED, true, B>), dim3(static_cast<uint32_t>(deep_blocks)),
+                               dim3(B), 0, st, tab, a);
+            return;
+        }
     }
+    const int64_t blocks = ceil_div(a.S / E + 1, B);
+    hipLaunchKernelGGL((reduce_kernel<GT, PRE, FUSED, false, B>), dim3(static_cast<uint32_t>(blocks)), dim3(B), 0, st,
+                       tab, a);
 }
 
 template <int GT, bool FUSED>
