@@ -18,6 +18,9 @@ from gpu_helpers import adam_close, first_diff, load_product, np_bits, np_f32, s
 
 pytestmark = pytest.mark.gpu
 
+BENCH_RANK = 0      # the rank bench.py times
+BENCH_DEPTH = 3     # bench.py's default --depth
+
 CASES = [(c, u) for c in range(workloads.NUM_CONFIGS) for u in workloads.config(c).distinct_units]
 
 
@@ -123,9 +126,42 @@ def test_config_unit_matches_oracle(F, cfg, unit_index):
             assert same_bits(np_bits(a), np_bits(b)), f"fused {n} differs from the two-call path at rank {r}"
         if lay.pad and r == W - 1:
             assert not np_bits(p)[S - lay.pad:].any()
+        if r == BENCH_RANK:
+            bench_ref = (rp.copy(), rm.copy(), rv.copy(), np_bits(p2).copy(), np_bits(m2).copy(), np_bits(v2).copy())
         print(f"[step] rank {r}: reduce-scatter bit-exact, Adam within 1e-6 (bit-identical to fp32 oracle: {exact}), "
               f"fused == two calls", flush=True)
         del p, m, v, p2, m2, v2, rp, rm, rv, dp, dm, dv, gp, gm, gv, ref_g
+
+    # ---- the launch configuration bench.py times by default: one batch holding the fused
+    # reduce-scatter + Adam of `depth` units and the unshards of `depth` units (here: copies of this unit)
+    rp, rm, rv, p2b, m2b, v2b = bench_ref
+    ref_flat = oracle.unshard_bf16(h_shards)
+    batch = F.Batch()
+    outs = []
+    for _ in range(BENCH_DEPTH):
+        pb, mb, vb = shards[BENCH_RANK].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
+        batch.add_reduce_scatter_adam(lay, grads, BENCH_RANK, pre, post, None, pb, mb, vb, *hp, None)
+        outs.append((pb, mb, vb))
+    flats = []
+    for _ in range(BENCH_DEPTH):
+        fb = torch.empty(P, dtype=torch.bfloat16, device="cuda")
+        fb.view(torch.int16).fill_(0x7FCD)
+        batch.add_unshard(lay, shards, fb)
+        flats.append(fb)
+    batch.launch(1)
+    torch.cuda.synchronize()
+    for j, (pb, mb, vb) in enumerate(outs):
+        ok, bad = adam_close(np_f32(pb), np_f32(mb), np_f32(vb), rp, rm, rv, h_shards[BENCH_RANK])
+        assert ok, f"batch update {j} vs fp32 oracle: {bad}"
+        for a, b, n in ((pb, p2b, "p"), (mb, m2b, "m"), (vb, v2b, "v")):
+            assert same_bits(np_bits(a), b), f"batch update {j}: {n} differs from the fused call"
+    for j, fb in enumerate(flats):
+        got = np_bits(fb)
+        assert same_bits(got, ref_flat), f"batch unshard {j}: " + first_diff(got, ref_flat)
+    print(f"[step] batch of {BENCH_DEPTH}+{BENCH_DEPTH} operations: updates within 1e-6 of the oracle and equal to "
+          "the fused call, unshards bit-exact", flush=True)
+    batch.close()
+    del outs, flats, batch, ref_flat, bench_ref
     del grads, shards, base, h_shards
     gc.collect()
     torch.cuda.empty_cache()
