@@ -1631,7 +1631,17 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
         int rc = FSDP_OK;
         // a grid without reduce operations never enters the reduce code, so any instantiation serves
         if (g.n_reduce == 0) kind = ReduceKind{kF32, kPreNone};
-        launch_batch_grid(kind, g, r_blocks + u_blocks, st);
+        if (g.n_reduce == 1 && g.n_unshard == 0) {
+            // a lone update (a unit too large to share a grid) goes through the stand-alone kernel, which
+            // may choose the deep rank walk
+            PtrTable tab = {};
+            for (int32_t w = 0; w < kBatchRanks; ++w) tab.p[w] = g.r[0].grads[w];
+            if (kind.gt == kBF16) launch_reduce_pre<kBF16, true>(kind.pre_mode, tab, g.r[0].a, st);
+            else if (kind.gt == kF16) launch_reduce_pre<kF16, true>(kind.pre_mode, tab, g.r[0].a, st);
+            else launch_reduce_pre<kF32, true>(kind.pre_mode, tab, g.r[0].a, st);
+        } else {
+            launch_batch_grid(kind, g, r_blocks + u_blocks, st);
+        }
         rc = launch_status();
         g = BatchArgs{};
         have_kind = false;
