@@ -1631,9 +1631,9 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
         int rc = FSDP_OK;
         // a grid without reduce operations never enters the reduce code, so any instantiation serves
         if (g.n_reduce == 0) kind = ReduceKind{kF32, kPreNone};
-        if (g.n_reduce == 1 && g.n_unshard == 0) {
-            // a lone update (a unit too large to share a grid) goes through the stand-alone kernel, which
-            // may choose the deep rank walk
+        if (g.n_reduce == 1 && g.n_unshard == 0 && large > 0) {
+            // the lone update of a unit too large to share a grid goes through the stand-alone kernel,
+            // which may choose the deep rank walk
             PtrTable tab = {};
             for (int32_t w = 0; w < kBatchRanks; ++w) tab.p[w] = g.r[0].grads[w];
             if (kind.gt == kBF16) launch_reduce_pre<kBF16, true>(kind.pre_mode, tab, g.r[0].a, st);
