@@ -22,6 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+GRAPH_MIN_LAUNCHES = 16      # steps with more launches than this are captured in a HIP graph by default
 HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published
 
 
@@ -45,7 +46,8 @@ def parse_args():
                          "(backward prefetching); fused: reduce-scatter + Adam in one launch, unshard in another; "
                          "separate: the three required entry points, one launch each; lp: every rank keeps a bf16 "
                          "copy of its shard (written by the fused Adam), the unshard gathers bf16 (Sec. 4.4)")
-    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--graph", action="store_true", help="always replay the step as a HIP graph")
+    ap.add_argument("--no-graph", action="store_true", help="always launch eagerly")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
                     help="run only N launches of a plain 256 MiB copy kernel (calibrates rocprofv3 --pmc byte counters)")
     ap.add_argument("--next-rows", action="store_true",
@@ -232,7 +234,10 @@ def main():
         for _kind, fn, _b in launches:
             fn(t)
 
-    use_graph = not args.no_graph
+    # A graph replay costs a fixed 6-10 us per step on this machine, which a step of
+    # a few long launches does not win back (measured: configuration 1, 6 launches,
+    # 259 us eagerly against 265 us replayed); steps of many launches replay a graph.
+    use_graph = args.graph or (not args.no_graph and len(launches) > GRAPH_MIN_LAUNCHES)
     graph = None
     with torch.cuda.stream(main_s):
         step(1)                      # first-touch / module load outside any capture
