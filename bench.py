@@ -53,6 +53,11 @@ def parse_args():
     ap.add_argument("--next-rows", action="store_true",
                     help="measure the kernels beyond the hot path (hybrid-sharding reduce, gradient accumulation) "
                          "on the workload's largest unit and print their own JSON line")
+    ap.add_argument("--raf", action="store_true",
+                    help="reshard after forward (Sec. 3, Sec. 4.4): every unit is unsharded twice per step, once for "
+                         "the forward pass and once before its backward; the metric's bytes count both")
+    ap.add_argument("--grad-dtype", choices=["f32", "bf16"], default=None,
+                    help="override the workload's gradient dtype (the fp32 / bf16 variants of every configuration)")
     ap.add_argument("--walk", choices=["auto", "wide", "deep"], default="auto",
                     help="rank walk of the stand-alone reduce-scatter kernels (fsdp_set_reduce_walk)")
     ap.add_argument("--grad-sets", type=int, default=0,
@@ -129,6 +134,9 @@ def main():
         return
     F.fsdp_set_reduce_walk({"auto": F.FSDP_WALK_AUTO, "wide": F.FSDP_WALK_WIDE, "deep": F.FSDP_WALK_DEEP}[args.walk])
     wl = workloads.config(args.config)
+    if args.grad_dtype:
+        import dataclasses
+        wl = dataclasses.replace(wl, grad_dtype=args.grad_dtype)
     if args.next_rows:
         next_rows(args, wl, F, torch, workloads)
         return
@@ -197,6 +205,21 @@ def main():
             nxt = groups[j + 1] if j + 1 < len(groups) else []
             bj, nbj = make_batch(grp, nxt)
             launches.append(("batch", (lambda t, b=bj: b.launch(t)), nbj))
+    if args.raf:
+        # forward pass: the unshards alone, in forward order (the list above then plays the backward pass)
+        fwd = []
+        if args.mode == "batch":
+            for grp in groups:
+                b, nb = make_batch([], grp)
+                fwd.append(("batch", (lambda t, b=b: b.launch(t)), nb))
+        else:
+            for i, s in enumerate(states):
+                if args.mode == "lp":
+                    fwd.append(("unshard_lp", (lambda t, s=s, buf=flats[i % 2]:
+                                               F.fsdp_unshard_lp(s.lay, s.lp_tab, buf[:s.P])), s.b_unshard))
+                else:
+                    fwd.append(("unshard", (lambda t, s=s, buf=flats[i % 2]: unshard(s, buf)), s.b_unshard))
+        launches = fwd + launches
     for i, s in enumerate(states):
         buf = flats[i % 2]
         if args.mode == "batch":
@@ -262,7 +285,7 @@ def main():
         wall_ms = (time.perf_counter() - tb) * 1e3
         dev_ms = e0.elapsed_time(e1)
     ms_per_step = wall_ms / args.steps
-    step_bytes = sum(s.b_total for s in states)
+    step_bytes = sum(s.b_total for s in states) + (sum(s.b_unshard for s in states) if args.raf else 0)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     log(f"[bench] {args.steps} steps: wall {wall_ms:.3f} ms, device {dev_ms:.3f} ms, "
         f"{ms_per_step * 1e3:.1f} us/step, {value:.1f} GB/s effective ({100 * value / HBM_PEAK_GBPS:.1f}% of peak)")
@@ -314,7 +337,7 @@ def main():
 
     # ---- the CPU oracle on the host cores, same three operations, bounded sample
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.raf:      # the oracle leg times the one-unshard step only
         cpu = cpu_baseline(states, wl, pre, post, rank, hp, torch)
 
     out = {
@@ -324,6 +347,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "units": len(states), "world_size": wl.world_size,
                    "grad_dtype": wl.grad_dtype, "unshard_dtype": "bf16", "rank": rank, "mode": args.mode,
+                   "reshard_after_forward": bool(args.raf),
                    "prefetch_depth": args.depth if args.mode == "batch" else (1 if args.mode == "prefetch" else 0),
                    "hip_graph": use_graph, "launches_per_step": len(launches), "alg_bytes_per_step": step_bytes},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
@@ -343,7 +367,7 @@ def next_rows(args, wl, F, torch, workloads):
     lay = F.fsdp_layout_init(unit.shapes, W)
     S, P, N = lay.shard, lay.padded, lay.numel
     G = 2 if 2 * W <= 64 else 1
-    nsets = max(1, min(3, int(100e9 // (W * G * P * gb + 2 * W * P + 14 * P))))   # rotate buffer sets while HBM allows
+    nsets = max(1, min(3, int(100e9 // (W * G * P * gb + 2 * W * P + 18 * P))))   # rotate buffer sets while HBM allows
     pre, post = F.fsdp_default_divide_factors(W * G)
     pre_w, post_w = F.fsdp_default_divide_factors(W)
     sets = []
@@ -355,6 +379,7 @@ def next_rows(args, wl, F, torch, workloads):
         d["g16"] = F.PtrArray([g.to(torch.float16) for g in grads[:W]])
         d["shards"] = F.PtrArray([torch.randn(S, device="cuda") * 0.02 for _ in range(W)])
         d["flat16"] = torch.empty(P, dtype=torch.float16, device="cuda")
+        d["flat32"] = torch.empty(P, dtype=torch.float32, device="cuda")
         d["flag"] = torch.zeros(1, device="cuda")
         sets.append(d)
     rows = {
@@ -364,6 +389,7 @@ def next_rows(args, wl, F, torch, workloads):
                                       gb * P + 8 * S),
         "grad_accumulate": (lambda d: F.fsdp_grad_accumulate(lay, d["acc"], d["flat"].tensors[0]), (8 + gb) * P),
         "unshard_fp16": (lambda d: F.fsdp_unshard(lay, d["shards"], d["flat16"]), 6 * P),
+        "unshard_fp32": (lambda d: F.fsdp_unshard(lay, d["shards"], d["flat32"]), 8 * P),
         "reduce_scatter_unscale_fp16": (lambda d: F.fsdp_reduce_scatter_unscale(
             lay, d["g16"], 0, pre_w, post_w, 1.0 / 1024.0, d["out"], d["flag"]), 2 * P + 4 * S),
     }
