@@ -37,8 +37,15 @@ extern "C" {
 typedef struct fsdp_layout fsdp_layout_t;   /* opaque, library-owned, host memory */
 typedef struct fsdp_batch fsdp_batch_t;     /* opaque, library-owned, host memory */
 
-/* FSDP_F16 is IEEE binary16; both 16-bit kinds travel as uint16_t bit patterns. */
-typedef enum { FSDP_F32 = 0, FSDP_BF16 = 1, FSDP_F16 = 2 } fsdp_dtype_t;
+/* FSDP_F16 is IEEE binary16; both 16-bit kinds travel as uint16_t bit patterns.
+ * A 4-byte integer at the ABI.  For C++ translation units the underlying type
+ * is fixed, so that any integer a caller passes is a representable value and
+ * the library's range check (FSDP_ERR_BAD_DTYPE) is well defined. */
+#ifdef __cplusplus
+typedef enum fsdp_dtype : int32_t { FSDP_F32 = 0, FSDP_BF16 = 1, FSDP_F16 = 2 } fsdp_dtype_t;
+#else
+typedef enum fsdp_dtype { FSDP_F32 = 0, FSDP_BF16 = 1, FSDP_F16 = 2 } fsdp_dtype_t;
+#endif
 
 typedef enum {
     FSDP_OK = 0,
