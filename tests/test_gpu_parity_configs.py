@@ -165,3 +165,71 @@ def test_config_unit_matches_oracle(F, cfg, unit_index):
     del grads, shards, base, h_shards
     gc.collect()
     torch.cuda.empty_cache()
+
+
+def test_unit_with_more_than_2_31_elements(F):
+    """Maximum-size edge: element indices and byte offsets beyond 32 bits in
+    every kernel (N = 2^31 + 12345 over two ranks, odd N so the last rank holds
+    one pad element and rank 1's shard is only 4-byte aligned)."""
+    W = 2
+    shapes = [(1 << 31,), (12345,)]
+    lay = F.fsdp_layout_init(shapes, W)
+    S, P, N = lay.shard, lay.padded, lay.numel
+    off_ref, N_ref, S_ref, P_ref, pad_ref = oracle.layout(shapes, W)
+    assert (N, S, P, lay.pad) == (N_ref, S_ref, P_ref, pad_ref) == ((1 << 31) + 12345, (1 << 30) + 6173, (1 << 31) + 12346, 1)
+    print(f"\n[case] 2^31+12345 elements, W={W}, S={S}", flush=True)
+
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(workloads.BASE_SEED)
+    params = [torch.empty(s, dtype=torch.float32, device="cuda").normal_(0.0, 0.02, generator=gen) for s in shapes]
+    base = torch.empty(P, dtype=torch.float32, device="cuda")
+    base.view(torch.int32).fill_(0x7FC00001)
+    shards = [base[w * S:(w + 1) * S] for w in range(W)]
+    F.fsdp_flatten_shard(lay, params, shards)
+    torch.cuda.synchronize()
+    h_params = [np_f32(p) for p in params]
+    del params
+    h_shards, _ = oracle.flatten_shard(h_params, W)
+    del h_params
+    for w in range(W):
+        got = np_bits(shards[w])
+        assert same_bits(got, h_shards[w].view(np.uint32)), f"flatten_shard rank {w}: " + first_diff(got, h_shards[w].view(np.uint32))
+    print("[step] flatten_shard bit-exact", flush=True)
+
+    flat = torch.empty(P, dtype=torch.bfloat16, device="cuda")
+    flat.view(torch.int16).fill_(0x7FCD)
+    F.fsdp_unshard(lay, shards, flat)
+    torch.cuda.synchronize()
+    ref = oracle.unshard_bf16(h_shards)
+    got = np_bits(flat)
+    assert same_bits(got, ref), "unshard: " + first_diff(got, ref)
+    views = F.fsdp_views(lay, flat)
+    assert views[1].data_ptr() == flat.data_ptr() + 2 * (1 << 31) and tuple(views[1].shape) == (12345,)
+    del got, ref, flat, views
+    print("[step] unshard bit-exact", flush=True)
+
+    grads = [workloads.gen_rank_grad(P, N, w, 0, "bf16", device="cuda") for w in range(W)]
+    pre, post = F.fsdp_default_divide_factors(W)
+    hp = (1e-4, 0.9, 0.999, 1e-8)
+    r = W - 1                                  # the slice that starts beyond 2^30 elements and ends with the pad
+    h_slices = [np_bits(g[r * S:(r + 1) * S]) for g in grads]
+    ref_g = oracle.reduce_slices(h_slices, pre, post)
+    del h_slices
+    gs = torch.empty(S, dtype=torch.float32, device="cuda")
+    gs.view(torch.int32).fill_(0x7FC00001)
+    F.fsdp_reduce_scatter_local(lay, grads, r, pre, post, gs)
+    p2, m2, v2 = shards[r].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
+    F.fsdp_reduce_scatter_adam_fused(lay, grads, r, pre, post, None, p2, m2, v2, 1, *hp, None)
+    torch.cuda.synchronize()
+    got = np_bits(gs)
+    assert same_bits(got, ref_g.view(np.uint32)), "reduce-scatter: " + first_diff(got, ref_g.view(np.uint32))
+    del got, gs, grads
+    z = np.zeros(S, np.float32)
+    rp, rm, rv = oracle.adam_f32(h_shards[r], ref_g, z, z, 1, *hp)
+    ok, bad = adam_close(np_f32(p2), np_f32(m2), np_f32(v2), rp, rm, rv, h_shards[r])
+    assert ok, f"fused update vs fp32 oracle: {bad}"
+    assert not np_bits(p2)[S - 1:].any(), "the pad element must stay zero"
+    print("[step] reduce-scatter bit-exact, fused update within 1e-6", flush=True)
+    del p2, m2, v2, shards, base, h_shards
+    gc.collect()
+    torch.cuda.empty_cache()
