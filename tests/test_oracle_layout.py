@@ -158,3 +158,29 @@ def test_gather_of_cast_shards_equals_unshard(W):
     got = oracle.gather_lp(lp)
     assert np.array_equal(got, np.concatenate(lp))
     assert np.array_equal(got, oracle.unshard_bf16(shards))
+
+
+@pytest.mark.parametrize("cfg", range(workloads.NUM_CONFIGS))
+def test_memory_model_of_the_sharded_layout(cfg):
+    """Sec. 3.2.1: peak parameter memory is O(sum_i psi_i / F + max_i psi_i);
+    Sec. 4.4 with mixed precision: K_full / F * sum_i psi_i + K_low * max_i psi_i.
+    The layout must realise these with no more slack than the pad: per unit the
+    persistent full-precision shard is K_full * S_i with
+    psi_i / F <= S_i < psi_i / F + 1, and the transient low-precision unsharded
+    buffer is K_low * P_i with psi_i <= P_i <= psi_i + F - 1."""
+    wl = workloads.config(cfg)
+    F = wl.world_size
+    K_full, K_low = 4, 2
+    psis, Ss, Ps = [], [], []
+    for u in wl.units:
+        off, N, S, P, pad = oracle.layout(u.shapes, F)
+        assert N == sum(workloads.numel(s) for s in u.shapes)
+        assert N <= S * F < N + F and P == S * F and pad == P - N
+        psis.append(N); Ss.append(S); Ps.append(P)
+    persistent = K_full * sum(Ss)
+    transient = K_low * max(Ps)
+    model = K_full * sum(psis) / F + K_low * max(psis)
+    slack = K_full * len(psis) + K_low * (F - 1)             # < one element per unit, plus one unit's pad
+    assert model <= persistent + transient < model + slack
+    # without sharding the same parameters would take K_full * sum psi: the saving approaches a factor F
+    assert persistent <= K_full * sum(psis) / F + K_full * len(psis)
