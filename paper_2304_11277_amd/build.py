@@ -10,7 +10,9 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfsdp_flat.so")
 SOURCES = [os.path.join(CSRC, "fsdp_layout.cpp"), os.path.join(CSRC, "fsdp_kernels.hip")]
-HEADERS = [os.path.join(ROOT, "include", "fsdp_flat.h"), os.path.join(CSRC, "fsdp_internal.h")]
+HEADERS = [os.path.join(ROOT, "include", "fsdp_flat.h")] + [
+    os.path.join(CSRC, h) for h in ("fsdp_internal.h", "device_common.h", "unshard_kernels.h", "pack_kernel.h",
+                                    "reduce_kernels.h", "batch_kernel.h", "elementwise_kernels.h")]
 # counter-calibration copy kernel: a library of its own, loaded by bench.py --probe-copy only
 PROBE_LIB = os.path.join(HERE, "libfsdp_probe.so")
 PROBE_SRC = os.path.join(CSRC, "copy_probe.hip")

@@ -1,0 +1,57 @@
+// Several independent reduce-scatter + Adam updates and unshards in one grid.
+#pragma once
+
+#include "reduce_kernels.h"
+#include "unshard_kernels.h"
+
+namespace {
+
+// ---------------------------------------------------------------------------
+// Batches of independent operations in one grid: up to kBatchOps fused
+// reduce-scatter + Adam operations and up to kBatchOps unshards of other units.
+// One launch floor for the whole batch, and the ramp and drain of the members
+// overlap.  Workgroups [0, r_end[n_reduce-1]) serve the reduce operations in
+// order, the rest the unshards.
+// ---------------------------------------------------------------------------
+constexpr int kBatchOps = 3;
+constexpr int kBatchRanks = 32;    // rank pointers per batched operation
+
+struct BatchReduceOp {
+    const void* grads[kBatchRanks];
+    RsArgs a;
+};
+struct BatchUnshardOp {
+    const void* shards[kBatchRanks];
+    int64_t S;
+    uint16_t* out;
+    int32_t tiles;
+    int32_t pad_;
+};
+struct BatchArgs {
+    int32_t n_reduce, n_unshard;
+    uint32_t r_end[kBatchOps];     // exclusive end of each reduce operation's workgroup range
+    uint32_t u_end[kBatchOps];     // same for the unshards, counted from the end of the reduce ranges
+    BatchReduceOp r[kBatchOps];
+    BatchUnshardOp u[kBatchOps];
+};
+
+template <int GT, int PRE>
+__global__ __launch_bounds__(kBlock) void batch_kernel(BatchArgs b)
+{
+    uint32_t bid = blockIdx.x;
+    const uint32_t n_red_blocks = b.n_reduce > 0 ? b.r_end[b.n_reduce - 1] : 0u;
+    if (bid < n_red_blocks) {
+        int32_t i = 0;
+        uint32_t start = 0;
+        while (bid >= b.r_end[i]) { start = b.r_end[i]; ++i; }     // uniform, at most kBatchOps - 1 steps
+        reduce_body<GT, PRE, true, false, kBlock>(b.r[i].grads, b.r[i].a, bid - start);
+    } else {
+        bid -= n_red_blocks;
+        int32_t i = 0;
+        uint32_t start = 0;
+        while (bid >= b.u_end[i]) { start = b.u_end[i]; ++i; }
+        unshard_lp_body<kBF16>(b.u[i].shards, b.u[i].S, b.u[i].out, b.u[i].tiles, bid - start);
+    }
+}
+
+}  // namespace
