@@ -285,7 +285,7 @@ int  fsdp_batch_launch(const fsdp_batch_t* batch, int64_t step, void* hip_stream
  *   FSDP_WALK_WIDE: a lane owns one 16-byte chunk and loads four ranks at a time;
  *   FSDP_WALK_DEEP: a lane owns four chunks and loads one rank at a time (fp32
  *                   gradients only: 16-bit gradients always take the wide walk);
- *   FSDP_WALK_AUTO (default): deep for fp32 gradients from ten ranks on when the
+ *   FSDP_WALK_AUTO (default): deep for fp32 gradients from eight ranks on when the
  *                   shard is large enough to still fill the chip, else wide.
  * Process-wide; takes effect for launches issued after the call returns.
  * Returns FSDP_ERR_INVALID_ARG for any other value. */

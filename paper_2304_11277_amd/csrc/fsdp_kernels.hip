@@ -102,10 +102,11 @@ void pad_rank_table(PtrTable& tab, int32_t n)
     for (int32_t j = n; j % kWideRanks != 0; ++j) tab.p[j] = tab.p[n - 1];
 }
 
-// The deep rank walk pays for fp32 gradients from about ten rank streams on
-// (4 % at 12 ranks), provided it still makes at least four workgroups per
-// compute unit (256 of them on MI355X).
-constexpr int32_t kDeepMinRanks = 10;
+// The deep rank walk pays for fp32 gradients from eight rank streams on (cold
+// buffers, 4.2 M elements per slice: 4 % at 8 ranks, 7 % at 12 to 24, 10 % at 32
+// and more), provided it still makes at least four workgroups per compute unit
+// (256 of them on MI355X).
+constexpr int32_t kDeepMinRanks = 8;
 constexpr int64_t kDeepMinBlocks = 4 * 256;
 std::atomic<int32_t> g_reduce_walk{FSDP_WALK_AUTO};      // fsdp_set_reduce_walk
 
