@@ -39,13 +39,15 @@ def parse_args():
                          "3 Llama-7B blocks W=64, 4 one GPT-3-175B block W=16")
     ap.add_argument("--max-units", type=int, default=0, help="limit the number of units (0 = all)")
     ap.add_argument("--depth", type=int, default=3, help="units per batch in --mode batch (prefetch depth)")
-    ap.add_argument("--mode", choices=["batch", "prefetch", "fused", "separate", "lp"], default="batch",
+    ap.add_argument("--mode", choices=["batch", "prefetch", "fused", "separate", "lp", "batch-lp"], default="batch",
                     help="batch: the updates of `depth` units and the prefetched unshards of the next `depth` units "
                          "are independent and share one launch (fsdp_batch_*); "
                          "prefetch: unit i's fused reduce-scatter+Adam shares one launch with unit i+1's unshard "
                          "(backward prefetching); fused: reduce-scatter + Adam in one launch, unshard in another; "
                          "separate: the three required entry points, one launch each; lp: every rank keeps a bf16 "
-                         "copy of its shard (written by the fused Adam), the unshard gathers bf16 (Sec. 4.4)")
+                         "copy of its shard (written by the fused Adam), the unshard gathers bf16 (Sec. 4.4); "
+                         "batch-lp: the same hand-off issued as batches (moves 4P instead of 6P per unshard; the "
+                         "metric's numerator stays the fixed 6P)")
     ap.add_argument("--graph", action="store_true", help="always replay the step as a HIP graph")
     ap.add_argument("--no-graph", action="store_true", help="always launch eagerly")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
@@ -167,7 +169,9 @@ def main():
 
     # The unsharded flat parameter is transient (Sec. 3.2.1: peak memory is the
     # largest unit); two buffers alternate, as with at most two unshards in flight.
-    nflat = 2 * args.depth if args.mode == "batch" else 2
+    batched = args.mode in ("batch", "batch-lp")
+    lp_handoff = args.mode in ("lp", "batch-lp")
+    nflat = 2 * args.depth if batched else 2
     flats = [flat] + [torch.empty_like(flat) for _ in range(nflat - 1)]
 
     def unshard(s, buf):
@@ -184,7 +188,8 @@ def main():
     # One step as a list of launches: (kernel kind, callable(t), algorithmic bytes).
     launches = []
     n = len(states)
-    if args.mode == "batch":
+    bkind = "batch_lp" if lp_handoff else "batch"
+    if batched:
         d = args.depth
         groups = [list(range(i, min(i + d, n))) for i in range(0, n, d)]
 
@@ -192,26 +197,30 @@ def main():
             b = F.Batch()
             for i in red:
                 s = states[i]
-                b.add_reduce_scatter_adam(s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m, s.v, *hp, None)
+                b.add_reduce_scatter_adam(s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m, s.v, *hp,
+                                          s.lp_shards[rank] if lp_handoff else None)
             for i in uns:
                 s = states[i]
-                b.add_unshard(s.lay, s.shard_tab, flats[i % nflat][:s.P])
+                if lp_handoff:
+                    b.add_unshard_lp(s.lay, s.lp_tab, flats[i % nflat][:s.P])
+                else:
+                    b.add_unshard(s.lay, s.shard_tab, flats[i % nflat][:s.P])
             nbytes = sum(states[i].b_reduce + states[i].b_adam for i in red) + sum(states[i].b_unshard for i in uns)
             return b, nbytes
 
         b0, nb0 = make_batch([], groups[0])
-        launches.append(("batch", (lambda t, b=b0: b.launch(t)), nb0))
+        launches.append((bkind, (lambda t, b=b0: b.launch(t)), nb0))
         for j, grp in enumerate(groups):
             nxt = groups[j + 1] if j + 1 < len(groups) else []
             bj, nbj = make_batch(grp, nxt)
-            launches.append(("batch", (lambda t, b=bj: b.launch(t)), nbj))
+            launches.append((bkind, (lambda t, b=bj: b.launch(t)), nbj))
     if args.raf:
         # forward pass: the unshards alone, in forward order (the list above then plays the backward pass)
         fwd = []
-        if args.mode == "batch":
+        if batched:
             for grp in groups:
                 b, nb = make_batch([], grp)
-                fwd.append(("batch", (lambda t, b=b: b.launch(t)), nb))
+                fwd.append((bkind, (lambda t, b=b: b.launch(t)), nb))
         else:
             for i, s in enumerate(states):
                 if args.mode == "lp":
@@ -222,7 +231,7 @@ def main():
         launches = fwd + launches
     for i, s in enumerate(states):
         buf = flats[i % 2]
-        if args.mode == "batch":
+        if batched:
             break
         if args.mode == "prefetch":
             if i == 0:
@@ -286,6 +295,14 @@ def main():
         dev_ms = e0.elapsed_time(e1)
     ms_per_step = wall_ms / args.steps
     step_bytes = sum(s.b_total for s in states) + (sum(s.b_unshard for s in states) if args.raf else 0)
+    # what the chosen mode's kernels really read and write per step (the metric's numerator above is fixed)
+    n_unshard = 2 if args.raf else 1
+    if args.mode == "separate":
+        touched = step_bytes
+    elif lp_handoff:
+        touched = sum(n_unshard * 4 * s.P + s.gbytes * s.P + 26 * s.S for s in states)
+    else:
+        touched = sum(n_unshard * 6 * s.P + s.gbytes * s.P + 24 * s.S for s in states)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     log(f"[bench] {args.steps} steps: wall {wall_ms:.3f} ms, device {dev_ms:.3f} ms, "
         f"{ms_per_step * 1e3:.1f} us/step, {value:.1f} GB/s effective ({100 * value / HBM_PEAK_GBPS:.1f}% of peak)")
@@ -348,8 +365,9 @@ def main():
         "config": {"workload": wl.name, "units": len(states), "world_size": wl.world_size,
                    "grad_dtype": wl.grad_dtype, "unshard_dtype": "bf16", "rank": rank, "mode": args.mode,
                    "reshard_after_forward": bool(args.raf),
-                   "prefetch_depth": args.depth if args.mode == "batch" else (1 if args.mode == "prefetch" else 0),
-                   "hip_graph": use_graph, "launches_per_step": len(launches), "alg_bytes_per_step": step_bytes},
+                   "prefetch_depth": args.depth if batched else (1 if args.mode == "prefetch" else 0),
+                   "hip_graph": use_graph, "launches_per_step": len(launches), "alg_bytes_per_step": step_bytes,
+                   "touched_bytes_per_step": touched},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "roofline": roofline, "cpu_baseline": cpu, "kernels": per_kernel,
     }

@@ -269,6 +269,10 @@ void fsdp_batch_destroy(fsdp_batch_t* batch);                /* NULL is a no-op 
 int  fsdp_batch_clear(fsdp_batch_t* batch);
 int  fsdp_batch_add_unshard(fsdp_batch_t* batch, const fsdp_layout_t* layout,
                             const float* const* shard_ptrs, void* flat_out, fsdp_dtype_t out_dtype);
+/* The Sec. 4.4 hand-off as a batch member: the gather of fsdp_unshard_lp (the
+ * ranks' 16-bit shards, e.g. written by p_lp_out below, into the flat buffer). */
+int  fsdp_batch_add_unshard_lp(fsdp_batch_t* batch, const fsdp_layout_t* layout,
+                               const void* const* lp_shard_ptrs, void* flat_out);
 int  fsdp_batch_add_reduce_scatter_adam(fsdp_batch_t* batch, const fsdp_layout_t* layout,
                                         const void* const* grad_ptrs, fsdp_dtype_t grad_dtype,
                                         int32_t rank, float pre_div, float post_div,

@@ -77,6 +77,7 @@ _SIGNATURES = {
     "fsdp_batch_create": [ctypes.POINTER(_vp)],
     "fsdp_batch_clear": [_vp],
     "fsdp_batch_add_unshard": [_vp, _vp, _pp, _vp, ctypes.c_int],
+    "fsdp_batch_add_unshard_lp": [_vp, _vp, _pp, _vp],
     "fsdp_batch_add_reduce_scatter_adam": [_vp, _vp, _pp, ctypes.c_int, _i32, _f32, _f32, _vp, _vp, _vp, _vp,
                                            _f32, _f32, _f32, _f32, _vp],
     "fsdp_batch_launch": [_vp, _i64, _vp],
@@ -446,6 +447,15 @@ class Batch:
         _dev_tensor(flat_out, flat_out.dtype, layout.padded, "flat_out")
         _check("fsdp_batch_add_unshard",
                lib().fsdp_batch_add_unshard(self._h, layout.handle, shards.array, _vp(flat_out.data_ptr()), dt))
+        self._keep += [layout, shards, flat_out]
+
+    def add_unshard_lp(self, layout: Layout, lp_shard_ptrs, flat_out: torch.Tensor) -> None:
+        if flat_out.dtype not in (torch.bfloat16, torch.float16):
+            raise TypeError("flat_out must be bfloat16 or float16")
+        shards = _ptr_table(lp_shard_ptrs, flat_out.dtype, layout.shard, layout.world_size, "lp_shard_ptrs")
+        _dev_tensor(flat_out, flat_out.dtype, layout.padded, "flat_out")
+        _check("fsdp_batch_add_unshard_lp",
+               lib().fsdp_batch_add_unshard_lp(self._h, layout.handle, shards.array, _vp(flat_out.data_ptr())))
         self._keep += [layout, shards, flat_out]
 
     def add_reduce_scatter_adam(self, layout: Layout, grad_ptrs, rank: int, pre_div: float, post_div: float,

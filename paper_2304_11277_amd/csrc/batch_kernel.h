@@ -8,7 +8,8 @@ namespace {
 
 // ---------------------------------------------------------------------------
 // Batches of independent operations in one grid: up to kBatchOps fused
-// reduce-scatter + Adam operations and up to kBatchOps unshards of other units.
+// reduce-scatter + Adam operations and up to kBatchOps unshards of other units
+// (cast + gather of fp32 shards to bf16, or the plain gather of 16-bit shards).
 // One launch floor for the whole batch, and the ramp and drain of the members
 // overlap.  Workgroups [0, r_end[n_reduce-1]) serve the reduce operations in
 // order, the rest the unshards.
@@ -25,7 +26,7 @@ struct BatchUnshardOp {
     int64_t S;
     uint16_t* out;
     int32_t tiles;
-    int32_t pad_;
+    int32_t lp;        // 1: the shards are 16-bit already (Sec. 4.4 hand-off): plain gather
 };
 struct BatchArgs {
     int32_t n_reduce, n_unshard;
@@ -50,7 +51,10 @@ __global__ __launch_bounds__(kBlock) void batch_kernel(BatchArgs b)
         int32_t i = 0;
         uint32_t start = 0;
         while (bid >= b.u_end[i]) { start = b.u_end[i]; ++i; }
-        unshard_lp_body<kBF16>(b.u[i].shards, b.u[i].S, b.u[i].out, b.u[i].tiles, bid - start);
+        if (b.u[i].lp)   // uniform
+            gather_lp_body(b.u[i].shards, b.u[i].S, b.u[i].out, b.u[i].tiles, bid - start);
+        else
+            unshard_lp_body<kBF16>(b.u[i].shards, b.u[i].S, b.u[i].out, b.u[i].tiles, bid - start);
     }
 }
 

@@ -666,9 +666,10 @@ struct fsdp_batch {
     };
     struct UnshardRec {
         const fsdp_layout_t* L;
-        std::vector<const float*> shards;
+        std::vector<const void*> shards;
         void* out;
         fsdp_dtype_t dtype;
+        bool lp;                             // the shards are 16-bit already: plain gather (fsdp_unshard_lp)
     };
     struct Op {
         bool is_reduce;
@@ -747,6 +748,30 @@ int fsdp_batch_add_unshard(fsdp_batch_t* b, const fsdp_layout_t* L, const float*
         r.shards.assign(shard_ptrs, shard_ptrs + L->world_size);
         r.out = flat_out;
         r.dtype = out_dtype;
+        r.lp = false;
+        b->unshards.push_back(std::move(r));
+        b->order.push_back({false, b->unshards.size() - 1});
+    } catch (const std::bad_alloc&) {
+        return FSDP_ERR_OOM;
+    }
+    return FSDP_OK;
+}
+
+int fsdp_batch_add_unshard_lp(fsdp_batch_t* b, const fsdp_layout_t* L, const void* const* lp_shard_ptrs, void* flat_out)
+{
+    if (!b || !L || !lp_shard_ptrs || !flat_out) return FSDP_ERR_NULL_PTR;
+    for (int32_t w = 0; w < L->world_size; ++w) {
+        if (!lp_shard_ptrs[w]) return FSDP_ERR_NULL_PTR;
+        if (misaligned(lp_shard_ptrs[w], 2)) return FSDP_ERR_INVALID_ARG;
+    }
+    if (misaligned(flat_out, 2)) return FSDP_ERR_INVALID_ARG;
+    try {
+        fsdp_batch::UnshardRec r;
+        r.L = L;
+        r.shards.assign(lp_shard_ptrs, lp_shard_ptrs + L->world_size);
+        r.out = flat_out;
+        r.dtype = FSDP_BF16;        // not looked at: a gather moves either 16-bit kind
+        r.lp = true;
         b->unshards.push_back(std::move(r));
         b->order.push_back({false, b->unshards.size() - 1});
     } catch (const std::bad_alloc&) {
@@ -879,13 +904,16 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
         } else {
             const fsdp_batch::UnshardRec& u = b->unshards[op.index];
             const int32_t W = u.L->world_size;
-            const int64_t bytes = 6 * u.L->P;
+            const int64_t bytes = (u.lp ? 4 : 6) * u.L->P;
             const int64_t tiles = ceil_div(u.L->S / 8 + 1, kBlock);
-            const bool batchable = W <= kBatchRanks && u.dtype == FSDP_BF16 && grid_ok(tiles * W + r_blocks + u_blocks);
+            const bool batchable = W <= kBatchRanks && (u.lp || u.dtype == FSDP_BF16) &&
+                                   grid_ok(tiles * W + r_blocks + u_blocks);
             if (!batchable) {
                 int rc = flush();
                 if (rc != FSDP_OK) return rc;
-                rc = fsdp_unshard(u.L, u.shards.data(), u.out, u.dtype, hip_stream);
+                rc = u.lp ? fsdp_unshard_lp(u.L, u.shards.data(), u.out, hip_stream)
+                          : fsdp_unshard(u.L, reinterpret_cast<const float* const*>(u.shards.data()), u.out, u.dtype,
+                                         hip_stream);
                 if (rc != FSDP_OK) return rc;
                 continue;
             }
@@ -900,6 +928,7 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
             o.S = u.L->S;
             o.out = static_cast<uint16_t*>(u.out);
             o.tiles = static_cast<int32_t>(tiles);
+            o.lp = u.lp ? 1 : 0;
             u_blocks += static_cast<uint32_t>(tiles * W);
             g.u_end[g.n_unshard] = u_blocks;
             ++g.n_unshard;

@@ -106,16 +106,16 @@ __global__ __launch_bounds__(kBlock) void unshard_f32_kernel(PtrTable shards, in
     }
 }
 
-// Gather of bf16 shards (the AllGather in the low precision, Sec. 4.4):
+// Gather of 16-bit shards (the AllGather in the low precision, Sec. 4.4):
 // flat_lp[w*S + k] = lp_shard_w[k]; 16-byte destination vectors, sources only
-// 2-byte aligned.
-__global__ __launch_bounds__(kBlock) void gather_lp_kernel(PtrTable shards, int64_t S,
-                                                            uint16_t* __restrict__ out_base,
-                                                            int32_t tiles_per_shard)
+// 2-byte aligned.  bid = index of the workgroup among the launch's gather
+// workgroups, as in unshard_lp_body.
+__device__ __forceinline__ void gather_lp_body(const void* const* shards, int64_t S, uint16_t* __restrict__ out_base,
+                                               int32_t tiles_per_shard, uint32_t bid)
 {
-    const int32_t w = blockIdx.x / tiles_per_shard;
-    const int32_t tile = blockIdx.x - w * tiles_per_shard;
-    const uint16_t* __restrict__ src = static_cast<const uint16_t*>(shards.p[w]);
+    const int32_t w = bid / tiles_per_shard;
+    const int32_t tile = bid - w * tiles_per_shard;
+    const uint16_t* __restrict__ src = static_cast<const uint16_t*>(shards[w]);
     uint16_t* __restrict__ dst = out_base + static_cast<int64_t>(w) * S;
 
     const int64_t head = head_elems(dst, 2, S);
@@ -132,6 +132,13 @@ __global__ __launch_bounds__(kBlock) void gather_lp_kernel(PtrTable shards, int6
         if (t < head) dst[t] = src[t];
         if (t >= 64 && t - 64 < ntail) dst[tail0 + t - 64] = src[tail0 + t - 64];
     }
+}
+
+__global__ __launch_bounds__(kBlock) void gather_lp_kernel(PtrTable shards, int64_t S,
+                                                            uint16_t* __restrict__ out_base,
+                                                            int32_t tiles_per_shard)
+{
+    gather_lp_body(shards.p, S, out_base, tiles_per_shard, blockIdx.x);
 }
 
 }  // namespace

@@ -227,6 +227,10 @@ static void validation_checks()
                                                          0.9f, 0.999f, 1e-8f, nullptr) ==
                       ((i % 3 == 0 && W > FSDP_MAX_RANKS_PER_LAUNCH) ? FSDP_ERR_NULL_PTR : FSDP_OK));
             }
+            CHECK(fsdp_batch_add_unshard_lp(b, L, tab.data(), fake(300)) == FSDP_OK);
+            CHECK(fsdp_batch_add_unshard_lp(b, L, bad.data(), out) == FSDP_ERR_NULL_PTR);
+            CHECK(fsdp_batch_add_unshard_lp(b, L, odd.data(), out) == FSDP_ERR_INVALID_ARG);
+            CHECK(fsdp_batch_add_unshard_lp(b, L, tab.data(), nullptr) == FSDP_ERR_NULL_PTR);
             CHECK(fsdp_batch_add_unshard(b, L, fbad, out, FSDP_BF16) == FSDP_ERR_NULL_PTR);
             CHECK(fsdp_batch_add_unshard(b, L, ftab, out, static_cast<fsdp_dtype_t>(9)) == FSDP_ERR_BAD_DTYPE);
             CHECK(fsdp_batch_add_reduce_scatter_adam(b, L, tab.data(), FSDP_F32, W, 1.0f, 1.0f, out, p, m, v, 1e-3f, 0.9f,

@@ -454,6 +454,66 @@ def test_batch_of_independent_operations_equals_single_calls(F, gdt):
     batch.close()
 
 
+@pytest.mark.parametrize("lp_dt", [torch.bfloat16, torch.float16])
+def test_batch_with_low_precision_hand_off(F, lp_dt):
+    """Sec. 4.4 hand-off in batches: updates that write the rank's 16-bit shard,
+    then gathers of 16-bit shards (one with W = 100, which is launched on its
+    own) next to a cast + gather member, against the oracle."""
+    specs = [(big_unit(), 3), (workloads.ragged_unit(), 8), (workloads.ragged_unit(), 100)]
+    units = []
+    for i, (unit, W) in enumerate(specs):
+        lay = F.fsdp_layout_init(unit.shapes, W)
+        params = make_params(unit, 70 + i, misalign=True)
+        shards, _ = alloc_shards(W, lay.shard, "contig_odd")
+        F.fsdp_flatten_shard(lay, params, shards)
+        lps = [carve(lay.shard, lp_dt, (w + i) % 8, fill=POISON16) for w in range(W)]
+        for w in range(W):
+            F.fsdp_cast_shard(lay, shards[w], lps[w])
+        units.append({"lay": lay, "W": W, "shards": shards, "lps": lps,
+                      "flat": carve(lay.padded, lp_dt, 3, fill=POISON16)})
+    torch.cuda.synchronize()
+    batch = F.Batch()
+    batch.add_unshard_lp(units[0]["lay"], units[0]["lps"], units[0]["flat"])
+    extra = carve(units[1]["lay"].padded, torch.bfloat16, 1, fill=POISON16)
+    batch.add_unshard(units[1]["lay"], units[1]["shards"], extra)              # cast + gather member in the same grid
+    batch.add_unshard_lp(units[1]["lay"], units[1]["lps"], units[1]["flat"])
+    batch.add_unshard_lp(units[2]["lay"], units[2]["lps"], units[2]["flat"])
+    batch.launch(1)
+    torch.cuda.synchronize()
+    for u in units:
+        h = [np_f32(x) for x in u["shards"]]
+        ref = oracle.unshard_bf16(h) if lp_dt == torch.bfloat16 else oracle.unshard_f16(h)
+        assert same_bits(np_bits(u["flat"]), ref), first_diff(np_bits(u["flat"]), ref)
+        assert same_bits(np_bits(u["flat"]), oracle.gather_lp([np_bits(x) for x in u["lps"]]))
+    assert same_bits(np_bits(extra), oracle.unshard_bf16([np_f32(x) for x in units[1]["shards"]]))
+    batch.close()
+
+    if lp_dt != torch.bfloat16:
+        return      # the Adam epilogue writes bf16 copies only
+    # one iteration of the hand-off: the update of rank r writes its bf16 shard, the next gather reads it
+    u = units[1]
+    lay, W, r = u["lay"], u["W"], 5
+    grads = make_grads(W, lay.padded, lay.numel, torch.bfloat16, 4242)
+    pre, post = F.fsdp_default_divide_factors(W)
+    m, v = torch.zeros(lay.shard, device="cuda"), torch.zeros(lay.shard, device="cuda")
+    p0 = np_f32(u["shards"][r]).copy()
+    b1, b2 = F.Batch(), F.Batch()
+    b1.add_reduce_scatter_adam(lay, grads, r, pre, post, None, u["shards"][r], m, v, LR, B1, B2, EPS, u["lps"][r])
+    b2.add_unshard_lp(lay, u["lps"], u["flat"])
+    b1.launch(1)
+    b2.launch(1)
+    torch.cuda.synchronize()
+    ref_g = oracle.reduce_scatter([np_grad(g) for g in grads], r, pre, post)
+    z = np.zeros(lay.shard, np.float32)
+    rp, rm, rv = oracle.adam_f32(p0, ref_g, z, z, 1, LR, B1, B2, EPS)
+    ok, bad = adam_close(np_f32(u["shards"][r]), np_f32(m), np_f32(v), rp, rm, rv, p0)
+    assert ok, bad
+    ref = oracle.unshard_bf16([np_f32(x) for x in u["shards"]])      # the other ranks' shards are unchanged
+    assert same_bits(np_bits(u["flat"]), ref), first_diff(np_bits(u["flat"]), ref)
+    b1.close()
+    b2.close()
+
+
 def test_fig3_worked_example_on_gpu(F):
     """Sec. 3.2.1 / Fig. 3: a 4x3 Linear (12 weights + 3 biases) over 16 ranks:
     one element per rank, the last rank holds the pad.  The whole path at S = 1."""
