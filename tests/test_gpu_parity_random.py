@@ -4,6 +4,8 @@ operation are drawn together, so that combinations the hand-written cases do
 not list (a split W with a misaligned bf16 slice under the deep walk, hybrid
 groups with fp16 gradients, ...) are compared with the oracle too.  The draws
 come from numpy's seeded generator: every run sees the same cases."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -77,7 +79,8 @@ def _factors(rng, F, W):
     return 3.0, float(W) / 3.0 if W % 3 == 0 else float(W)     # non-power-of-two pre: true divisions
 
 
-CASES = list(range(600))
+# FSDP_RANDOM_CASES=<n> widens the sweep for an occasional longer run
+CASES = list(range(int(os.environ.get("FSDP_RANDOM_CASES", "600"))))
 
 
 @pytest.mark.parametrize("case", CASES)
