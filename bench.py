@@ -33,8 +33,8 @@ def log(*a):
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=1, help="workload: 0 one GPT-2-small block, 1 full GPT-2-small (default), 2 1.3B blocks W=12, "
                          "3 Llama-7B blocks W=64, 4 one GPT-3-175B block W=16")
     ap.add_argument("--max-units", type=int, default=0, help="limit the number of units (0 = all)")
@@ -315,7 +315,7 @@ def main():
         # whole sequence repeated, bracketed by one pair of HIP events on the
         # launch stream: average duration per launch with the same cold-cache
         # rotation over the units' buffers as in the timed steps.
-        reps = 10
+        reps = max(10, min(200, int(25.0 / max(ms_per_step, 1e-3))))      # about 25 ms of launches per kind
         kinds = []
         for kind, _fn, _b in launches:
             if kind not in kinds:
