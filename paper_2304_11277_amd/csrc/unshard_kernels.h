@@ -9,7 +9,7 @@ namespace {
 // ---------------------------------------------------------------------------
 // unshard: flat_out[w*S + k] = cast(shard_w[k])   (Sec. 3.2.1 gather, Sec. 4.4 cast)
 // grid = nshards * tiles_per_shard blocks; block b serves shard b / tiles and
-// tile b % tiles.  A tile is kBlock * U destination vectors of 16 bytes.
+// tile b % tiles.  A tile is kBlock destination vectors of 16 bytes.
 // ---------------------------------------------------------------------------
 // bid = index of the workgroup among the unshard workgroups of the launch
 template <int LP>
