@@ -95,11 +95,11 @@ AdamConsts make_adam_consts(int64_t step, float lr, float b1, float b2, float ep
     return c;
 }
 
-// the wide rank walk loads whole batches of kWideRanks ranks: repeat the last pointer up to the batch boundary
+// the wide rank walk loads whole batches of up to kMaxWideRanks ranks: repeat the last pointer up to the batch boundary
 void pad_rank_table(PtrTable& tab, int32_t n)
 {
-    static_assert(kMaxRanks % kWideRanks == 0, "the padded table must fit");
-    for (int32_t j = n; j % kWideRanks != 0; ++j) tab.p[j] = tab.p[n - 1];
+    static_assert(kMaxRanks % kMaxWideRanks == 0, "the padded table must fit");
+    for (int32_t j = n; j % kMaxWideRanks != 0; ++j) tab.p[j] = tab.p[n - 1];
 }
 
 // The deep rank walk pays for fp32 gradients from eight rank streams on (cold
@@ -114,9 +114,9 @@ template <int GT, int PRE, bool FUSED>
 void launch_reduce(const PtrTable& tab, const RsArgs& a, hipStream_t st)
 {
     constexpr int B = kReduceBlock;
-    constexpr int E = WalkShape<GT, false>::E;
+    constexpr int E = WalkShape<GT, FUSED, false>::E;
     if constexpr (GT == kF32) {   // 16-bit gradients measured no gain from the deep walk (6 % slower at 64 ranks)
-        const int64_t deep_blocks = ceil_div(a.S / E + 1, B * WalkShape<GT, true>::C);
+        const int64_t deep_blocks = ceil_div(a.S / E + 1, B * WalkShape<GT, FUSED, true>::C);
         const int32_t walk = g_reduce_walk.load(std::memory_order_relaxed);
         const bool deep = walk == FSDP_WALK_AUTO ? a.W >= kDeepMinRanks && deep_blocks >= kDeepMinBlocks
                                                  : walk == FSDP_WALK_DEEP;

@@ -89,22 +89,26 @@ __device__ __forceinline__ float post_scale(float x, const RsArgs& a)
 // contiguous across the wave.  Ranks are taken G at a time, two such batches in
 // flight: the next batch's G*C loads are issued before the current batch's adds
 // wait for their data, and the adds run strictly in rank order.
-//   wide  (G = 4, C = 1): four rank streams per batch.  Best for up to 8 ranks,
-//         for small units (it makes the most workgroups) and for 16-bit
-//         gradients at any rank count.
+//   wide  (C = 1): one chunk per lane, the most workgroups.  G, the ranks per
+//         batch, is what measured fastest on MI355X with cold buffers: 4 for the
+//         fused kernels on 16-bit gradients (with the Adam state fetched before
+//         the walk), 1 for the fused kernels on fp32 gradients (state fetched
+//         after the walk; 3-9 % faster than G = 4 from 7 M-element units up),
+//         2 resp. 1 for the reduce-scatter alone (13 % faster than G = 4 at 64
+//         ranks: the more rank streams, the shallower the best queue per lane).
 //   deep  (G = 1, C = 4): one rank stream at a time, four chunks of it.  Used
-//         for fp32 gradients with many ranks, where the wide form loses
-//         bandwidth to the number of streams open at once (a lone kernel on
-//         MI355X: wide 6.5 TB/s at W = 8, 5.3 TB/s at W = 48; deep 6.4-6.6 TB/s
-//         throughout).
-// The host pads the pointer table to a multiple of kWideRanks with copies of the
-// last pointer, so loads never need a predicate; the padding's adds are skipped.
-constexpr int kWideRanks = 4;
-template <int GT, bool DEEP>
+//         for fp32 gradients with many ranks on large shards (another 4-10 %).
+// The host pads the pointer table to a multiple of kMaxWideRanks with copies of
+// the last pointer, so loads never need a predicate; the padding's adds are
+// skipped.
+constexpr int kMaxWideRanks = 4;
+template <int GT, bool FUSED, bool DEEP>
 struct WalkShape {
     static constexpr int E = GT != kF32 ? 8 : 4;
-    static constexpr int G = DEEP ? 1 : kWideRanks;
+    static constexpr int G = DEEP ? 1 : (GT == kF32 ? 1 : (FUSED ? kMaxWideRanks : 2));
     static constexpr int C = DEEP ? 4 : 1;
+    // fetch p, m, v (and the accumulated gradient) before the rank walk rather than after it
+    static constexpr bool kStateFirst = !DEEP && GT != kF32;
 };
 
 template <int GT, int G, int C>
@@ -173,7 +177,7 @@ __device__ __forceinline__ void add_batch(const u32x4 (&x)[G][C], int32_t n, flo
 template <int GT, int PRE, bool FUSED, bool DEEP, int B>
 __device__ __forceinline__ void reduce_body(const void* const* grads, const RsArgs& a, uint32_t bid)
 {
-    using Shape = WalkShape<GT, DEEP>;
+    using Shape = WalkShape<GT, FUSED, DEEP>;
     constexpr int E = Shape::E, G = Shape::G, C = Shape::C;
     constexpr int Q = E / 4;
     // The chunk grid is aligned on the primary fp32 output.
@@ -211,9 +215,8 @@ __device__ __forceinline__ void reduce_body(const void* const* grads, const RsAr
             for (int e = 0; e < E; ++e) outer[j][e] = -0.0f;
         }
 
-        // The optimizer state (and the accumulated gradient) of the lane's chunks.
-        // The wide shape has the registers to fetch it ahead of the rank walk, off
-        // the critical path of small launches; the deep shape fetches it after.
+        // The optimizer state (and the accumulated gradient) of the lane's chunks,
+        // fetched ahead of the rank walk or after it (WalkShape::kStateFirst).
         f32x4 pv[C][Q], mv[C][Q], vv[C][Q], old[C][Q];
         auto fetch_state = [&]() {
 #pragma unroll
@@ -229,7 +232,7 @@ __device__ __forceinline__ void reduce_body(const void* const* grads, const RsAr
                 }
             }
         };
-        if constexpr (!DEEP) fetch_state();
+        if constexpr (Shape::kStateFirst) fetch_state();
 
         u32x4 xa[G][C], xb[G][C];
         const int32_t nbatch = (W + G - 1) / G;
@@ -242,7 +245,7 @@ __device__ __forceinline__ void reduce_body(const void* const* grads, const RsAr
             if (has_b) add_batch<GT, PRE, G, C, E>(xb, W - (b + 1) * G, a.pre_c, a.group, cnt, acc, outer);
         }
 
-        if constexpr (DEEP) fetch_state();
+        if constexpr (!Shape::kStateFirst) fetch_state();
 #pragma unroll
         for (int j = 0; j < C; ++j) {
             if (!live[j]) continue;
