@@ -55,6 +55,8 @@ def parse_args():
     ap.add_argument("--next-rows", action="store_true",
                     help="measure the kernels beyond the hot path (hybrid-sharding reduce, gradient accumulation) "
                          "on the workload's largest unit and print their own JSON line")
+    ap.add_argument("--unit-scale", type=int, default=1,
+                    help="size study: every unit holds this many copies of its parameter list")
     ap.add_argument("--raf", action="store_true",
                     help="reshard after forward (Sec. 3, Sec. 4.4): every unit is unsharded twice per step, once for "
                          "the forward pass and once before its backward; the metric's bytes count both")
@@ -145,6 +147,8 @@ def main():
     units = list(wl.units)
     if args.max_units:
         units = units[:args.max_units]
+    if args.unit_scale > 1:
+        units = [workloads.Unit(f"{u.name}x{args.unit_scale}", tuple(u.shapes) * args.unit_scale) for u in units]
     pre, post = F.fsdp_default_divide_factors(wl.world_size)
     t0 = time.time()
     states = []

@@ -102,12 +102,13 @@ void pad_rank_table(PtrTable& tab, int32_t n)
     for (int32_t j = n; j % kMaxWideRanks != 0; ++j) tab.p[j] = tab.p[n - 1];
 }
 
-// The deep rank walk pays for fp32 gradients from eight rank streams on (cold
-// buffers, 4.2 M elements per slice: 4 % at 8 ranks, 7 % at 12 to 24, 10 % at 32
-// and more), provided it still makes at least four workgroups per compute unit
-// (256 of them on MI355X).
+// The deep rank walk pays for fp32 gradients from eight rank streams on when the
+// shard is large: against the wide walk (one rank per batch) it measured -8 % at
+// 3.2 M elements per shard and 64 ranks, -1 % at 4.2 M and 12 ranks, +1 % at 8.4 M
+// and 16.8 M, +3 % at 33.6 M, +9 % at 113 M and 16 ranks.  The bound below is
+// eight workgroups per compute unit (256 of them on MI355X), 8.4 M elements.
 constexpr int32_t kDeepMinRanks = 8;
-constexpr int64_t kDeepMinBlocks = 4 * 256;
+constexpr int64_t kDeepMinBlocks = 8 * 256;
 std::atomic<int32_t> g_reduce_walk{FSDP_WALK_AUTO};      // fsdp_set_reduce_walk
 
 template <int GT, int PRE, bool FUSED>
