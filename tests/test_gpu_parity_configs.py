@@ -128,6 +128,19 @@ def test_config_unit_matches_oracle(F, cfg, unit_index):
             assert not np_bits(p)[S - lay.pad:].any()
         if r == BENCH_RANK:
             bench_ref = (rp.copy(), rm.copy(), rv.copy(), np_bits(p2).copy(), np_bits(m2).copy(), np_bits(v2).copy())
+            if gdt == torch.float32:
+                # the other rank walk of the fp32 kernels at full size: same bits
+                auto_deep = W >= 8 and S >= 8 * 256 * 256 * 4 * 4
+                F.fsdp_set_reduce_walk(F.FSDP_WALK_WIDE if auto_deep else F.FSDP_WALK_DEEP)
+                try:
+                    p3, m3, v3 = shards[r].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
+                    F.fsdp_reduce_scatter_adam_fused(lay, grads, r, pre, post, None, p3, m3, v3, 1, *hp, None)
+                    torch.cuda.synchronize()
+                finally:
+                    F.fsdp_set_reduce_walk(F.FSDP_WALK_AUTO)
+                for a, b, n in ((p3, p2, "p"), (m3, m2, "m"), (v3, v2, "v")):
+                    assert same_bits(np_bits(a), np_bits(b)), f"{n}: the two rank walks differ at rank {r}"
+                del p3, m3, v3
         print(f"[step] rank {r}: reduce-scatter bit-exact, Adam within 1e-6 (bit-identical to fp32 oracle: {exact}), "
               f"fused == two calls", flush=True)
         del p, m, v, p2, m2, v2, rp, rm, rv, dp, dm, dv, gp, gm, gv, ref_g
