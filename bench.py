@@ -38,7 +38,7 @@ def parse_args():
     ap.add_argument("--config", type=int, default=1, help="workload: 0 one GPT-2-small block, 1 full GPT-2-small (default), 2 1.3B blocks W=12, "
                          "3 Llama-7B blocks W=64, 4 one GPT-3-175B block W=16")
     ap.add_argument("--max-units", type=int, default=0, help="limit the number of units (0 = all)")
-    ap.add_argument("--depth", type=int, default=3, help="units per batch in --mode batch (prefetch depth)")
+    ap.add_argument("--depth", type=int, default=6, help="units per batch in --mode batch (prefetch depth)")
     ap.add_argument("--mode", choices=["batch", "prefetch", "fused", "separate", "lp", "batch-lp"], default="batch",
                     help="batch: the updates of `depth` units and the prefetched unshards of the next `depth` units "
                          "are independent and share one launch (fsdp_batch_*); "

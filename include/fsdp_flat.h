@@ -254,7 +254,7 @@ int fsdp_grad_scaler_update(float* scale, int32_t* growth_tracker, const float* 
  * (Sec. 3.2.1).  A batch records fused reduce-scatter + Adam operations and
  * unshards that do NOT depend on each other (e.g. the updates of units i..i+2
  * and the prefetched unshards of units i+3..i+5, Sec. 3.3.2 / 3.3.3) and issues
- * them in as few grids as possible: up to 3 + 3 operations share one grid.
+ * them in as few grids as possible: up to 6 + 6 operations share one grid.
  * Results are bit-identical to issuing the operations one by one.  Operations
  * that cannot share a grid (W > 32, fp32 / fp16 unshard output, more than one
  * operation above 128 MiB, different gradient dtype or divide mode) are issued

@@ -19,7 +19,7 @@ from gpu_helpers import adam_close, first_diff, load_product, np_bits, np_f32, s
 pytestmark = pytest.mark.gpu
 
 BENCH_RANK = 0      # the rank bench.py times
-BENCH_DEPTH = 3     # bench.py's default --depth
+BENCH_DEPTH = 6     # bench.py's default --depth
 
 CASES = [(c, u) for c in range(workloads.NUM_CONFIGS) for u in workloads.config(c).distinct_units]
 
