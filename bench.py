@@ -38,7 +38,10 @@ def parse_args():
     ap.add_argument("--config", type=int, default=1, help="workload: 0 one GPT-2-small block, 1 full GPT-2-small (default), 2 1.3B blocks W=12, "
                          "3 Llama-7B blocks W=64, 4 one GPT-3-175B block W=16")
     ap.add_argument("--max-units", type=int, default=0, help="limit the number of units (0 = all)")
-    ap.add_argument("--depth", type=int, default=6, help="units per batch in --mode batch (prefetch depth)")
+    ap.add_argument("--depth", type=int, default=0,
+                    help="units per batch in --mode batch (prefetch depth); 0 = 6 when the units are small enough to "
+                         "share grids (launch-bound), 1 when they are not (then only the pairing of unit i's update "
+                         "with unit i+1's unshard matters)")
     ap.add_argument("--mode", choices=["batch", "prefetch", "fused", "separate", "lp", "batch-lp"], default="batch",
                     help="batch: the updates of `depth` units and the prefetched unshards of the next `depth` units "
                          "are independent and share one launch (fsdp_batch_*); "
@@ -174,6 +177,9 @@ def main():
     # The unsharded flat parameter is transient (Sec. 3.2.1: peak memory is the
     # largest unit); two buffers alternate, as with at most two unshards in flight.
     batched = args.mode in ("batch", "batch-lp")
+    if args.depth <= 0:
+        small = sorted(s.b_unshard for s in states)[len(states) // 2] <= (128 << 20)
+        args.depth = 6 if small else 1
     lp_handoff = args.mode in ("lp", "batch-lp")
     nflat = 2 * args.depth if batched else 2
     flats = [flat] + [torch.empty_like(flat) for _ in range(nflat - 1)]
@@ -199,16 +205,19 @@ def main():
 
         def make_batch(red, uns):
             b = F.Batch()
-            for i in red:
-                s = states[i]
-                b.add_reduce_scatter_adam(s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m, s.v, *hp,
-                                          s.lp_shards[rank] if lp_handoff else None)
-            for i in uns:
-                s = states[i]
-                if lp_handoff:
-                    b.add_unshard_lp(s.lay, s.lp_tab, flats[i % nflat][:s.P])
-                else:
-                    b.add_unshard(s.lay, s.shard_tab, flats[i % nflat][:s.P])
+            # updates and unshards alternate, so that the library can pair a large update with a large unshard
+            for j in range(max(len(red), len(uns))):
+                if j < len(red):
+                    s = states[red[j]]
+                    b.add_reduce_scatter_adam(s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m, s.v, *hp,
+                                              s.lp_shards[rank] if lp_handoff else None)
+                if j < len(uns):
+                    i = uns[j]
+                    s = states[i]
+                    if lp_handoff:
+                        b.add_unshard_lp(s.lay, s.lp_tab, flats[i % nflat][:s.P])
+                    else:
+                        b.add_unshard(s.lay, s.shard_tab, flats[i % nflat][:s.P])
             nbytes = sum(states[i].b_reduce + states[i].b_adam for i in red) + sum(states[i].b_unshard for i in uns)
             return b, nbytes
 

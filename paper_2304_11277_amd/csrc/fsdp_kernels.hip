@@ -111,17 +111,23 @@ constexpr int32_t kDeepMinRanks = 8;
 constexpr int64_t kDeepMinBlocks = 8 * 256;
 std::atomic<int32_t> g_reduce_walk{FSDP_WALK_AUTO};      // fsdp_set_reduce_walk
 
+// fp32 gradients: does the library's own choice of rank walk fall on the deep one?
+inline bool deep_walk_pays(int32_t W, int64_t S)
+{
+    const int64_t deep_blocks = ceil_div(S / 4 + 1, kReduceBlock * WalkShape<kF32, true, true>::C);
+    return W >= kDeepMinRanks && deep_blocks >= kDeepMinBlocks;
+}
+
 template <int GT, int PRE, bool FUSED>
 void launch_reduce(const PtrTable& tab, const RsArgs& a, hipStream_t st)
 {
     constexpr int B = kReduceBlock;
     constexpr int E = WalkShape<GT, FUSED, false>::E;
     if constexpr (GT == kF32) {   // 16-bit gradients measured no gain from the deep walk (6 % slower at 64 ranks)
-        const int64_t deep_blocks = ceil_div(a.S / E + 1, B * WalkShape<GT, FUSED, true>::C);
         const int32_t walk = g_reduce_walk.load(std::memory_order_relaxed);
-        const bool deep = walk == FSDP_WALK_AUTO ? a.W >= kDeepMinRanks && deep_blocks >= kDeepMinBlocks
-                                                 : walk == FSDP_WALK_DEEP;
+        const bool deep = walk == FSDP_WALK_AUTO ? deep_walk_pays(a.W, a.S) : walk == FSDP_WALK_DEEP;
         if (deep) {
+            const int64_t deep_blocks = ceil_div(a.S / E + 1, B * WalkShape<GT, FUSED, true>::C);
             hipLaunchKernelGGL((reduce_kernel<GT, PRE, FUSED, true, B>), dim3(static_cast<uint32_t>(deep_blocks)),
                                dim3(B), 0, st, tab, a);
             return;
@@ -447,12 +453,18 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* L, const void
     const int64_t tiles = ceil_div(N->S / 8 + 1, kBlock);
     const int64_t n_unshard = tiles * N->world_size;
     // Sharing a grid pays while the fixed cost of a launch (about 2 us of ramp
-    // and drain) is visible next to the smaller half; for large halves the
-    // shared kernel's register budget costs the unshard more than it saves.
+    // and drain) is visible next to the smaller half.  For large halves it
+    // still pays with fp32 gradients (5 % on 300 MB halves: the fp32 reduce body
+    // needs 20 registers) up to the shard size from which the stand-alone kernel
+    // would take the deep walk, which is worth more; with 16-bit gradients the
+    // shared kernel's register budget (52) costs a large unshard more than the
+    // launch saves (5 % slower).
     const int64_t reduce_bytes = dtype_size(grad_dtype) * L->P + 24 * L->S;
     const int64_t unshard_bytes = 6 * N->P;
     const bool small_half = (reduce_bytes < unshard_bytes ? reduce_bytes : unshard_bytes) <= kOneLaunchMaxBytes;
-    const bool one_launch = small_half && L->world_size <= kMaxRanks && N->world_size <= kMaxRanks &&
+    const bool pair_large = grad_dtype == FSDP_F32 && !deep_walk_pays(L->world_size, L->S);
+    const bool one_launch = (small_half || pair_large) && L->world_size <= kMaxRanks &&
+                            N->world_size <= kMaxRanks &&
                             next_out_dtype == FSDP_BF16 && grid_ok(n_reduce + n_unshard);
     if (!one_launch) {   // same results from the two separate entry points, one after the other
         rc = fsdp_reduce_scatter_adam_fused(L, grad_ptrs, grad_dtype, rank, pre_div, post_div, grad_shard_out, p_shard,
@@ -826,13 +838,15 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
 
     // Greedy grouping in insertion order.  A grid takes up to kBatchOps reduce
     // operations of one kernel kind and up to kBatchOps bf16 unshards, each with
-    // at most kBatchRanks ranks, and at most one operation above
-    // kOneLaunchMaxBytes (see the prefetch entry point).  Anything else is
-    // issued through its own entry point.
+    // at most kBatchRanks ranks.  Of the operations above kOneLaunchMaxBytes it
+    // takes at most one of each kind, and both kinds together only with fp32
+    // gradients (see the prefetch entry point).  Anything else is issued
+    // through its own entry point.
     BatchArgs g = {};
     ReduceKind kind = {kF32, kPreNone};
     bool have_kind = false;
-    int large = 0;
+    int large_r = 0, large_u = 0;
+    bool pairable = true;          // may a large unshard join the grid's large update?
     uint32_t r_blocks = 0, u_blocks = 0;
 
     auto flush = [&]() -> int {
@@ -840,7 +854,7 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
         int rc = FSDP_OK;
         // a grid without reduce operations never enters the reduce code, so any instantiation serves
         if (g.n_reduce == 0) kind = ReduceKind{kF32, kPreNone};
-        if (g.n_reduce == 1 && g.n_unshard == 0 && large > 0) {
+        if (g.n_reduce == 1 && g.n_unshard == 0 && large_r > 0) {
             // the lone update of a unit too large to share a grid goes through the stand-alone kernel,
             // which may choose the deep rank walk
             PtrTable tab = {};
@@ -854,7 +868,8 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
         rc = launch_status();
         g = BatchArgs{};
         have_kind = false;
-        large = 0;
+        large_r = large_u = 0;
+        pairable = true;
         r_blocks = u_blocks = 0;
         return rc;
     };
@@ -877,13 +892,15 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
             }
             const ReduceKind k = {static_cast<int>(r.dtype), pre_mode_of(r.pre)};
             const bool is_large = bytes > kOneLaunchMaxBytes;
-            if (g.n_reduce == kBatchOps || (have_kind && !(k == kind)) || (is_large && large > 0)) {
+            if (g.n_reduce == kBatchOps || (have_kind && !(k == kind)) ||
+                (is_large && (large_r > 0 || (large_u > 0 && !(k.gt == kF32 && !deep_walk_pays(W, r.L->S)))))) {
                 const int rc = flush();
                 if (rc != FSDP_OK) return rc;
             }
             kind = k;
             have_kind = true;
-            large += is_large ? 1 : 0;
+            large_r += is_large ? 1 : 0;
+            if (is_large) pairable = k.gt == kF32 && !deep_walk_pays(W, r.L->S);
             BatchReduceOp& o = g.r[g.n_reduce];
             for (int32_t w = 0; w < kBatchRanks; ++w) o.grads[w] = r.grads[w < W ? w : W - 1];   // padded for whole groups
             RsArgs& a = o.a;
@@ -919,11 +936,11 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
                 continue;
             }
             const bool is_large = bytes > kOneLaunchMaxBytes;
-            if (g.n_unshard == kBatchOps || (is_large && large > 0)) {
+            if (g.n_unshard == kBatchOps || (is_large && (large_u > 0 || (large_r > 0 && !pairable)))) {
                 const int rc = flush();
                 if (rc != FSDP_OK) return rc;
             }
-            large += is_large ? 1 : 0;
+            large_u += is_large ? 1 : 0;
             BatchUnshardOp& o = g.u[g.n_unshard];
             for (int32_t w = 0; w < kBatchRanks; ++w) o.shards[w] = u.shards[w < W ? w : W - 1];
             o.S = u.L->S;
