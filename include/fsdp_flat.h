@@ -158,8 +158,9 @@ int fsdp_reduce_scatter_adam_fused(const fsdp_layout_t* layout, const void* cons
  * Results are bit-identical to calling fsdp_reduce_scatter_adam_fused and
  * fsdp_unshard one after the other, which is also what happens (two launches)
  * when either W exceeds FSDP_MAX_RANKS_PER_LAUNCH, when next_out_dtype is
- * FSDP_F32, or when both halves move more than 128 MiB (sharing a grid only
- * pays while the fixed cost of a launch is visible next to the smaller half). */
+ * FSDP_F32, or when both halves move more than 128 MiB and the gradients are
+ * 16-bit or the shard has 8.4 M elements or more (measured: the shared grid
+ * pays for large fp32 halves, not for 16-bit ones). */
 int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* layout, const void* const* grad_ptrs,
                                               fsdp_dtype_t grad_dtype, int32_t rank, float pre_div,
                                               float post_div, float* grad_shard_out, float* p_shard,
@@ -256,8 +257,10 @@ int fsdp_grad_scaler_update(float* scale, int32_t* growth_tracker, const float* 
  * and the prefetched unshards of units i+3..i+5, Sec. 3.3.2 / 3.3.3) and issues
  * them in as few grids as possible: up to 6 + 6 operations share one grid.
  * Results are bit-identical to issuing the operations one by one.  Operations
- * that cannot share a grid (W > 32, fp32 / fp16 unshard output, more than one
- * operation above 128 MiB, different gradient dtype or divide mode) are issued
+ * that cannot share a grid (W > 32, fp32 / fp16 unshard output, a second
+ * operation of the same kind above 128 MiB, an update above 128 MiB next to an
+ * unshard above 128 MiB unless the gradients are fp32 and the shard has fewer
+ * than 8.4 M elements, different gradient dtype or divide mode) are issued
  * through their own entry points, in order.
  * The batch copies the pointer tables; layouts and device buffers must stay
  * valid while the batch is used.  A batch may be launched any number of times;
