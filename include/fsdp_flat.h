@@ -291,10 +291,9 @@ int  fsdp_batch_launch(const fsdp_batch_t* batch, int64_t step, void* hip_stream
  * the same bits.
  *   FSDP_WALK_WIDE: a lane owns one 16-byte chunk (and loads one to four ranks at a
  *                   time, by gradient dtype);
- *   FSDP_WALK_DEEP: a lane owns four chunks and loads one rank at a time (fp32
- *                   gradients only: 16-bit gradients always take the wide walk);
- *   FSDP_WALK_AUTO (default): deep for fp32 gradients from eight ranks on when the
- *                   shard has at least 8.4 M elements, else wide.
+ *   FSDP_WALK_DEEP: a lane owns four chunks and loads one rank at a time;
+ *   FSDP_WALK_AUTO (default): deep from eight ranks on when the shard has at
+ *                   least 8.4 M fp32 or 16.8 M 16-bit elements, else wide.
  * Process-wide; takes effect for launches issued after the call returns.
  * Returns FSDP_ERR_INVALID_ARG for any other value. */
 enum { FSDP_WALK_AUTO = 0, FSDP_WALK_WIDE = 1, FSDP_WALK_DEEP = 2 };

@@ -102,19 +102,22 @@ void pad_rank_table(PtrTable& tab, int32_t n)
     for (int32_t j = n; j % kMaxWideRanks != 0; ++j) tab.p[j] = tab.p[n - 1];
 }
 
-// The deep rank walk pays for fp32 gradients from eight rank streams on when the
-// shard is large: against the wide walk (one rank per batch) it measured -8 % at
-// 3.2 M elements per shard and 64 ranks, -1 % at 4.2 M and 12 ranks, +1 % at 8.4 M
-// and 16.8 M, +3 % at 33.6 M, +9 % at 113 M and 16 ranks.  The bound below is
-// eight workgroups per compute unit (256 of them on MI355X), 8.4 M elements.
+// The deep rank walk pays from eight rank streams on when the shard is large.
+// fp32 gradients, against the wide walk (one rank per batch): -8 % at 3.2 M
+// elements per shard and 64 ranks, -1 % at 4.2 M and 12 ranks, +1 % at 8.4 M and
+// 16.8 M, +3 % at 33.6 M, +9 % at 113 M and 16 ranks.  bf16 gradients (wide walk
+// with four ranks per batch): +1 to +3 % at 3.2 M and 64 ranks (386 workgroups),
+// +7 % at 113 M and 16 ranks.  The bound below is eight deep workgroups per
+// compute unit (256 of them on MI355X): 8.4 M fp32 or 16.8 M 16-bit elements.
 constexpr int32_t kDeepMinRanks = 8;
 constexpr int64_t kDeepMinBlocks = 8 * 256;
 std::atomic<int32_t> g_reduce_walk{FSDP_WALK_AUTO};      // fsdp_set_reduce_walk
 
-// fp32 gradients: does the library's own choice of rank walk fall on the deep one?
-inline bool deep_walk_pays(int32_t W, int64_t S)
+// does the library's own choice of rank walk fall on the deep one?
+inline bool deep_walk_pays(int gt, int32_t W, int64_t S)
 {
-    const int64_t deep_blocks = ceil_div(S / 4 + 1, kReduceBlock * WalkShape<kF32, true, true>::C);
+    const int64_t E = gt == kF32 ? 4 : 8;
+    const int64_t deep_blocks = ceil_div(S / E + 1, kReduceBlock * WalkShape<kF32, true, true>::C);
     return W >= kDeepMinRanks && deep_blocks >= kDeepMinBlocks;
 }
 
@@ -123,15 +126,13 @@ void launch_reduce(const PtrTable& tab, const RsArgs& a, hipStream_t st)
 {
     constexpr int B = kReduceBlock;
     constexpr int E = WalkShape<GT, FUSED, false>::E;
-    if constexpr (GT == kF32) {   // 16-bit gradients measured no gain from the deep walk (6 % slower at 64 ranks)
-        const int32_t walk = g_reduce_walk.load(std::memory_order_relaxed);
-        const bool deep = walk == FSDP_WALK_AUTO ? deep_walk_pays(a.W, a.S) : walk == FSDP_WALK_DEEP;
-        if (deep) {
-            const int64_t deep_blocks = ceil_div(a.S / E + 1, B * WalkShape<GT, FUSED, true>::C);
-            hipLaunchKernelGGL((reduce_kernel<GT, PRE, FUSED, true, B>), dim3(static_cast<uint32_t>(deep_blocks)),
-                               dim3(B), 0, st, tab, a);
-            return;
-        }
+    const int32_t walk = g_reduce_walk.load(std::memory_order_relaxed);
+    const bool deep = walk == FSDP_WALK_AUTO ? deep_walk_pays(GT, a.W, a.S) : walk == FSDP_WALK_DEEP;
+    if (deep) {
+        const int64_t deep_blocks = ceil_div(a.S / E + 1, B * WalkShape<GT, FUSED, true>::C);
+        hipLaunchKernelGGL((reduce_kernel<GT, PRE, FUSED, true, B>), dim3(static_cast<uint32_t>(deep_blocks)), dim3(B),
+                           0, st, tab, a);
+        return;
     }
     const int64_t blocks = ceil_div(a.S / E + 1, B);
     hipLaunchKernelGGL((reduce_kernel<GT, PRE, FUSED, false, B>), dim3(static_cast<uint32_t>(blocks)), dim3(B), 0, st,
@@ -462,7 +463,7 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* L, const void
     const int64_t reduce_bytes = dtype_size(grad_dtype) * L->P + 24 * L->S;
     const int64_t unshard_bytes = 6 * N->P;
     const bool small_half = (reduce_bytes < unshard_bytes ? reduce_bytes : unshard_bytes) <= kOneLaunchMaxBytes;
-    const bool pair_large = grad_dtype == FSDP_F32 && !deep_walk_pays(L->world_size, L->S);
+    const bool pair_large = grad_dtype == FSDP_F32 && !deep_walk_pays(kF32, L->world_size, L->S);
     const bool one_launch = (small_half || pair_large) && L->world_size <= kMaxRanks &&
                             N->world_size <= kMaxRanks &&
                             next_out_dtype == FSDP_BF16 && grid_ok(n_reduce + n_unshard);
@@ -893,14 +894,14 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
             const ReduceKind k = {static_cast<int>(r.dtype), pre_mode_of(r.pre)};
             const bool is_large = bytes > kOneLaunchMaxBytes;
             if (g.n_reduce == kBatchOps || (have_kind && !(k == kind)) ||
-                (is_large && (large_r > 0 || (large_u > 0 && !(k.gt == kF32 && !deep_walk_pays(W, r.L->S)))))) {
+                (is_large && (large_r > 0 || (large_u > 0 && !(k.gt == kF32 && !deep_walk_pays(kF32, W, r.L->S)))))) {
                 const int rc = flush();
                 if (rc != FSDP_OK) return rc;
             }
             kind = k;
             have_kind = true;
             large_r += is_large ? 1 : 0;
-            if (is_large) pairable = k.gt == kF32 && !deep_walk_pays(W, r.L->S);
+            if (is_large) pairable = k.gt == kF32 && !deep_walk_pays(kF32, W, r.L->S);
             BatchReduceOp& o = g.r[g.n_reduce];
             for (int32_t w = 0; w < kBatchRanks; ++w) o.grads[w] = r.grads[w < W ? w : W - 1];   // padded for whole groups
             RsArgs& a = o.a;

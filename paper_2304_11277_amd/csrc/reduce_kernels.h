@@ -97,7 +97,7 @@ __device__ __forceinline__ float post_scale(float x, const RsArgs& a)
 //         2 resp. 1 for the reduce-scatter alone (13 % faster than G = 4 at 64
 //         ranks: the more rank streams, the shallower the best queue per lane).
 //   deep  (G = 1, C = 4): one rank stream at a time, four chunks of it.  Used
-//         for fp32 gradients with many ranks on large shards (another 4-10 %).
+//         with many ranks on large shards (another 1-9 %).
 // The host pads the pointer table to a multiple of kMaxWideRanks with copies of
 // the last pointer, so loads never need a predicate; the padding's adds are
 // skipped.
