@@ -514,6 +514,38 @@ def test_batch_with_low_precision_hand_off(F, lp_dt):
     b2.close()
 
 
+def test_resume_from_copied_state_is_bit_identical(F):
+    """The state is caller-owned (p, m, v, step count): two steps in place equal
+    one step, a copy of the state to other buffers, and one more step there."""
+    unit, W, r = big_unit(), 8, 3
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S = lay.shard
+    pre, post = F.fsdp_default_divide_factors(W)
+    g1 = make_grads(W, lay.padded, lay.numel, torch.float32, 611)
+    g2 = make_grads(W, lay.padded, lay.numel, torch.float32, 612)
+    p, _, m, v = _adam_state(S, 1, 77)
+    h0 = np_f32(p).copy()
+    F.fsdp_reduce_scatter_adam_fused(lay, g1, r, pre, post, None, p, m, v, 1, LR, B1, B2, EPS, None)
+    torch.cuda.synchronize()
+    saved = [np_f32(x).copy() for x in (p, m, v)]                      # "checkpoint" on the host
+    F.fsdp_reduce_scatter_adam_fused(lay, g2, r, pre, post, None, p, m, v, 2, LR, B1, B2, EPS, None)
+    p2, m2, v2 = (carve(S, torch.float32, off) for off in (1, 2, 3))   # restore into other, misaligned buffers
+    for dst, src in zip((p2, m2, v2), saved):
+        dst.copy_(torch.from_numpy(src))
+    F.fsdp_reduce_scatter_adam_fused(lay, g2, r, pre, post, None, p2, m2, v2, 2, LR, B1, B2, EPS, None)
+    torch.cuda.synchronize()
+    for a, b, n in ((p, p2, "p"), (m, m2, "m"), (v, v2, "v")):
+        assert same_bits(np_bits(a), np_bits(b)), n
+    # and the chain equals the oracle's
+    z = np.zeros(S, np.float32)
+    r1 = oracle.reduce_scatter([np_grad(g) for g in g1], r, pre, post)
+    r2 = oracle.reduce_scatter([np_grad(g) for g in g2], r, pre, post)
+    op, om, ov = oracle.adam_f32(h0, r1, z, z, 1, LR, B1, B2, EPS)
+    op2, om2, ov2 = oracle.adam_f32(op, r2, om, ov, 2, LR, B1, B2, EPS)
+    ok, bad = adam_close(np_f32(p), np_f32(m), np_f32(v), op2, om2, ov2, op, m_old=om, g=r2)
+    assert ok, bad
+
+
 def test_fig3_worked_example_on_gpu(F):
     """Sec. 3.2.1 / Fig. 3: a 4x3 Linear (12 weights + 3 biases) over 16 ranks:
     one element per rank, the last rank holds the pad.  The whole path at S = 1."""
