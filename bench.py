@@ -482,8 +482,8 @@ def cpu_baseline(states, wl, pre, post, rank, hp, torch):
         else:
             h_slices = [g[rank * S:(rank + 1) * S].cpu().view(torch.int16).numpy().view(np.uint16) for g in s.grads]
         host.append(([x.cpu().numpy() for x in s.shards], h_slices, s.m.cpu().numpy(), s.v.cpu().numpy(), s.b_total))
-    passes = 0
-    while spent < budget_s:
+    def one_pass():
+        nonlocal done_bytes, spent, n_units
         for h_shards, h_slices, h_m, h_v, nbytes in host:
             t0 = time.perf_counter()
             oracle.unshard_bf16(h_shards)
@@ -492,10 +492,25 @@ def cpu_baseline(states, wl, pre, post, rank, hp, torch):
             spent += time.perf_counter() - t0
             done_bytes += nbytes
             n_units += 1
+
+    passes = 0
+    while spent < budget_s:
+        one_pass()
         passes += 1
-    return {"value": round(done_bytes / spent / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "sample": f"{passes} passes over all {len(states)} units of {wl.name} "
-                                        f"({n_units} unit passes), {spent:.2f} s of oracle time"}
+    out = {"value": round(done_bytes / spent / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(),
+           "kind": "oracle", "sample": f"{passes} passes over all {len(states)} units of {wl.name} "
+                                       f"({n_units} unit passes), {spent:.2f} s of oracle time"}
+    # the same on one host thread, a shorter sample (reported beside the all-cores figure)
+    threads = oracle.num_threads()
+    oracle.set_num_threads(1)
+    try:
+        done_bytes, spent, n_units = 0, 0.0, 0
+        while spent < 3.0:
+            one_pass()
+        out["value_1_thread"] = round(done_bytes / spent / 1e9, 3)
+    finally:
+        oracle.set_num_threads(threads)
+    return out
 
 
 if __name__ == "__main__":
