@@ -225,8 +225,11 @@ def test_random_case(F, case):
             rp, rm, rv = oracle.adam_f32(hp0, ref_g, hm0, hv0, t, *HP)
             ok, bad = adam_close(np_f32(p), np_f32(m), np_f32(v), rp, rm, rv, hp0, m_old=hm0, g=ref_g)
             assert ok, f"Adam vs fp32 oracle: {bad}"
+            # The binary64 evaluation is a second witness, not the bar: from a random state with
+            # v near zero the binary32 oracle itself departs from it by up to 1.04e-6 (2 of 6e8
+            # elements beyond 1e-6 in a CPU sweep of this distribution), hence twice the tolerance.
             dp, dm, dv = oracle.adam_f64(hp0, ref_g, hm0, hv0, t, *HP)
-            ok, bad = adam_close(np_f32(p), np_f32(m), np_f32(v), dp, dm, dv, hp0, m_old=hm0, g=ref_g)
+            ok, bad = adam_close(np_f32(p), np_f32(m), np_f32(v), dp, dm, dv, hp0, m_old=hm0, g=ref_g, rel=2e-6)
             assert ok, f"Adam vs fp64 oracle: {bad}"
             if want_lp:
                 ref_lp = oracle.cast_bf16(np_f32(p))
