@@ -79,8 +79,9 @@ def _factors(rng, F, W):
     return 3.0, float(W) / 3.0 if W % 3 == 0 else float(W)     # non-power-of-two pre: true divisions
 
 
-# FSDP_RANDOM_CASES=<n> widens the sweep for an occasional longer run
+# FSDP_RANDOM_CASES=<n> widens the sweep for an occasional longer run, FSDP_RANDOM_SCALE=<k> multiplies the unit sizes
 CASES = list(range(int(os.environ.get("FSDP_RANDOM_CASES", "600"))))
+SCALE = int(os.environ.get("FSDP_RANDOM_SCALE", "1"))
 
 
 @pytest.mark.parametrize("case", CASES)
@@ -93,7 +94,7 @@ def test_random_case(F, case):
         W = min(W, 64)
     if op in ("prefetch", "batch"):
         W = min(W, 65)
-    target = int(rng.choice([1, 50, 3000, 40000, 300000]))
+    target = int(rng.choice([1, 50, 3000, 40000, 300000])) * SCALE
     shapes = _shapes(rng, target)
     lay = F.fsdp_layout_init(shapes, W)
     S, P, N = lay.shard, lay.padded, lay.numel
