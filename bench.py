@@ -1,20 +1,26 @@
 #!/usr/bin/env python3
 """Benchmark of the FlatParameter data path on one MI355X.
 
-A step is one pass of the hot path over every FSDP unit of the workload, in
+A step is one pass of the hot path over every FSDP unit of a workload, in
 order: unshard (fp32 shards -> bf16 flat buffer, all W ranks' shards), then the
 rank-0 share of the reduce-scatter over W simulated ranks' gradient buffers and
 the sharded Adam step.  Inputs are synthetic, seeded, and resident in HBM before
 the timed region starts.
 
-Prints ONE JSON line:  metric = effective HBM GB/s (algorithmic bytes of
-unshard + reduce-scatter + Adam, summed over the units, per second).
+Without --config all five configurations are timed in one run.  The headline
+(`value`, `config.workload`, `roofline`, `cpu_baseline`) is the largest one, a
+GPT-3-175B block over 16 ranks (18.1 GB per pass); the others are listed under
+`configs`.  Prints ONE JSON line: metric = effective HBM GB/s (algorithmic bytes
+of unshard + reduce-scatter + Adam, summed over the units, per second).
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
+import gc
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -23,7 +29,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 GRAPH_MIN_LAUNCHES = 16      # steps with more launches than this are captured in a HIP graph by default
-HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published
+HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, published
+HEADLINE_CONFIG = 4          # the largest single-GPU configuration
+COLD_REPLICAS = 6            # configuration 0 rotates over this many copies of its unit (see run_config)
+PROBE_SRC = os.path.join(ROOT, "bench_probe.hip")
+PROBE_LIB = os.path.join(ROOT, "libbench_probe.so")
 
 
 def log(*a):
@@ -33,31 +43,35 @@ def log(*a):
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--config", type=int, default=1, help="workload: 0 one GPT-2-small block, 1 full GPT-2-small (default), 2 1.3B blocks W=12, "
-                         "3 Llama-7B blocks W=64, 4 one GPT-3-175B block W=16")
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=None,
+                    help="time one workload only: 0 one GPT-2-small block, 1 full GPT-2-small, 2 1.3B blocks W=12, "
+                         "3 Llama-7B blocks W=64, 4 one GPT-3-175B block W=16 (default: all five, headline = 4)")
     ap.add_argument("--max-units", type=int, default=0, help="limit the number of units (0 = all)")
     ap.add_argument("--depth", type=int, default=0,
                     help="units per batch in --mode batch (prefetch depth); 0 = 6 when the units are small enough to "
                          "share grids (launch-bound), 1 when they are not (then only the pairing of unit i's update "
                          "with unit i+1's unshard matters)")
-    ap.add_argument("--mode", choices=["batch", "prefetch", "fused", "separate", "lp", "batch-lp"], default="batch",
+    ap.add_argument("--mode", choices=["batch", "fused", "separate", "lp", "batch-lp"], default="batch",
                     help="batch: the updates of `depth` units and the prefetched unshards of the next `depth` units "
-                         "are independent and share one launch (fsdp_batch_*); "
-                         "prefetch: unit i's fused reduce-scatter+Adam shares one launch with unit i+1's unshard "
-                         "(backward prefetching); fused: reduce-scatter + Adam in one launch, unshard in another; "
+                         "are independent and are recorded as one batch (fsdp_batch_*), which the library issues in "
+                         "as few grids as it can; fused: reduce-scatter + Adam in one launch, unshard in another; "
                          "separate: the three required entry points, one launch each; lp: every rank keeps a bf16 "
                          "copy of its shard (written by the fused Adam), the unshard gathers bf16 (Sec. 4.4); "
                          "batch-lp: the same hand-off issued as batches (moves 4P instead of 6P per unshard; the "
                          "metric's numerator stays the fixed 6P)")
     ap.add_argument("--graph", action="store_true", help="always replay the step as a HIP graph")
     ap.add_argument("--no-graph", action="store_true", help="always launch eagerly")
+    ap.add_argument("--replicas", type=int, default=0,
+                    help="rotate the steps over this many copies of the workload's buffers (cold caches); 0 = "
+                         f"{COLD_REPLICAS} for configuration 0, whose single unit would otherwise stay in the 256 MB "
+                         "Infinity Cache, 1 for the others (their steps already cycle through far more than that)")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
                     help="run only N launches of a plain 256 MiB copy kernel (calibrates rocprofv3 --pmc byte counters)")
     ap.add_argument("--next-rows", action="store_true",
-                    help="measure the kernels beyond the hot path (hybrid-sharding reduce, gradient accumulation) "
-                         "on the workload's largest unit and print their own JSON line")
+                    help="measure the kernels beyond the hot path (hybrid-sharding reduce, gradient accumulation, "
+                         "fp16 / fp32 unshard, unscale) on the workload's largest unit and print their own JSON line")
     ap.add_argument("--unit-scale", type=int, default=1,
                     help="size study: every unit holds this many copies of its parameter list")
     ap.add_argument("--raf", action="store_true",
@@ -66,23 +80,112 @@ def parse_args():
     ap.add_argument("--grad-dtype", choices=["f32", "bf16"], default=None,
                     help="override the workload's gradient dtype (the fp32 / bf16 variants of every configuration)")
     ap.add_argument("--walk", choices=["auto", "wide", "deep"], default="auto",
-                    help="rank walk of the stand-alone reduce-scatter kernels (fsdp_set_reduce_walk)")
+                    help="rank walk of the stand-alone reduce-scatter kernels (the layouts' fsdp_layout_init_ex hint)")
     ap.add_argument("--grad-sets", type=int, default=0,
                     help="cap the number of distinct sets of gradient buffers per unit shape (0 = as many as fit)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (timing and parity)")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the plain copy / read / write kernels")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
-                    help="rocprofv3 --pmc derived HBM bytes per launch (written by hand from profiles/)")
+                    help="HBM bytes per launch by `workload:kernel`, from rocprofv3 --pmc runs (see profiles/)")
     return ap.parse_args()
 
 
+# ---------------------------------------------------------------------------
+# measurement support: plain streaming kernels (bench_probe.hip)
+# ---------------------------------------------------------------------------
+def build_probe(force: bool = False) -> str:
+    """Compile bench_probe.hip next to this file (hipcc, gfx950)."""
+    if not force and os.path.exists(PROBE_LIB) and os.path.getmtime(PROBE_LIB) >= os.path.getmtime(PROBE_SRC):
+        return PROBE_LIB
+    tmp = PROBE_LIB + f".tmp{os.getpid()}"
+    hipcc = os.environ.get("HIPCC") or ("/opt/rocm/bin/hipcc" if os.path.exists("/opt/rocm/bin/hipcc") else "hipcc")
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Xclang",
+                           "-target-feature", "-Xclang", "-packed-fp32-ops", "-x", "hip", PROBE_SRC, "-o", tmp])
+    os.replace(tmp, PROBE_LIB)
+    return PROBE_LIB
+
+
+def load_probe():
+    lib = ctypes.CDLL(build_probe(force=False))
+    vp, i64 = ctypes.c_void_p, ctypes.c_int64
+    lib.fsdp_probe_copy.argtypes = [vp, vp, i64, vp]
+    lib.fsdp_probe_read.argtypes = [vp, i64, vp, vp]
+    lib.fsdp_probe_write.argtypes = [vp, i64, ctypes.c_float, vp]
+    return lib
+
+
+def measure_ceilings(torch):
+    """Plain copy, read-only and write-only streaming kernels over 1 GiB
+    buffers (four in rotation, far beyond the 256 MB Infinity Cache), timed
+    with HIP events on the launch stream: what this machine gives a kernel that
+    does nothing but stream."""
+    lib = load_probe()
+    nbytes = 1 << 30
+    bufs = [torch.zeros(nbytes // 4, dtype=torch.float32, device="cuda") for _ in range(4)]
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    reps = 24
+
+    def timed(fn, moved):
+        for i in range(4):
+            fn(i)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(reps):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        return round(moved * reps / (a.elapsed_time(b) * 1e-3) / 1e9, 1)
+
+    def chk(rc):
+        assert rc == 0, f"probe kernel launch failed: hipError_t {rc}"
+
+    out = {
+        "copy_GBps": timed(lambda i: chk(lib.fsdp_probe_copy(bufs[(i + 1) % 4].data_ptr(), bufs[i % 4].data_ptr(), nbytes,
+                                                             st)), 2 * nbytes),
+        "read_GBps": timed(lambda i: chk(lib.fsdp_probe_read(bufs[i % 4].data_ptr(), nbytes, sink.data_ptr(), st)), nbytes),
+        "write_GBps": timed(lambda i: chk(lib.fsdp_probe_write(bufs[i % 4].data_ptr(), nbytes, 0.0, st)), nbytes),
+        "buffer_bytes": nbytes,
+        "note": "plain nontemporal streaming kernels of bench_probe.hip, same run, HIP events; copy counts bytes read + "
+                "bytes written",
+    }
+    assert float(sink.item()) == 0.0
+    del bufs
+    torch.cuda.empty_cache()
+    return out
+
+
+def probe_copy(n, torch):
+    """N launches of a plain copy of 256 MiB (reads 256 MiB, writes 256 MiB)."""
+    lib = load_probe()
+    nbytes = 256 << 20
+    bufs = [(torch.ones(nbytes // 4, dtype=torch.float32, device="cuda"),
+             torch.empty(nbytes // 4, dtype=torch.float32, device="cuda")) for _ in range(3)]
+    torch.cuda.synchronize()
+    st = torch.cuda.current_stream().cuda_stream
+    for i in range(n):
+        src, dst = bufs[i % len(bufs)]
+        rc = lib.fsdp_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, st)
+        assert rc == 0, rc
+    torch.cuda.synchronize()
+    assert bool((bufs[0][1] == 1).all())
+    print(json.dumps({"probe": "copy", "launches": n, "bytes_read_per_launch": nbytes,
+                      "bytes_written_per_launch": nbytes}), flush=True)
+
+
+# ---------------------------------------------------------------------------
+# one workload
+# ---------------------------------------------------------------------------
 class UnitState:
     """Device buffers of one FSDP unit (caller-owned, as the library expects)."""
 
-    def __init__(self, F, wl, unit, index, torch, workloads, share_grads_with=None):
+    def __init__(self, F, wl, unit, index, torch, workloads, share_grads_with=None, walk=0):
         W = wl.world_size
         self.name = unit.name
-        self.lay = F.fsdp_layout_init(unit.shapes, W)
+        self.index = index
+        self.lay = F.fsdp_layout_init(unit.shapes, W, reduce_walk=walk)
         S, P, N = self.lay.shard, self.lay.padded, self.lay.numel
         self.S, self.P, self.N, self.W = S, P, N, W
         self.gbytes = 4 if wl.grad_dtype == "f32" else 2
@@ -108,292 +211,402 @@ class UnitState:
         self.v = torch.zeros(S, dtype=torch.float32, device="cuda")
         self.gshard = torch.empty(S, dtype=torch.float32, device="cuda")
         self.shard_tab = F.PtrArray(self.shards)
-        self.lp_base = torch.empty(W * S, dtype=torch.bfloat16, device="cuda")
-        self.lp_shards = [self.lp_base[w * S:(w + 1) * S] for w in range(W)]
-        for w in range(W):
-            F.fsdp_cast_shard(self.lay, self.shards[w], self.lp_shards[w])
-        self.lp_tab = F.PtrArray(self.lp_shards)
         self.grad_tab = F.PtrArray(self.grads)
+        self.lp_shards = self.lp_tab = None
         # algorithmic bytes (fixed numerators, whatever the kernels really touch)
         self.b_unshard = 6 * P
         self.b_reduce = self.gbytes * P + 4 * S
         self.b_adam = 28 * S
         self.b_total = self.b_unshard + self.b_reduce + self.b_adam
 
+    def make_lp_shards(self, F, torch):
+        """The ranks' bf16 copies of their shards (Sec. 4.4 hand-off modes only)."""
+        W, S = self.W, self.S
+        self.lp_base = torch.empty(W * S, dtype=torch.bfloat16, device="cuda")
+        self.lp_shards = [self.lp_base[w * S:(w + 1) * S] for w in range(W)]
+        for w in range(W):
+            F.fsdp_cast_shard(self.lay, self.shards[w], self.lp_shards[w])
+        self.lp_tab = F.PtrArray(self.lp_shards)
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build simulates all W ranks on ONE GPU; --gpus must be 1 "
-              "(no multi-GPU figure exists for it)", file=sys.stderr)
-        sys.exit(2)
 
-    import torch
-    import workloads
-    from paper_2304_11277_amd import build as fbuild
-    fbuild.build_lib(force=False)
-    import paper_2304_11277_amd as F
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    if args.probe_copy:
-        probe_copy(args.probe_copy, torch, fbuild)
-        return
-    F.fsdp_set_reduce_walk({"auto": F.FSDP_WALK_AUTO, "wide": F.FSDP_WALK_WIDE, "deep": F.FSDP_WALK_DEEP}[args.walk])
-    wl = workloads.config(args.config)
-    if args.grad_dtype:
-        import dataclasses
-        wl = dataclasses.replace(wl, grad_dtype=args.grad_dtype)
-    if args.next_rows:
-        next_rows(args, wl, F, torch, workloads)
-        return
-    units = list(wl.units)
-    if args.max_units:
-        units = units[:args.max_units]
-    if args.unit_scale > 1:
-        units = [workloads.Unit(f"{u.name}x{args.unit_scale}", tuple(u.shapes) * args.unit_scale) for u in units]
-    pre, post = F.fsdp_default_divide_factors(wl.world_size)
-    t0 = time.time()
+def make_states(F, wl, units, args, torch, workloads):
     states = []
     grad_budget = 160e9          # bytes of HBM given to the simulated ranks' gradient buffers
     used = 0.0
+    walk = {"auto": F.FSDP_WALK_AUTO, "wide": F.FSDP_WALK_WIDE, "deep": F.FSDP_WALK_DEEP}[args.walk]
     for i, u in enumerate(units):
         share = None
         need = wl.world_size * sum(workloads.numel(s) for s in u.shapes) * (4 if wl.grad_dtype == "f32" else 2)
         same = [s for s in states if s.unit_shapes == u.shapes and s.owns_grads]
         if used + need > grad_budget or (args.grad_sets and len(same) >= args.grad_sets):
             share = same[len(states) % len(same)] if same else None
-        st = UnitState(F, wl, u, i, torch, workloads, share_grads_with=share)
+        st = UnitState(F, wl, u, i, torch, workloads, share_grads_with=share, walk=walk)
         st.unit_shapes, st.owns_grads = u.shapes, share is None
         used += need if share is None else 0
         states.append(st)
-    flat = torch.empty(max(s.P for s in states), dtype=torch.bfloat16, device="cuda")   # transient, reused
-    torch.cuda.synchronize()
-    log(f"[bench] {wl.name}: {len(states)} units, W={wl.world_size}, grads {wl.grad_dtype}, "
-        f"setup {time.time() - t0:.1f}s, HBM in use {torch.cuda.memory_allocated() / 2**30:.2f} GiB")
-    hp = (wl.lr, wl.beta1, wl.beta2, wl.eps)
-    rank = 0
+    return states
 
-    # The unsharded flat parameter is transient (Sec. 3.2.1: peak memory is the
-    # largest unit); two buffers alternate, as with at most two unshards in flight.
-    batched = args.mode in ("batch", "batch-lp")
-    if args.depth <= 0:
-        small = sorted(s.b_unshard for s in states)[len(states) // 2] <= (128 << 20)
-        args.depth = 6 if small else 1
-    lp_handoff = args.mode in ("lp", "batch-lp")
-    nflat = 2 * args.depth if batched else 2
-    flats = [flat] + [torch.empty_like(flat) for _ in range(nflat - 1)]
 
-    def unshard(s, buf):
-        F.fsdp_unshard(s.lay, s.shard_tab, buf[:s.P])
-
-    def reduce_adam(s, t):
-        F.fsdp_reduce_scatter_adam_fused(s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m, s.v, t,
-                                         *hp, None)
-
-    def reduce_adam_prefetch(s, t, nxt, buf):
-        F.fsdp_reduce_scatter_adam_prefetch_unshard(s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m,
-                                                    s.v, t, *hp, None, nxt.lay, nxt.shard_tab, buf[:nxt.P])
-
-    # One step as a list of launches: (kernel kind, callable(t), algorithmic bytes).
-    launches = []
+def build_launches(F, states, flats, args, depth, rank, pre, post, hp):
+    """One step as a list of launches, each exactly one kernel of the library:
+    (kernel name, callable(t), algorithmic bytes, bytes the kernel touches)."""
+    mode = args.mode
+    lp_handoff = mode in ("lp", "batch-lp")
+    nflat = len(flats)
     n = len(states)
-    bkind = "batch_lp" if lp_handoff else "batch"
-    if batched:
-        d = args.depth
-        groups = [list(range(i, min(i + d, n))) for i in range(0, n, d)]
+    launches = []
 
-        def make_batch(red, uns):
+    def touched_update(s):
+        return s.gbytes * s.P + (26 if lp_handoff else 24) * s.S      # fused: the gradient shard stays in registers
+
+    def touched_unshard(s):
+        return (4 if lp_handoff else 6) * s.P
+
+    def batch_items(ops):
+        """ops: [("update" | "unshard", unit index)] in issue order.  One batch when the library issues it as one
+        grid; otherwise one batch per operation, in the same order, so that every item is one kernel."""
+        def record(sub):
             b = F.Batch()
-            # updates and unshards alternate, so that the library can pair a large update with a large unshard
-            for j in range(max(len(red), len(uns))):
-                if j < len(red):
-                    s = states[red[j]]
+            for kind, i in sub:
+                s = states[i]
+                if kind == "update":
                     b.add_reduce_scatter_adam(s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m, s.v, *hp,
                                               s.lp_shards[rank] if lp_handoff else None)
-                if j < len(uns):
-                    i = uns[j]
-                    s = states[i]
-                    if lp_handoff:
-                        b.add_unshard_lp(s.lay, s.lp_tab, flats[i % nflat][:s.P])
-                    else:
-                        b.add_unshard(s.lay, s.shard_tab, flats[i % nflat][:s.P])
-            nbytes = sum(states[i].b_reduce + states[i].b_adam for i in red) + sum(states[i].b_unshard for i in uns)
-            return b, nbytes
-
-        b0, nb0 = make_batch([], groups[0])
-        launches.append((bkind, (lambda t, b=b0: b.launch(t)), nb0))
-        for j, grp in enumerate(groups):
-            nxt = groups[j + 1] if j + 1 < len(groups) else []
-            bj, nbj = make_batch(grp, nxt)
-            launches.append((bkind, (lambda t, b=bj: b.launch(t)), nbj))
-    if args.raf:
-        # forward pass: the unshards alone, in forward order (the list above then plays the backward pass)
-        fwd = []
-        if batched:
-            for grp in groups:
-                b, nb = make_batch([], grp)
-                fwd.append((bkind, (lambda t, b=b: b.launch(t)), nb))
-        else:
-            for i, s in enumerate(states):
-                if args.mode == "lp":
-                    fwd.append(("unshard_lp", (lambda t, s=s, buf=flats[i % 2]:
-                                               F.fsdp_unshard_lp(s.lay, s.lp_tab, buf[:s.P])), s.b_unshard))
+                elif lp_handoff:
+                    b.add_unshard_lp(s.lay, s.lp_tab, flats[i % nflat][:s.P])
                 else:
-                    fwd.append(("unshard", (lambda t, s=s, buf=flats[i % 2]: unshard(s, buf)), s.b_unshard))
-        launches = fwd + launches
-    for i, s in enumerate(states):
+                    b.add_unshard(s.lay, s.shard_tab, flats[i % nflat][:s.P])
+            return b
+
+        def item(b, sub, plan):
+            alg = sum(states[i].b_reduce + states[i].b_adam if k == "update" else states[i].b_unshard for k, i in sub)
+            tch = sum(touched_update(states[i]) if k == "update" else touched_unshard(states[i]) for k, i in sub)
+            return (plan["kernel"], (lambda t, b=b: b.launch(t)), alg, tch)
+
+        b = record(ops)
+        plan = b.launches()
+        if len(plan) == 1:
+            return [item(b, ops, plan[0])]
+        b.close()
+        out = []
+        for op in ops:
+            b1 = record([op])
+            p1 = b1.launches()
+            assert len(p1) == 1, f"{op}: {p1}"
+            out.append(item(b1, [op], p1[0]))
+        return out
+
+    if mode in ("batch", "batch-lp"):
+        groups = [list(range(i, min(i + depth, n))) for i in range(0, n, depth)]
+
+        def ops_of(red, uns):
+            # updates and unshards alternate, so that the library can pair a large update with a large unshard
+            ops = []
+            for j in range(max(len(red), len(uns))):
+                if j < len(red):
+                    ops.append(("update", red[j]))
+                if j < len(uns):
+                    ops.append(("unshard", uns[j]))
+            return ops
+
+        if args.raf:      # forward pass: the unshards alone, in forward order (the rest then plays the backward pass)
+            for grp in groups:
+                launches += batch_items(ops_of([], grp))
+        launches += batch_items(ops_of([], groups[0]))
+        for j, grp in enumerate(groups):
+            launches += batch_items(ops_of(grp, groups[j + 1] if j + 1 < len(groups) else []))
+        return launches
+
+    def unshard_item(i, s):
         buf = flats[i % 2]
-        if batched:
-            break
-        if args.mode == "prefetch":
-            if i == 0:
-                launches.append(("unshard", (lambda t, s=s, buf=buf: unshard(s, buf)), s.b_unshard))
-            if i + 1 < n:
-                nxt, nbuf = states[i + 1], flats[(i + 1) % 2]
-                launches.append(("reduce_adam+unshard",
-                                 (lambda t, s=s, nxt=nxt, nbuf=nbuf: reduce_adam_prefetch(s, t, nxt, nbuf)),
-                                 s.b_reduce + s.b_adam + nxt.b_unshard))
-            else:
-                launches.append(("reduce_adam", (lambda t, s=s: reduce_adam(s, t)), s.b_reduce + s.b_adam))
-        elif args.mode == "lp":
-            launches.append(("unshard_lp", (lambda t, s=s, buf=buf: F.fsdp_unshard_lp(s.lay, s.lp_tab, buf[:s.P])),
-                             s.b_unshard))
-            launches.append(("reduce_adam_lp", (lambda t, s=s: F.fsdp_reduce_scatter_adam_fused(
-                s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m, s.v, t, *hp, s.lp_shards[rank])),
-                s.b_reduce + s.b_adam))
+        if mode == "lp":
+            return ("gather_lp_kernel", (lambda t, s=s, buf=buf: F.fsdp_unshard_lp(s.lay, s.lp_tab, buf[:s.P])),
+                    s.b_unshard, touched_unshard(s))
+        return ("unshard_lp_kernel", (lambda t, s=s, buf=buf: F.fsdp_unshard(s.lay, s.shard_tab, buf[:s.P])),
+                s.b_unshard, touched_unshard(s))
+
+    assert all(s.W <= 64 for s in states), "these modes name one kernel per entry point, which holds up to 64 ranks"
+    if args.raf:
+        launches += [unshard_item(i, s) for i, s in enumerate(states)]
+    for i, s in enumerate(states):
+        launches.append(unshard_item(i, s))
+        if mode in ("fused", "lp"):
+            launches.append(("reduce_kernel", (lambda t, s=s: F.fsdp_reduce_scatter_adam_fused(
+                s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m, s.v, t, *hp,
+                s.lp_shards[rank] if mode == "lp" else None)), s.b_reduce + s.b_adam, touched_update(s)))
         else:
-            launches.append(("unshard", (lambda t, s=s, buf=buf: unshard(s, buf)), s.b_unshard))
-            if args.mode == "fused":
-                launches.append(("reduce_adam", (lambda t, s=s: reduce_adam(s, t)), s.b_reduce + s.b_adam))
-            else:
-                launches.append(("reduce_scatter", (lambda t, s=s: F.fsdp_reduce_scatter_local(
-                    s.lay, s.grad_tab, rank, pre, post, s.gshard)), s.b_reduce))
-                launches.append(("adam", (lambda t, s=s: F.fsdp_shard_adam_step(
-                    s.lay, s.shards[rank], s.gshard, s.m, s.v, t, *hp)), s.b_adam))
+            launches.append(("reduce_kernel", (lambda t, s=s: F.fsdp_reduce_scatter_local(
+                s.lay, s.grad_tab, rank, pre, post, s.gshard)), s.b_reduce, s.b_reduce))
+            launches.append(("adam_kernel", (lambda t, s=s: F.fsdp_shard_adam_step(
+                s.lay, s.shards[rank], s.gshard, s.m, s.v, t, *hp)), s.b_adam, s.b_adam))
+    return launches
+
+
+def run_config(cfg, args, F, torch, workloads, headline, traffic_table):
+    """Set up one workload, time `steps` steps after `warmup`, then the kernels
+    one kind at a time.  Returns (record for the JSON line, cpu_baseline or None)."""
+    wl = workloads.config(cfg)
+    if args.grad_dtype:
+        import dataclasses
+        wl = dataclasses.replace(wl, grad_dtype=args.grad_dtype)
+    units = list(wl.units)
+    if args.max_units:
+        units = units[:args.max_units]
+    if args.unit_scale > 1:
+        units = [workloads.Unit(f"{u.name}x{args.unit_scale}", tuple(u.shapes) * args.unit_scale) for u in units]
+    pre, post = F.fsdp_default_divide_factors(wl.world_size)
+    hp = (wl.lr, wl.beta1, wl.beta2, wl.eps)
+    rank = 0
+    batched = args.mode in ("batch", "batch-lp")
+    lp_handoff = args.mode in ("lp", "batch-lp")
+    # Configuration 0 is one 99 MB unit: run over and over it would stay in the
+    # 256 MB Infinity Cache, so its steps rotate over copies of the unit (cold),
+    # and the figure with one copy (warm) is reported beside it.
+    replicas = args.replicas or (COLD_REPLICAS if cfg == 0 else 1)
+
+    t0 = time.time()
+    reps_states, reps_launches = [], []
+    depth = args.depth
+    for _ in range(replicas):
+        states = make_states(F, wl, units, args, torch, workloads)
+        if lp_handoff:
+            for s in states:
+                s.make_lp_shards(F, torch)
+        if depth <= 0:
+            small = sorted(s.b_unshard for s in states)[len(states) // 2] <= (128 << 20)
+            depth = 6 if small else 1
+        # The unsharded flat parameter is transient (Sec. 3.2.1: peak memory is the largest unit);
+        # as many buffers rotate as unshards can be in flight.
+        nflat = 2 * depth if batched else 2
+        flats = [torch.empty(max(s.P for s in states), dtype=torch.bfloat16, device="cuda") for _ in range(nflat)]
+        reps_states.append(states)
+        reps_launches.append(build_launches(F, states, flats, args, depth, rank, pre, post, hp))
+    states, launches = reps_states[0], reps_launches[0]
+    torch.cuda.synchronize()
+    log(f"[bench] {wl.name}: {len(states)} units, W={wl.world_size}, grads {wl.grad_dtype}, mode {args.mode}, "
+        f"{len(launches)} launches per step, setup {time.time() - t0:.1f}s, HBM in use "
+        f"{torch.cuda.memory_allocated() / 2**30:.2f} GiB")
+
+    # ---- parity of the first step against the oracle, and the oracle's own timing (headline only)
+    first = None
+    if headline and not args.no_cpu_baseline and not args.raf and args.mode == "batch":
+        first = FirstStepCheck(states, wl, rank, torch)
 
     main_s = torch.cuda.Stream()
 
-    def step(t):
-        """One pass over all units, in order, on main_s."""
-        for _kind, fn, _b in launches:
-            fn(t)
+    def step_of(ls):
+        def step(t):
+            for _kind, fn, _a, _b in ls:
+                fn(t)
+        return step
 
-    # A graph replay costs a fixed 6-10 us per step on this machine, which a step of
-    # a few long launches does not win back (measured: configuration 1, 6 launches,
-    # 259 us eagerly against 265 us replayed); steps of many launches replay a graph.
-    use_graph = args.graph or (not args.no_graph and len(launches) > GRAPH_MIN_LAUNCHES)
-    graph = None
+    steps_fns = [step_of(ls) for ls in reps_launches]
+    # A graph replay costs a fixed 6-10 us per step on this machine, which a step of a few
+    # long launches does not win back; steps of many launches replay a graph.
+    use_graph = (args.graph or (not args.no_graph and len(launches) > GRAPH_MIN_LAUNCHES)) and replicas == 1
+    rec = {}
     with torch.cuda.stream(main_s):
-        step(1)                      # first-touch / module load outside any capture
+        for fn in steps_fns:
+            fn(1)                      # first touch / module load outside any capture
         torch.cuda.synchronize()
+        if first is not None:
+            first.fetch_gpu(states, rank)
         if use_graph:
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph, stream=main_s):
-                step(2)
-        run = (lambda t: graph.replay()) if use_graph else step
+                steps_fns[0](2)
+            run = lambda t: graph.replay()                                   # noqa: E731
+        else:
+            run = lambda t: steps_fns[t % replicas](t)                       # noqa: E731
 
-        for i in range(args.warmup):
-            run(3 + i)
-        torch.cuda.synchronize()
-        tb = time.perf_counter()
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(args.steps):
-            run(3 + args.warmup + i)
-        e1.record()
-        torch.cuda.synchronize()
-        wall_ms = (time.perf_counter() - tb) * 1e3
-        dev_ms = e0.elapsed_time(e1)
-    ms_per_step = wall_ms / args.steps
+        def timed_pass(run_fn, per_step_events):
+            for i in range(args.warmup):
+                run_fn(3 + i)
+            torch.cuda.synchronize()
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)] if per_step_events else None
+            tb = time.perf_counter()
+            if evs:
+                evs[0].record()
+            for i in range(args.steps):
+                run_fn(3 + args.warmup + i)
+                if evs:
+                    evs[i + 1].record()
+            torch.cuda.synchronize()
+            wall_ms = (time.perf_counter() - tb) * 1e3
+            if not evs:
+                return wall_ms, None
+            return wall_ms, sorted(evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(args.steps))
+
+        # the figure: exactly `steps` steps between two synchronisations, wall clock
+        wall_ms, _ = timed_pass(run, False)
+        # the same again with a HIP event after every step: minimum and median step time
+        _, per_step = timed_pass(run, True)
+        ms_per_step = wall_ms / args.steps
+        warm = None
+        if replicas > 1:               # the same steps on one copy of the buffers: what the Infinity Cache adds
+            _w_ms, w_steps = timed_pass(lambda t: steps_fns[0](t), True)
+            warm = {"us_per_step_median": round(w_steps[len(w_steps) // 2], 2), "us_per_step_min": round(w_steps[0], 2)}
+
     step_bytes = sum(s.b_total for s in states) + (sum(s.b_unshard for s in states) if args.raf else 0)
-    # what the chosen mode's kernels really read and write per step (the metric's numerator above is fixed)
-    n_unshard = 2 if args.raf else 1
-    if args.mode == "separate":
-        touched = step_bytes
-    elif lp_handoff:
-        touched = sum(n_unshard * 4 * s.P + s.gbytes * s.P + 26 * s.S for s in states)
-    else:
-        touched = sum(n_unshard * 6 * s.P + s.gbytes * s.P + 24 * s.S for s in states)
+    touched = sum(b for _k, _f, _a, b in launches)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
-    log(f"[bench] {args.steps} steps: wall {wall_ms:.3f} ms, device {dev_ms:.3f} ms, "
-        f"{ms_per_step * 1e3:.1f} us/step, {value:.1f} GB/s effective ({100 * value / HBM_PEAK_GBPS:.1f}% of peak)")
+    log(f"[bench] {wl.name}: {args.steps} steps, {ms_per_step * 1e3:.1f} us/step (min {per_step[0]:.1f}, median "
+        f"{per_step[len(per_step) // 2]:.1f}), {value:.1f} GB/s effective ({100 * value / HBM_PEAK_GBPS:.1f}% of peak)")
+    rec.update({
+        "workload": wl.name, "units": len(states), "world_size": wl.world_size, "grad_dtype": wl.grad_dtype,
+        "unshard_dtype": "bf16", "rank": rank, "mode": args.mode, "reshard_after_forward": bool(args.raf),
+        "prefetch_depth": depth if batched else 0, "hip_graph": use_graph, "launches_per_step": len(launches),
+        "buffer_replicas": replicas, "alg_bytes_per_step": step_bytes, "touched_bytes_per_step": touched,
+        "us_per_step": round(ms_per_step * 1e3, 2), "us_per_step_min": round(per_step[0], 2),
+        "us_per_step_median": round(per_step[len(per_step) // 2], 2),
+        "GBps": round(value, 1), "GBps_touched": round(touched / (ms_per_step * 1e-3) / 1e9, 1),
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
+    })
+    if warm:
+        warm["GBps"] = round(step_bytes / (warm["us_per_step_median"] * 1e-6) / 1e9, 1)
+        rec["warm_one_replica"] = warm
+    if cfg == 0:
+        rec["note"] = ("99 MB in two dependent launches of ~8 us each: launch ramp and drain, not HBM, bound this "
+                       "configuration; it stays below the 70 % target")
 
-    # ---- per-kernel durations (HIP events on the launch stream) -> roofline of the dominant kernel
-    roofline = None
+    # ---- per-kernel durations (HIP events on the launch stream)
     per_kernel = {}
     if not args.no_kernel_timing:
-        # Each kernel kind alone, launched for unit 0, 1, ... in order and the
-        # whole sequence repeated, bracketed by one pair of HIP events on the
-        # launch stream: average duration per launch with the same cold-cache
-        # rotation over the units' buffers as in the timed steps.
-        reps = max(10, min(200, int(25.0 / max(ms_per_step, 1e-3))))      # about 25 ms of launches per kind
-        kinds = []
-        for kind, _fn, _b in launches:
-            if kind not in kinds:
-                kinds.append(kind)
+        # Each kernel alone: its launches of one step (of every replica), in order, the
+        # sequence repeated, between one pair of HIP events on the launch stream: average
+        # duration per launch with the same cold-cache rotation over the units' buffers
+        # as in the timed steps.
+        reps = max(5, min(200, int(25.0 / max(ms_per_step * replicas, 1e-3))))      # about 25 ms of launches per kernel
+        names = []
+        for k, _f, _a, _b in launches:
+            if k not in names:
+                names.append(k)
         with torch.cuda.stream(main_s):
-            for kind in kinds:
-                mine = [(fn, b) for k, fn, b in launches if k == kind]
-                for fn, _b in mine:
+            for name in names:
+                mine = [(fn, a, b) for ls in reps_launches for k, fn, a, b in ls if k == name]
+                for fn, _a, _b in mine:
                     fn(2)
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 torch.cuda.synchronize()
-                a.record()
+                e0.record()
                 for _ in range(reps):
-                    for fn, _b in mine:
+                    for fn, _a, _b in mine:
                         fn(2)
-                b.record()
+                e1.record()
                 torch.cuda.synchronize()
-                tot_us = a.elapsed_time(b) * 1e3 / reps
-                nb = sum(b_ for _fn, b_ in mine)
-                per_kernel[kind] = {"launches_per_step": len(mine), "avg_us": tot_us / len(mine),
-                                    "total_us_per_step": tot_us, "alg_bytes_per_launch": nb / len(mine),
-                                    "GBps": nb / (tot_us * 1e-6) / 1e9}
-        dom = max(per_kernel, key=lambda k: per_kernel[k]["total_us_per_step"])
-        traffic = None
-        try:
-            with open(args.traffic_json) as fh:
-                traffic = json.load(fh).get(f"{wl.name}:{args.mode}:{dom}")
-        except (OSError, ValueError):
-            pass
-        roofline = {"bound": "hbm", "kernel": dom, "achieved": round(per_kernel[dom]["GBps"], 1),
-                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(per_kernel[dom]["GBps"] / HBM_PEAK_GBPS, 4),
-                    "traffic": traffic, "avg_launch_us": round(per_kernel[dom]["avg_us"], 2),
-                    "alg_bytes_per_launch": per_kernel[dom]["alg_bytes_per_launch"]}
-        for k, v in per_kernel.items():
-            log(f"[bench] kernel {k}: avg {v['avg_us']:.2f} us/launch, {v['GBps']:.1f} GB/s algorithmic")
+                avg_us = e0.elapsed_time(e1) * 1e3 / reps / len(mine)
+                alg = sum(a for _f, a, _b in mine) / len(mine)
+                tch = sum(b for _f, _a, b in mine) / len(mine)
+                per_step_launches = len(mine) // replicas
+                per_kernel[name] = {
+                    "launches_per_step": per_step_launches, "avg_us": round(avg_us, 2),
+                    "total_us_per_step": round(avg_us * per_step_launches, 2), "alg_bytes_per_launch": round(alg),
+                    "touched_bytes_per_launch": round(tch), "GBps": round(alg / (avg_us * 1e-6) / 1e9, 1),
+                    "GBps_touched": round(tch / (avg_us * 1e-6) / 1e9, 1),
+                    "hbm_bytes_per_launch": traffic_table.get(f"{wl.name}:{name}") if args.mode == "batch" else None,
+                }
+                log(f"[bench] {wl.name} kernel {name}: {per_step_launches} per step, avg {avg_us:.2f} us, "
+                    f"{alg / avg_us / 1e3:.1f} GB/s algorithmic, {tch / avg_us / 1e3:.1f} GB/s touched")
+    rec["kernels"] = per_kernel
 
-    # ---- the CPU oracle on the host cores, same three operations, bounded sample
     cpu = None
-    if not args.no_cpu_baseline and not args.raf:      # the oracle leg times the one-unshard step only
-        cpu = cpu_baseline(states, wl, pre, post, rank, hp, torch)
+    if first is not None:
+        cpu = first.oracle_leg(wl, pre, post, rank, hp)
+    # free this workload's HBM before the next one
+    del reps_states, reps_launches, states, launches, steps_fns
+    gc.collect()
+    torch.cuda.empty_cache()
+    return rec, cpu
 
-    out = {
-        "metric": "effective HBM GB/s per FSDP unit pass: unshard + reduce-scatter + Adam",
-        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": wl.name, "units": len(states), "world_size": wl.world_size,
-                   "grad_dtype": wl.grad_dtype, "unshard_dtype": "bf16", "rank": rank, "mode": args.mode,
-                   "reshard_after_forward": bool(args.raf),
-                   "prefetch_depth": args.depth if batched else (1 if args.mode == "prefetch" else 0),
-                   "hip_graph": use_graph, "launches_per_step": len(launches), "alg_bytes_per_step": step_bytes,
-                   "touched_bytes_per_step": touched},
-        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": per_kernel,
-    }
-    print(json.dumps(out), flush=True)
+
+class FirstStepCheck:
+    """Headline workload only: keeps the inputs of the first step on the host,
+    fetches what the GPU made of them, then times the oracle on the same
+    inputs (the `cpu_baseline`) and compares its results with the GPU's."""
+
+    def __init__(self, states, wl, rank, torch):
+        import numpy as np
+        self.torch, self.np = torch, np
+        self.units = []
+        for s in states:
+            S = s.S
+            if wl.grad_dtype == "f32":
+                sl = [g[rank * S:(rank + 1) * S].cpu().numpy() for g in s.grads]
+            else:
+                sl = [g[rank * S:(rank + 1) * S].cpu().view(torch.int16).numpy().view(np.uint16) for g in s.grads]
+            self.units.append({"name": s.name, "shards": [x.cpu().numpy() for x in s.shards], "slices": sl,
+                               "m": s.m.cpu().numpy(), "v": s.v.cpu().numpy(), "bytes": s.b_total})
+        self.gpu = None
+
+    def fetch_gpu(self, states, rank):
+        """After step 1 from the initial state: unit 0's updated rank shard and optimizer state."""
+        s = states[0]
+        self.gpu = {"p": s.shards[rank].cpu().numpy(), "m": s.m.cpu().numpy(), "v": s.v.cpu().numpy()}
+
+    def _pass(self, oracle, u, rank, pre, post, hp):
+        t0 = time.perf_counter()
+        flat = oracle.unshard_bf16(u["shards"])
+        g = oracle.reduce_slices(u["slices"], pre, post)
+        res = oracle.adam_f32(u["shards"][rank], g, u["m"], u["v"], 1, *hp)
+        dt = time.perf_counter() - t0
+        del flat, g
+        return dt, res
+
+    def oracle_leg(self, wl, pre, post, rank, hp):
+        import oracle
+        np = self.np
+        budget_s = 12.0
+        done, spent, passes = 0, 0.0, 0
+        per_unit_ms = []
+        ref0 = None
+        while spent < budget_s:
+            for i, u in enumerate(self.units):
+                dt, res = self._pass(oracle, u, rank, pre, post, hp)
+                spent += dt
+                done += u["bytes"]
+                if passes == 0:
+                    per_unit_ms.append(round(dt * 1e3, 1))
+                    if i == 0:
+                        ref0 = res
+                del res
+            passes += 1
+        out = {"value": round(done / spent / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"{passes} passes over all {len(self.units)} units of {wl.name}, {spent:.2f} s of oracle time "
+                         f"(unshard + rank-0 reduce-scatter + Adam per unit)",
+               "oracle_ms_all_cores": per_unit_ms}
+        # the same on one host thread: units in order until about 8 s are spent (reported beside the all-cores figure)
+        threads = oracle.num_threads()
+        oracle.set_num_threads(1)
+        try:
+            done, spent, one_thread_ms = 0, 0.0, []
+            for u in self.units:
+                dt, _res = self._pass(oracle, u, rank, pre, post, hp)
+                spent += dt
+                done += u["bytes"]
+                one_thread_ms.append(round(dt * 1e3, 1))
+                if spent > 8.0:
+                    break
+            out["value_1_thread"] = round(done / spent / 1e9, 3)
+            out["oracle_ms_1_core"] = one_thread_ms
+        finally:
+            oracle.set_num_threads(threads)
+        # parity of the GPU's first step (unit 0, the timed rank) with the oracle's first pass
+        if self.gpu is not None and ref0 is not None:
+            same = all(np.array_equal(np.ascontiguousarray(a).view(np.uint32), np.ascontiguousarray(b).view(np.uint32))
+                       for a, b in zip((self.gpu["p"], self.gpu["m"], self.gpu["v"]), ref0))
+            out["parity_first_step"] = {"unit": self.units[0]["name"], "rank": rank,
+                                        "reduce_scatter+adam": "bit-identical to the oracle" if same else "MISMATCH"}
+            assert same, "bench: the first step's update differs from the oracle's"
+        return out
 
 
 def next_rows(args, wl, F, torch, workloads):
-    """Hybrid-sharding reduction (Sec. 3.2.2) and gradient accumulation
-    (Sec. 3.3.4) on the largest unit of the workload: one kernel each, timed
-    back to back over rotating buffer sets between one pair of HIP events."""
+    """Hybrid-sharding reduction (Sec. 3.2.2), gradient accumulation
+    (Sec. 3.3.4), fp16 / fp32 unshard and the unscaling reduce (Sec. 4.4) on the
+    largest unit of the workload: one kernel each, timed back to back over
+    rotating buffer sets between one pair of HIP events."""
     unit = max(wl.units, key=lambda u: sum(workloads.numel(s) for s in u.shapes))
     W = wl.world_size
-    gdt = torch.float32 if wl.grad_dtype == "f32" else torch.bfloat16
     gb = 4 if wl.grad_dtype == "f32" else 2
     lay = F.fsdp_layout_init(unit.shapes, W)
     S, P, N = lay.shard, lay.padded, lay.numel
@@ -445,72 +658,89 @@ def next_rows(args, wl, F, torch, workloads):
                                  "grad_dtype": wl.grad_dtype}, "rows": out}), flush=True)
 
 
-def probe_copy(n, torch, fbuild):
-    """N launches of a plain copy of 256 MiB (reads 256 MiB, writes 256 MiB)."""
-    import ctypes
-    lib = ctypes.CDLL(fbuild.build_probe(force=False))
-    lib.fsdp_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
-    nbytes = 256 << 20
-    bufs = [(torch.ones(nbytes // 4, dtype=torch.float32, device="cuda"),
-             torch.empty(nbytes // 4, dtype=torch.float32, device="cuda")) for _ in range(3)]
-    torch.cuda.synchronize()
-    st = torch.cuda.current_stream().cuda_stream
-    for i in range(n):
-        src, dst = bufs[i % len(bufs)]
-        rc = lib.fsdp_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, st)
-        assert rc == 0, rc
-    torch.cuda.synchronize()
-    assert bool((bufs[0][1] == 1).all())
-    print(json.dumps({"probe": "copy", "launches": n, "bytes_read_per_launch": nbytes,
-                      "bytes_written_per_launch": nbytes}), flush=True)
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build simulates all W ranks on ONE GPU; --gpus must be 1 "
+              "(no multi-GPU figure exists for it)", file=sys.stderr)
+        sys.exit(2)
 
+    import torch
+    import workloads
+    from paper_2304_11277_amd import build as fbuild
+    fbuild.build_lib(force=False)
+    import paper_2304_11277_amd as F
 
-def cpu_baseline(states, wl, pre, post, rank, hp, torch):
-    """Time the oracle (as it stands) on the host: unshard + rank share of the
-    reduce-scatter + Adam for a bounded sample of the workload's units."""
-    import numpy as np
-    import oracle
-    budget_s = 10.0
-    done_bytes = 0
-    spent = 0.0
-    n_units = 0
-    host = []
-    for s in states:
-        S = s.S
-        if wl.grad_dtype == "f32":
-            h_slices = [g[rank * S:(rank + 1) * S].cpu().numpy() for g in s.grads]
-        else:
-            h_slices = [g[rank * S:(rank + 1) * S].cpu().view(torch.int16).numpy().view(np.uint16) for g in s.grads]
-        host.append(([x.cpu().numpy() for x in s.shards], h_slices, s.m.cpu().numpy(), s.v.cpu().numpy(), s.b_total))
-    def one_pass():
-        nonlocal done_bytes, spent, n_units
-        for h_shards, h_slices, h_m, h_v, nbytes in host:
-            t0 = time.perf_counter()
-            oracle.unshard_bf16(h_shards)
-            g = oracle.reduce_slices(h_slices, pre, post)
-            oracle.adam_f32(h_shards[rank], g, h_m, h_v, 1, *hp)
-            spent += time.perf_counter() - t0
-            done_bytes += nbytes
-            n_units += 1
-
-    passes = 0
-    while spent < budget_s:
-        one_pass()
-        passes += 1
-    out = {"value": round(done_bytes / spent / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(),
-           "kind": "oracle", "sample": f"{passes} passes over all {len(states)} units of {wl.name} "
-                                       f"({n_units} unit passes), {spent:.2f} s of oracle time"}
-    # the same on one host thread, a shorter sample (reported beside the all-cores figure)
-    threads = oracle.num_threads()
-    oracle.set_num_threads(1)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.probe_copy:
+        probe_copy(args.probe_copy, torch)
+        return
+    if args.next_rows:
+        wl = workloads.config(1 if args.config is None else args.config)
+        if args.grad_dtype:
+            import dataclasses
+            wl = dataclasses.replace(wl, grad_dtype=args.grad_dtype)
+        next_rows(args, wl, F, torch, workloads)
+        return
     try:
-        done_bytes, spent, n_units = 0, 0.0, 0
-        while spent < 3.0:
-            one_pass()
-        out["value_1_thread"] = round(done_bytes / spent / 1e9, 3)
-    finally:
-        oracle.set_num_threads(threads)
-    return out
+        with open(args.traffic_json) as fh:
+            traffic_table = json.load(fh)
+    except (OSError, ValueError):
+        traffic_table = {}
+
+    cfgs = [args.config] if args.config is not None else list(range(workloads.NUM_CONFIGS))
+    head_cfg = args.config if args.config is not None else HEADLINE_CONFIG
+    records, cpu = [], None
+    for c in cfgs:
+        rec, cpu_c = run_config(c, args, F, torch, workloads, c == head_cfg, traffic_table)
+        records.append(rec)
+        cpu = cpu_c if c == head_cfg else cpu
+    ceilings = None if args.no_ceilings else measure_ceilings(torch)
+    if ceilings:
+        log(f"[bench] ceilings of this box: copy {ceilings['copy_GBps']} GB/s, read-only {ceilings['read_GBps']} GB/s, "
+            f"write-only {ceilings['write_GBps']} GB/s")
+
+    head = next(r for r in records if r["workload"] == workloads.config(head_cfg).name)
+    roofline = None
+    if head["kernels"]:
+        # the kernel with the largest total time per step of the headline workload, under the name rocprofv3 shows
+        dom = max(head["kernels"], key=lambda k: head["kernels"][k]["total_us_per_step"])
+        k = head["kernels"][dom]
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": k["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(k["GBps"] / HBM_PEAK_GBPS, 4), "traffic": k["hbm_bytes_per_launch"],
+                    "avg_launch_us": k["avg_us"], "alg_bytes_per_launch": k["alg_bytes_per_launch"],
+                    "launches_per_step": k["launches_per_step"],
+                    "frac_of_measured_copy": round(k["GBps_touched"] / ceilings["copy_GBps"], 4) if ceilings else None}
+    # per-unit record of the headline workload when it is a single unit (the batch grids of the
+    # multi-unit workloads mix units, so only their per-configuration figures exist)
+    units_table = None
+    if head["units"] == 1:
+        hbm = [k["hbm_bytes_per_launch"] for k in head["kernels"].values()]
+        units_table = [{
+            "unit": workloads.config(head_cfg).units[0].name, "bytes_algorithmic": head["alg_bytes_per_step"],
+            "gpu_ms": round(head["us_per_step"] / 1e3, 4), "gpu_GBps": head["GBps"], "pct_of_8TBps": head["pct_of_hbm_peak"],
+            "rocprof_bytes": sum(hbm) if hbm and all(h is not None for h in hbm) else None,
+            "oracle_ms_all_cores": cpu["oracle_ms_all_cores"][0] if cpu else None,
+            "oracle_ms_1_core": cpu["oracle_ms_1_core"][0] if cpu and cpu.get("oracle_ms_1_core") else None,
+            "host_cores": cpu["cores"] if cpu else None,
+            "parity": cpu.get("parity_first_step") if cpu else None,
+        }]
+    out = {
+        "metric": "effective HBM GB/s per FSDP unit pass: unshard + reduce-scatter + Adam",
+        "value": head["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(head["us_per_step"] / 1e3, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {k: head[k] for k in ("workload", "units", "world_size", "grad_dtype", "unshard_dtype", "rank", "mode",
+                                        "reshard_after_forward", "prefetch_depth", "hip_graph", "launches_per_step",
+                                        "buffer_replicas", "alg_bytes_per_step", "touched_bytes_per_step")},
+        "pct_of_hbm_peak": head["pct_of_hbm_peak"],
+        "ms_per_step_min": round(head["us_per_step_min"] / 1e3, 5),
+        "ms_per_step_median": round(head["us_per_step_median"] / 1e3, 5),
+        "roofline": roofline, "cpu_baseline": cpu, "measured_ceilings": ceilings, "units_table": units_table,
+        "kernels": head["kernels"], "configs": records,
+    }
+    print(json.dumps(out), flush=True)
 
 
 if __name__ == "__main__":

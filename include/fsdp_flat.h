@@ -23,7 +23,9 @@
  *    different roles must not overlap.
  *  - bf16 is the upper half of an IEEE binary32 pattern (uint16_t).
  *  - A layout is immutable after init; calls that share a layout may run
- *    concurrently from several host threads and on several streams.
+ *    concurrently from several host threads and on several streams.  The
+ *    library keeps no mutable state of its own besides the per-thread value
+ *    behind fsdp_last_hip_error().
  */
 #ifndef FSDP_FLAT_H
 #define FSDP_FLAT_H
@@ -71,6 +73,23 @@ typedef enum {
 int fsdp_layout_init(const int64_t* dims, const int32_t* ndims, int32_t num_params,
                      int32_t world_size, fsdp_layout_t** out);
 void fsdp_layout_destroy(fsdp_layout_t* layout);           /* NULL is a no-op */
+
+/* fsdp_layout_init with a tuning hint that is stored in the (immutable) layout:
+ * how the reduce-scatter kernels of Sec. 3 / eq. (1) walk the W rank buffers
+ * for this unit.  Both walks add in rank order and give the same bits.
+ *   FSDP_WALK_WIDE: a lane owns one 16-byte chunk (and loads one to four ranks
+ *                   at a time, by gradient dtype);
+ *   FSDP_WALK_DEEP: a lane owns four chunks and loads one rank at a time;
+ *   FSDP_WALK_AUTO (what fsdp_layout_init uses): deep from eight ranks on when
+ *                   the shard has at least 8.4 M fp32 or 16.8 M 16-bit
+ *                   elements, else wide.
+ * The hint applies to the stand-alone reduce kernels (fsdp_reduce_scatter_local,
+ * _adam_fused, _hybrid, _accumulate, _unscale, the two-launch form of
+ * _prefetch_unshard and a batch's lone large update); kernels that share a grid
+ * with an unshard always walk wide.  Any other value: FSDP_ERR_INVALID_ARG. */
+enum { FSDP_WALK_AUTO = 0, FSDP_WALK_WIDE = 1, FSDP_WALK_DEEP = 2 };
+int fsdp_layout_init_ex(const int64_t* dims, const int32_t* ndims, int32_t num_params,
+                        int32_t world_size, int32_t reduce_walk, fsdp_layout_t** out);
 
 /* Queries (host only).  Any out pointer may be NULL to skip that field. */
 int fsdp_layout_info(const fsdp_layout_t* layout, int64_t* numel /*N*/, int64_t* padded /*P*/,
@@ -283,21 +302,22 @@ int  fsdp_batch_add_reduce_scatter_adam(fsdp_batch_t* batch, const fsdp_layout_t
                                         float* exp_avg, float* exp_avg_sq, float lr, float beta1,
                                         float beta2, float eps, void* p_lp_out /* may be NULL */);
 int  fsdp_batch_launch(const fsdp_batch_t* batch, int64_t step, void* hip_stream);
-
-/* Tuning and test knob: how the stand-alone reduce-scatter kernels
- * (fsdp_reduce_scatter_local, _adam_fused, _hybrid, _accumulate, _unscale, and
- * the two-launch form of _prefetch_unshard) walk the W rank buffers of the
- * reduce-scatter of Sec. 3 / eq. (1).  Both walks add in rank order and give
- * the same bits.
- *   FSDP_WALK_WIDE: a lane owns one 16-byte chunk (and loads one to four ranks at a
- *                   time, by gradient dtype);
- *   FSDP_WALK_DEEP: a lane owns four chunks and loads one rank at a time;
- *   FSDP_WALK_AUTO (default): deep from eight ranks on when the shard has at
- *                   least 8.4 M fp32 or 16.8 M 16-bit elements, else wide.
- * Process-wide; takes effect for launches issued after the call returns.
- * Returns FSDP_ERR_INVALID_ARG for any other value. */
-enum { FSDP_WALK_AUTO = 0, FSDP_WALK_WIDE = 1, FSDP_WALK_DEEP = 2 };
-int fsdp_set_reduce_walk(int32_t walk);
+/* How the recorded batch is issued (host only; for profiling and reports): the
+ * number of kernel launches of one fsdp_batch_launch call and, for launch i,
+ * which kernel it is (fsdp_kernel_name gives its name as profilers show it,
+ * without template arguments), how many updates and unshards it carries and its
+ * grid size in workgroups.  Any out pointer may be NULL. */
+typedef enum {
+    FSDP_KERNEL_BATCH = 0,        /* batch_kernel: several operations in one grid */
+    FSDP_KERNEL_REDUCE = 1,       /* reduce_kernel: one reduce-scatter (+ Adam) */
+    FSDP_KERNEL_UNSHARD_LP = 2,   /* unshard_lp_kernel: cast + gather to bf16 / fp16 */
+    FSDP_KERNEL_UNSHARD_F32 = 3,  /* unshard_f32_kernel: fp32 gather */
+    FSDP_KERNEL_GATHER_LP = 4     /* gather_lp_kernel: gather of 16-bit shards */
+} fsdp_kernel_t;
+int  fsdp_batch_launch_count(const fsdp_batch_t* batch, int32_t* count);
+int  fsdp_batch_launch_info(const fsdp_batch_t* batch, int32_t i, int32_t* kernel, int32_t* n_updates,
+                            int32_t* n_unshards, int64_t* workgroups);
+const char* fsdp_kernel_name(int32_t kernel);     /* NULL for an unknown value */
 
 /* Last hipError_t seen by this thread inside the library (0 if none). */
 int fsdp_last_hip_error(void);

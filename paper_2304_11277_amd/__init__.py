@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     fsdp_found_inf_combine,
     fsdp_grad_scaler_update,
     fsdp_layout_init,
+    fsdp_layout_init_ex,
     fsdp_reduce_scatter_adam_fused,
     fsdp_reduce_scatter_adam_prefetch_unshard,
     fsdp_grad_accumulate,
@@ -28,7 +29,6 @@ from .binding import (  # noqa: F401
     fsdp_reduce_scatter_hybrid,
     fsdp_reduce_scatter_local,
     fsdp_reduce_scatter_unscale,
-    fsdp_set_reduce_walk,
     fsdp_shard_adam_step,
     fsdp_shard_adam_step_guarded,
     fsdp_unshard,

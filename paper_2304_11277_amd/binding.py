@@ -52,6 +52,7 @@ _pp = ctypes.POINTER(ctypes.c_void_p)
 
 _SIGNATURES = {
     "fsdp_layout_init": [ctypes.POINTER(_i64), ctypes.POINTER(_i32), _i32, _i32, ctypes.POINTER(_vp)],
+    "fsdp_layout_init_ex": [ctypes.POINTER(_i64), ctypes.POINTER(_i32), _i32, _i32, _i32, ctypes.POINTER(_vp)],
     "fsdp_layout_info": [_vp, ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.POINTER(_i64),
                          ctypes.POINTER(_i64), ctypes.POINTER(_i32), ctypes.POINTER(_i32)],
     "fsdp_layout_param": [_vp, _i32, ctypes.POINTER(_i64), ctypes.POINTER(_i64)],
@@ -81,7 +82,9 @@ _SIGNATURES = {
     "fsdp_batch_add_reduce_scatter_adam": [_vp, _vp, _pp, ctypes.c_int, _i32, _f32, _f32, _vp, _vp, _vp, _vp,
                                            _f32, _f32, _f32, _f32, _vp],
     "fsdp_batch_launch": [_vp, _i64, _vp],
-    "fsdp_set_reduce_walk": [_i32],
+    "fsdp_batch_launch_count": [_vp, ctypes.POINTER(_i32)],
+    "fsdp_batch_launch_info": [_vp, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(_i32),
+                               ctypes.POINTER(_i64)],
     "fsdp_last_hip_error": [],
 }
 
@@ -105,6 +108,8 @@ def lib() -> ctypes.CDLL:
         l.fsdp_batch_destroy.restype = None
         l.fsdp_status_string.argtypes = [ctypes.c_int]
         l.fsdp_status_string.restype = ctypes.c_char_p
+        l.fsdp_kernel_name.argtypes = [_i32]
+        l.fsdp_kernel_name.restype = ctypes.c_char_p
         _lib = l
     return _lib
 
@@ -116,11 +121,38 @@ def _check(fn: str, status: int) -> None:
 
 class PtrArray:
     """A host array of device addresses, marshalled once and reusable across
-    calls (keeps the tensors alive)."""
+    calls (keeps the tensors alive).  The tensors are checked here (device
+    tensors of one device and one dtype, contiguous) and their dtype and sizes
+    recorded, so that every call that takes the array can compare them with
+    what its layout needs before anything is launched.  `allow_empty` admits
+    zero-element entries (a null address, never dereferenced)."""
 
-    def __init__(self, tensors: Sequence[torch.Tensor], allow_empty: bool = False):
+    def __init__(self, tensors: Sequence[torch.Tensor], allow_empty: bool = False, _device_check: bool = True):
         self.tensors = list(tensors)
-        addrs = [(t.data_ptr() if t.numel() or not allow_empty else 0) for t in self.tensors]
+        self.dtype = None
+        self.device = None
+        self.numels: List[int] = []
+        # False only in CPU tests of the checks below; such an array is refused by every call
+        self.device_checked = bool(_device_check)
+        addrs = []
+        for i, t in enumerate(self.tensors):
+            if not isinstance(t, torch.Tensor):
+                raise TypeError(f"PtrArray[{i}]: expected a tensor, got {type(t).__name__}")
+            self.numels.append(t.numel())
+            if t.numel() == 0 and allow_empty:
+                addrs.append(0)
+                continue
+            if _device_check and not t.is_cuda:
+                raise TypeError(f"PtrArray[{i}]: expected a device tensor, got one on {t.device}")
+            if not t.is_contiguous():
+                raise ValueError(f"PtrArray[{i}]: must be contiguous")
+            if self.dtype is None:
+                self.dtype, self.device = t.dtype, t.device
+            elif t.dtype != self.dtype:
+                raise TypeError(f"PtrArray[{i}]: {t.dtype} in a table of {self.dtype}")
+            elif t.device != self.device:
+                raise ValueError(f"PtrArray[{i}]: on {t.device} in a table on {self.device}")
+            addrs.append(t.data_ptr())
         self.array = (ctypes.c_void_p * max(1, len(addrs)))(*addrs)
         self.n = len(addrs)
 
@@ -145,20 +177,26 @@ def _dev_tensor(t: torch.Tensor, dtype, min_numel: int, what: str) -> int:
     return t.data_ptr()
 
 
-def _ptr_table(ts, dtype, min_numel: int, n_expected: int, what: str, allow_empty=False) -> PtrArray:
-    if isinstance(ts, PtrArray):
-        if ts.n != n_expected:
-            raise ValueError(f"{what}: expected {n_expected} entries, got {ts.n}")
-        return ts
-    ts = list(ts)
-    if len(ts) != n_expected:
-        raise ValueError(f"{what}: expected {n_expected} entries, got {len(ts)}")
-    for i, t in enumerate(ts):
+def _ptr_table(ts, dtype, min_numel, n_expected: int, what: str, allow_empty=False) -> PtrArray:
+    """Checked pointer table: `ts` is a sequence of tensors or a PtrArray built
+    earlier; either way every entry must be a contiguous device tensor of
+    `dtype` with at least min_numel (one number, or one per entry) elements."""
+    tab = ts if isinstance(ts, PtrArray) else PtrArray(list(ts), allow_empty=allow_empty)
+    if tab.n != n_expected:
+        raise ValueError(f"{what}: expected {n_expected} entries, got {tab.n}")
+    if not tab.device_checked:
+        raise TypeError(f"{what}: built without the device check")
+    for i, have in enumerate(tab.numels):
         need = min_numel[i] if isinstance(min_numel, (list, tuple)) else min_numel
         if allow_empty and need == 0:
             continue
-        _dev_tensor(t, dtype, need, f"{what}[{i}]")
-    return PtrArray(ts, allow_empty=allow_empty)
+        if have < need:
+            raise ValueError(f"{what}[{i}]: needs at least {need} elements, has {have}")
+        if have == 0:
+            raise ValueError(f"{what}[{i}]: empty tensor where {need} elements are read or written")
+    if tab.dtype is not None and tab.dtype != dtype:
+        raise TypeError(f"{what}: expected {dtype}, got {tab.dtype}")
+    return tab
 
 
 class Layout:
@@ -200,14 +238,23 @@ class Layout:
             pass
 
 
-def fsdp_layout_init(shapes: Sequence[Sequence[int]], world_size: int) -> Layout:
+def fsdp_layout_init(shapes: Sequence[Sequence[int]], world_size: int, reduce_walk: Optional[int] = None) -> Layout:
+    """fsdp_layout_init, or fsdp_layout_init_ex when a rank-walk hint
+    (FSDP_WALK_AUTO / _WIDE / _DEEP) is given."""
     shapes = [tuple(int(d) for d in s) for s in shapes]
     flat = [d for s in shapes for d in s]
     dims = (_i64 * max(1, len(flat)))(*flat)
     ndims = (_i32 * max(1, len(shapes)))(*[len(s) for s in shapes])
     out = _vp()
-    _check("fsdp_layout_init", lib().fsdp_layout_init(dims, ndims, len(shapes), int(world_size), ctypes.byref(out)))
+    if reduce_walk is None:
+        _check("fsdp_layout_init", lib().fsdp_layout_init(dims, ndims, len(shapes), int(world_size), ctypes.byref(out)))
+    else:
+        _check("fsdp_layout_init_ex", lib().fsdp_layout_init_ex(dims, ndims, len(shapes), int(world_size),
+                                                                int(reduce_walk), ctypes.byref(out)))
     return Layout(out.value, shapes)
+
+
+fsdp_layout_init_ex = fsdp_layout_init
 
 
 def fsdp_default_divide_factors(world_size: int) -> Tuple[float, float]:
@@ -263,14 +310,11 @@ def fsdp_unshard(layout: Layout, shard_ptrs, flat_out: torch.Tensor, stream=None
 
 
 def _grad_table(layout: Layout, grad_ptrs, num_groups: int = 1) -> Tuple[PtrArray, int]:
-    if isinstance(grad_ptrs, PtrArray):
-        gdt = grad_ptrs.tensors[0].dtype
-    else:
-        grad_ptrs = list(grad_ptrs)
-        gdt = grad_ptrs[0].dtype
+    tab = grad_ptrs if isinstance(grad_ptrs, PtrArray) else PtrArray(list(grad_ptrs))
+    gdt = tab.dtype
     if gdt not in _DTYPES:
         raise TypeError(f"grad dtype {gdt} not supported")
-    tab = _ptr_table(grad_ptrs, gdt, layout.padded, layout.world_size * num_groups, "grad_ptrs")
+    tab = _ptr_table(tab, gdt, layout.padded, layout.world_size * num_groups, "grad_ptrs")
     return tab, _DTYPES[gdt]
 
 
@@ -422,11 +466,6 @@ def fsdp_grad_scaler_update(scale: torch.Tensor, growth_tracker: torch.Tensor, f
                                          int(growth_interval), _stream_handle(stream)))
 
 
-def fsdp_set_reduce_walk(walk: int) -> None:
-    """Process-wide choice of the reduce-scatter kernels' rank walk (FSDP_WALK_AUTO / _WIDE / _DEEP)."""
-    _check("fsdp_set_reduce_walk", lib().fsdp_set_reduce_walk(int(walk)))
-
-
 class Batch:
     """Owner of a fsdp_batch_t: independent operations issued in few launches.
     Keeps the tensors and layouts it was given alive."""
@@ -477,6 +516,19 @@ class Batch:
 
     def launch(self, step: int, stream=None) -> None:
         _check("fsdp_batch_launch", lib().fsdp_batch_launch(self._h, int(step), _stream_handle(stream)))
+
+    def launches(self) -> List[dict]:
+        """fsdp_batch_launch_count / _info: the kernel launches one launch() call issues."""
+        n = _i32()
+        _check("fsdp_batch_launch_count", lib().fsdp_batch_launch_count(self._h, ctypes.byref(n)))
+        out = []
+        for i in range(n.value):
+            k, nu, ns, wg = _i32(), _i32(), _i32(), _i64()
+            _check("fsdp_batch_launch_info", lib().fsdp_batch_launch_info(self._h, i, ctypes.byref(k), ctypes.byref(nu),
+                                                                         ctypes.byref(ns), ctypes.byref(wg)))
+            out.append({"kernel": lib().fsdp_kernel_name(k.value).decode(), "updates": nu.value, "unshards": ns.value,
+                        "workgroups": wg.value})
+        return out
 
     def close(self) -> None:
         if self._h is not None:

@@ -13,9 +13,6 @@ SOURCES = [os.path.join(CSRC, "fsdp_layout.cpp"), os.path.join(CSRC, "fsdp_kerne
 HEADERS = [os.path.join(ROOT, "include", "fsdp_flat.h")] + [
     os.path.join(CSRC, h) for h in ("fsdp_internal.h", "device_common.h", "unshard_kernels.h", "pack_kernel.h",
                                     "reduce_kernels.h", "batch_kernel.h", "elementwise_kernels.h")]
-# counter-calibration copy kernel: a library of its own, loaded by bench.py --probe-copy only
-PROBE_LIB = os.path.join(HERE, "libfsdp_probe.so")
-PROBE_SRC = os.path.join(CSRC, "copy_probe.hip")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -54,15 +51,5 @@ def build_lib(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
-def build_probe(force: bool = True) -> str:
-    if not force and os.path.exists(PROBE_LIB) and os.path.getmtime(PROBE_LIB) >= os.path.getmtime(PROBE_SRC):
-        return PROBE_LIB
-    tmp = PROBE_LIB + f".tmp{os.getpid()}"
-    subprocess.check_call([hipcc(), *HIPCC_FLAGS, "-x", "hip", PROBE_SRC, "-o", tmp])
-    os.replace(tmp, PROBE_LIB)
-    return PROBE_LIB
-
-
 if __name__ == "__main__":
     print(build_lib(force=True, verbose=True))
-    print(build_probe(force=True))

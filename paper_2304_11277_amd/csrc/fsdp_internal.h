@@ -15,6 +15,7 @@ struct fsdp_layout {
     int64_t S = 0;     // shard numel, ceil(N / W)
     int64_t P = 0;     // padded numel, S * W
     int64_t pad = 0;   // P - N
+    int32_t reduce_walk = FSDP_WALK_AUTO;   // tuning hint of fsdp_layout_init_ex
     std::vector<int64_t> off;    // [p + 1] exclusive prefix sum of numels
     std::vector<int64_t> numel;  // [p]
 };

@@ -21,7 +21,6 @@
 // denormals kept (gfx950's default).
 #include <hip/hip_runtime.h>
 
-#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <new>
@@ -111,7 +110,6 @@ void pad_rank_table(PtrTable& tab, int32_t n)
 // compute unit (256 of them on MI355X): 8.4 M fp32 or 16.8 M 16-bit elements.
 constexpr int32_t kDeepMinRanks = 8;
 constexpr int64_t kDeepMinBlocks = 8 * 256;
-std::atomic<int32_t> g_reduce_walk{FSDP_WALK_AUTO};      // fsdp_set_reduce_walk
 
 // does the library's own choice of rank walk fall on the deep one?
 inline bool deep_walk_pays(int gt, int32_t W, int64_t S)
@@ -120,13 +118,18 @@ inline bool deep_walk_pays(int gt, int32_t W, int64_t S)
     const int64_t deep_blocks = ceil_div(S / E + 1, kReduceBlock * WalkShape<kF32, true, true>::C);
     return W >= kDeepMinRanks && deep_blocks >= kDeepMinBlocks;
 }
+// would a stand-alone reduce kernel of this unit take the deep walk (the layout's hint, else the library's choice)?
+inline bool wants_deep(const fsdp_layout_t* L, int gt)
+{
+    return L->reduce_walk == FSDP_WALK_AUTO ? deep_walk_pays(gt, L->world_size, L->S) : L->reduce_walk == FSDP_WALK_DEEP;
+}
 
+// walk: the layout's hint (FSDP_WALK_*)
 template <int GT, int PRE, bool FUSED>
-void launch_reduce(const PtrTable& tab, const RsArgs& a, hipStream_t st)
+void launch_reduce(const PtrTable& tab, const RsArgs& a, int32_t walk, hipStream_t st)
 {
     constexpr int B = kReduceBlock;
     constexpr int E = WalkShape<GT, FUSED, false>::E;
-    const int32_t walk = g_reduce_walk.load(std::memory_order_relaxed);
     const bool deep = walk == FSDP_WALK_AUTO ? deep_walk_pays(GT, a.W, a.S) : walk == FSDP_WALK_DEEP;
     if (deep) {
         const int64_t deep_blocks = ceil_div(a.S / E + 1, B * WalkShape<GT, FUSED, true>::C);
@@ -140,11 +143,11 @@ void launch_reduce(const PtrTable& tab, const RsArgs& a, hipStream_t st)
 }
 
 template <int GT, bool FUSED>
-void launch_reduce_pre(int pre_mode, const PtrTable& tab, const RsArgs& a, hipStream_t st)
+void launch_reduce_pre(int pre_mode, const PtrTable& tab, const RsArgs& a, int32_t walk, hipStream_t st)
 {
-    if (pre_mode == kPreNone) launch_reduce<GT, kPreNone, FUSED>(tab, a, st);
-    else if (pre_mode == kPreMul) launch_reduce<GT, kPreMul, FUSED>(tab, a, st);
-    else launch_reduce<GT, kPreDiv, FUSED>(tab, a, st);
+    if (pre_mode == kPreNone) launch_reduce<GT, kPreNone, FUSED>(tab, a, walk, st);
+    else if (pre_mode == kPreMul) launch_reduce<GT, kPreMul, FUSED>(tab, a, walk, st);
+    else launch_reduce<GT, kPreDiv, FUSED>(tab, a, walk, st);
 }
 
 inline bool valid_dtype(fsdp_dtype_t d) { return d == FSDP_F32 || d == FSDP_BF16 || d == FSDP_F16; }
@@ -204,14 +207,14 @@ int reduce_driver(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dty
         a.adam = adam;
         const bool fuse_now = fused && a.last;
         if (grad_dtype == FSDP_BF16) {
-            if (fuse_now) launch_reduce_pre<kBF16, true>(pre_mode, tab, a, st);
-            else launch_reduce_pre<kBF16, false>(pre_mode, tab, a, st);
+            if (fuse_now) launch_reduce_pre<kBF16, true>(pre_mode, tab, a, L->reduce_walk, st);
+            else launch_reduce_pre<kBF16, false>(pre_mode, tab, a, L->reduce_walk, st);
         } else if (grad_dtype == FSDP_F16) {
-            if (fuse_now) launch_reduce_pre<kF16, true>(pre_mode, tab, a, st);
-            else launch_reduce_pre<kF16, false>(pre_mode, tab, a, st);
+            if (fuse_now) launch_reduce_pre<kF16, true>(pre_mode, tab, a, L->reduce_walk, st);
+            else launch_reduce_pre<kF16, false>(pre_mode, tab, a, L->reduce_walk, st);
         } else {
-            if (fuse_now) launch_reduce_pre<kF32, true>(pre_mode, tab, a, st);
-            else launch_reduce_pre<kF32, false>(pre_mode, tab, a, st);
+            if (fuse_now) launch_reduce_pre<kF32, true>(pre_mode, tab, a, L->reduce_walk, st);
+            else launch_reduce_pre<kF32, false>(pre_mode, tab, a, L->reduce_walk, st);
         }
         const int rc = launch_status();
         if (rc != FSDP_OK) return rc;
@@ -240,13 +243,6 @@ int check_reduce_args(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp
 }  // namespace
 
 extern "C" {
-
-int fsdp_set_reduce_walk(int32_t walk)
-{
-    if (walk != FSDP_WALK_AUTO && walk != FSDP_WALK_WIDE && walk != FSDP_WALK_DEEP) return FSDP_ERR_INVALID_ARG;
-    g_reduce_walk.store(walk, std::memory_order_relaxed);
-    return FSDP_OK;
-}
 
 int fsdp_flatten_shard(const fsdp_layout_t* L, const void* const* param_ptrs, float* const* shard_ptrs,
                        void* hip_stream)
@@ -463,7 +459,7 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* L, const void
     const int64_t reduce_bytes = dtype_size(grad_dtype) * L->P + 24 * L->S;
     const int64_t unshard_bytes = 6 * N->P;
     const bool small_half = (reduce_bytes < unshard_bytes ? reduce_bytes : unshard_bytes) <= kOneLaunchMaxBytes;
-    const bool pair_large = grad_dtype == FSDP_F32 && !deep_walk_pays(kF32, L->world_size, L->S);
+    const bool pair_large = grad_dtype == FSDP_F32 && !wants_deep(L, kF32);
     const bool one_launch = (small_half || pair_large) && L->world_size <= kMaxRanks &&
                             N->world_size <= kMaxRanks &&
                             next_out_dtype == FSDP_BF16 && grid_ok(n_reduce + n_unshard);
@@ -665,34 +661,10 @@ int fsdp_grad_scaler_update(float* scale, int32_t* growth_tracker, const float* 
 }  // extern "C"
 
 // ---- batches ----------------------------------------------------------------
-
-struct fsdp_batch {
-    struct ReduceRec {
-        const fsdp_layout_t* L;
-        std::vector<const void*> grads;      // already advanced to the rank's slice
-        fsdp_dtype_t dtype;
-        int32_t rank;
-        float pre, post;
-        float *out, *p, *m, *v;
-        uint16_t* p_lp;
-        float lr, beta1, beta2, eps;
-        std::vector<const void*> raw;        // the caller's table, for the single-operation fallback
-    };
-    struct UnshardRec {
-        const fsdp_layout_t* L;
-        std::vector<const void*> shards;
-        void* out;
-        fsdp_dtype_t dtype;
-        bool lp;                             // the shards are 16-bit already: plain gather (fsdp_unshard_lp)
-    };
-    struct Op {
-        bool is_reduce;
-        size_t index;
-    };
-    std::vector<ReduceRec> reduces;
-    std::vector<UnshardRec> unshards;
-    std::vector<Op> order;
-};
+// A batch is planned while it is recorded: every fsdp_batch_add_* call either
+// joins the last grid of the plan or opens a new step, and writes the member's
+// kernel arguments once.  fsdp_batch_launch walks the plan and only fills in
+// the Adam constants that depend on the step count.
 
 namespace {
 
@@ -701,7 +673,16 @@ struct ReduceKind {
     bool operator==(const ReduceKind& o) const { return gt == o.gt && pre_mode == o.pre_mode; }
 };
 
-int pre_mode_of(float pre) {
+struct AdamHyper {
+    float lr, beta1, beta2, eps;
+    bool operator==(const AdamHyper& o) const
+    {
+        return lr == o.lr && beta1 == o.beta1 && beta2 == o.beta2 && eps == o.eps;
+    }
+};
+
+int pre_mode_of(float pre)
+{
     float r;
     if (pre == 1.0f) return kPreNone;
     return is_pow2_float(pre, &r) ? kPreMul : kPreDiv;
@@ -726,6 +707,56 @@ void launch_batch_grid(const ReduceKind& k, const BatchArgs& b, uint32_t blocks,
 
 }  // namespace
 
+struct fsdp_batch {
+    // operations that cannot share a grid are kept as the caller gave them and
+    // issued through their own entry points
+    struct ReduceRec {
+        const fsdp_layout_t* L;
+        std::vector<const void*> raw;        // the caller's table
+        fsdp_dtype_t dtype;
+        int32_t rank;
+        float pre, post;
+        float *out, *p, *m, *v;
+        uint16_t* p_lp;
+        AdamHyper hyper;
+    };
+    struct UnshardRec {
+        const fsdp_layout_t* L;
+        std::vector<const void*> shards;
+        void* out;
+        fsdp_dtype_t dtype;
+        bool lp;                             // the shards are 16-bit already: plain gather (fsdp_unshard_lp)
+    };
+    // one grid: up to kBatchOps reduce members of one kernel kind and up to
+    // kBatchOps unshard members, their rank pointers in one pool
+    struct Grid {
+        BatchArgs args = {};                 // complete except for the members' Adam constants
+        ReduceKind kind = {kF32, kPreNone};
+        AdamHyper hyper[kBatchOps] = {};
+        int32_t walk0 = FSDP_WALK_AUTO;      // rank-walk hint of the first reduce member's layout
+        int32_t n_ptrs = 0;
+        int large_r = 0, large_u = 0;
+        bool pairable = true;                // may a large unshard join the grid's large update?
+        uint32_t r_blocks = 0, u_blocks = 0;
+    };
+    struct Step {
+        enum Kind { kGrid, kReduce, kUnshard } kind;
+        size_t index;                        // into grids, reduces or unshards
+    };
+    std::vector<ReduceRec> reduces;
+    std::vector<UnshardRec> unshards;
+    std::vector<Grid> grids;
+    std::vector<Step> steps;
+
+    Grid* open_grid() { return !steps.empty() && steps.back().kind == Step::kGrid ? &grids[steps.back().index] : nullptr; }
+    Grid* new_grid()
+    {
+        grids.emplace_back();
+        steps.push_back({Step::kGrid, grids.size() - 1});
+        return &grids.back();
+    }
+};
+
 extern "C" {
 
 int fsdp_batch_create(fsdp_batch_t** out)
@@ -742,7 +773,54 @@ int fsdp_batch_clear(fsdp_batch_t* b)
     if (!b) return FSDP_ERR_NULL_PTR;
     b->reduces.clear();
     b->unshards.clear();
-    b->order.clear();
+    b->grids.clear();
+    b->steps.clear();
+    return FSDP_OK;
+}
+
+static int batch_add_unshard_impl(fsdp_batch_t* b, const fsdp_layout_t* L, const void* const* shard_ptrs, void* flat_out,
+                                  fsdp_dtype_t out_dtype, bool lp)
+{
+    const int32_t W = L->world_size;
+    const int64_t bytes = (lp ? 4 : 6) * L->P;
+    const int64_t tiles = ceil_div(L->S / 8 + 1, kBlock);
+    // A grid takes up to kBatchOps 16-bit unshards of at most kMaxRanks ranks
+    // each while the pointer pool lasts; of the operations above
+    // kOneLaunchMaxBytes at most one of each kind, and both kinds together only
+    // with fp32 gradients (see the prefetch entry point).
+    const bool batchable = W <= kMaxRanks && (lp || out_dtype == FSDP_BF16) && grid_ok(tiles * W);
+    try {
+        if (!batchable) {
+            fsdp_batch::UnshardRec r;
+            r.L = L;
+            r.shards.assign(shard_ptrs, shard_ptrs + W);
+            r.out = flat_out;
+            r.dtype = out_dtype;
+            r.lp = lp;
+            b->unshards.push_back(std::move(r));
+            b->steps.push_back({fsdp_batch::Step::kUnshard, b->unshards.size() - 1});
+            return FSDP_OK;
+        }
+        const bool is_large = bytes > kOneLaunchMaxBytes;
+        fsdp_batch::Grid* g = b->open_grid();
+        if (!g || g->args.n_unshard == kBatchOps || g->n_ptrs + W > kBatchPtrs ||
+            !grid_ok(tiles * W + g->r_blocks + g->u_blocks) ||
+            (is_large && (g->large_u > 0 || (g->large_r > 0 && !g->pairable))))
+            g = b->new_grid();
+        g->large_u += is_large ? 1 : 0;
+        BatchUnshardOp& o = g->args.u[g->args.n_unshard];
+        o.ptr0 = g->n_ptrs;
+        for (int32_t w = 0; w < W; ++w) g->args.ptrs[g->n_ptrs++] = shard_ptrs[w];
+        o.S = L->S;
+        o.out = static_cast<uint16_t*>(flat_out);
+        o.tiles = static_cast<int32_t>(tiles);
+        o.lp = lp ? 1 : 0;
+        g->u_blocks += static_cast<uint32_t>(tiles * W);
+        g->args.u_end[g->args.n_unshard] = g->u_blocks;
+        ++g->args.n_unshard;
+    } catch (const std::bad_alloc&) {
+        return FSDP_ERR_OOM;
+    }
     return FSDP_OK;
 }
 
@@ -756,19 +834,7 @@ int fsdp_batch_add_unshard(fsdp_batch_t* b, const fsdp_layout_t* L, const float*
         if (misaligned(shard_ptrs[w], 4)) return FSDP_ERR_INVALID_ARG;
     }
     if (misaligned(flat_out, static_cast<uintptr_t>(dtype_size(out_dtype)))) return FSDP_ERR_INVALID_ARG;
-    try {
-        fsdp_batch::UnshardRec r;
-        r.L = L;
-        r.shards.assign(shard_ptrs, shard_ptrs + L->world_size);
-        r.out = flat_out;
-        r.dtype = out_dtype;
-        r.lp = false;
-        b->unshards.push_back(std::move(r));
-        b->order.push_back({false, b->unshards.size() - 1});
-    } catch (const std::bad_alloc&) {
-        return FSDP_ERR_OOM;
-    }
-    return FSDP_OK;
+    return batch_add_unshard_impl(b, L, reinterpret_cast<const void* const*>(shard_ptrs), flat_out, out_dtype, false);
 }
 
 int fsdp_batch_add_unshard_lp(fsdp_batch_t* b, const fsdp_layout_t* L, const void* const* lp_shard_ptrs, void* flat_out)
@@ -779,19 +845,8 @@ int fsdp_batch_add_unshard_lp(fsdp_batch_t* b, const fsdp_layout_t* L, const voi
         if (misaligned(lp_shard_ptrs[w], 2)) return FSDP_ERR_INVALID_ARG;
     }
     if (misaligned(flat_out, 2)) return FSDP_ERR_INVALID_ARG;
-    try {
-        fsdp_batch::UnshardRec r;
-        r.L = L;
-        r.shards.assign(lp_shard_ptrs, lp_shard_ptrs + L->world_size);
-        r.out = flat_out;
-        r.dtype = FSDP_BF16;        // not looked at: a gather moves either 16-bit kind
-        r.lp = true;
-        b->unshards.push_back(std::move(r));
-        b->order.push_back({false, b->unshards.size() - 1});
-    } catch (const std::bad_alloc&) {
-        return FSDP_ERR_OOM;
-    }
-    return FSDP_OK;
+    // the dtype is not looked at: a gather moves either 16-bit kind
+    return batch_add_unshard_impl(b, L, lp_shard_ptrs, flat_out, FSDP_BF16, true);
 }
 
 int fsdp_batch_add_reduce_scatter_adam(fsdp_batch_t* b, const fsdp_layout_t* L, const void* const* grad_ptrs,
@@ -809,26 +864,158 @@ int fsdp_batch_add_reduce_scatter_adam(fsdp_batch_t* b, const fsdp_layout_t* L, 
     if (misaligned(p_shard, 4) || misaligned(exp_avg, 4) || misaligned(exp_avg_sq, 4) ||
         (grad_shard_out && misaligned(grad_shard_out, 4)) || (p_lp_out && misaligned(p_lp_out, 2)))
         return FSDP_ERR_INVALID_ARG;
+
+    const int32_t W = L->world_size;
+    const int32_t W_padded = (W + kMaxWideRanks - 1) / kMaxWideRanks * kMaxWideRanks;   // whole wide batches
+    const int64_t bytes = dtype_size(grad_dtype) * L->P + 24 * L->S;
+    const int64_t E = grad_dtype == FSDP_F32 ? 4 : 8;
+    const int64_t nb = ceil_div(L->S / E + 1, kBlock);
+    const bool batchable = W <= kMaxRanks && grid_ok(nb);
+    const AdamHyper hyper = {lr, beta1, beta2, eps};
     try {
-        fsdp_batch::ReduceRec r;
-        r.L = L;
-        r.raw.assign(grad_ptrs, grad_ptrs + L->world_size);
+        if (!batchable) {
+            fsdp_batch::ReduceRec r;
+            r.L = L;
+            r.raw.assign(grad_ptrs, grad_ptrs + W);
+            r.dtype = grad_dtype;
+            r.rank = rank;
+            r.pre = pre_div;
+            r.post = post_div;
+            r.out = grad_shard_out;
+            r.p = p_shard; r.m = exp_avg; r.v = exp_avg_sq;
+            r.p_lp = static_cast<uint16_t*>(p_lp_out);
+            r.hyper = hyper;
+            b->reduces.push_back(std::move(r));
+            b->steps.push_back({fsdp_batch::Step::kReduce, b->reduces.size() - 1});
+            return FSDP_OK;
+        }
+        const ReduceKind k = {static_cast<int>(grad_dtype), pre_mode_of(pre_div)};
+        const bool is_large = bytes > kOneLaunchMaxBytes;
+        const bool pairs_with_large_unshard = k.gt == kF32 && !wants_deep(L, kF32);
+        fsdp_batch::Grid* g = b->open_grid();
+        if (!g || g->args.n_reduce == kBatchOps || (g->args.n_reduce > 0 && !(k == g->kind)) ||
+            g->n_ptrs + W_padded > kBatchPtrs || !grid_ok(nb + g->r_blocks + g->u_blocks) ||
+            (is_large && (g->large_r > 0 || (g->large_u > 0 && !pairs_with_large_unshard))))
+            g = b->new_grid();
+        if (g->args.n_reduce == 0) {
+            g->kind = k;
+            g->walk0 = L->reduce_walk;
+        }
+        g->large_r += is_large ? 1 : 0;
+        if (is_large) g->pairable = pairs_with_large_unshard;
+        BatchReduceOp& o = g->args.r[g->args.n_reduce];
+        o.ptr0 = g->n_ptrs;
         const int64_t off = static_cast<int64_t>(rank) * L->S * dtype_size(grad_dtype);
-        for (int32_t w = 0; w < L->world_size; ++w) r.grads.push_back(static_cast<const char*>(grad_ptrs[w]) + off);
-        r.dtype = grad_dtype;
-        r.rank = rank;
-        r.pre = pre_div;
-        r.post = post_div;
-        r.out = grad_shard_out;
-        r.p = p_shard; r.m = exp_avg; r.v = exp_avg_sq;
-        r.p_lp = static_cast<uint16_t*>(p_lp_out);
-        r.lr = lr; r.beta1 = beta1; r.beta2 = beta2; r.eps = eps;
-        b->reduces.push_back(std::move(r));
-        b->order.push_back({true, b->reduces.size() - 1});
+        for (int32_t w = 0; w < W_padded; ++w)     // the padding repeats the last rank's pointer; its adds are skipped
+            g->args.ptrs[g->n_ptrs++] = static_cast<const char*>(grad_ptrs[w < W ? w : W - 1]) + off;
+        RsArgs& a = o.a;
+        a = RsArgs{};
+        float recip;
+        a.pre_c = pre_div;
+        if (k.pre_mode == kPreMul) { is_pow2_float(pre_div, &recip); a.pre_c = recip; }
+        a.post_c = post_div;
+        if (is_pow2_float(post_div, &recip)) { a.post_mul = 1; a.post_c = recip; }
+        a.W = W;
+        a.last = 1;
+        a.S = L->S;
+        a.out = grad_shard_out;
+        a.p = p_shard; a.m = exp_avg; a.v = exp_avg_sq; a.p_lp = static_cast<uint16_t*>(p_lp_out);
+        g->hyper[g->args.n_reduce] = hyper;
+        g->r_blocks += static_cast<uint32_t>(nb);
+        g->args.r_end[g->args.n_reduce] = g->r_blocks;
+        ++g->args.n_reduce;
     } catch (const std::bad_alloc&) {
         return FSDP_ERR_OOM;
     }
     return FSDP_OK;
+}
+
+namespace {
+// launches of one plan step: (kernel, updates, unshards, workgroups) of launch j of the step; returns the count
+int32_t step_launches(const fsdp_batch_t* b, const fsdp_batch::Step& s, int32_t j, int32_t* kernel, int32_t* n_upd,
+                      int32_t* n_uns, int64_t* wgs)
+{
+    if (s.kind == fsdp_batch::Step::kGrid) {
+        const fsdp_batch::Grid& g = b->grids[s.index];
+        const bool lone = g.args.n_reduce == 1 && g.args.n_unshard == 0 && g.large_r > 0;
+        *kernel = lone ? FSDP_KERNEL_REDUCE : FSDP_KERNEL_BATCH;
+        *n_upd = g.args.n_reduce;
+        *n_uns = g.args.n_unshard;
+        *wgs = static_cast<int64_t>(g.r_blocks) + g.u_blocks;
+        if (lone) {   // the stand-alone kernel sizes its own grid by the rank walk it takes
+            const RsArgs& a = g.args.r[0].a;
+            const int64_t E = g.kind.gt == kF32 ? 4 : 8;
+            const bool deep = g.walk0 == FSDP_WALK_AUTO ? deep_walk_pays(g.kind.gt, a.W, a.S) : g.walk0 == FSDP_WALK_DEEP;
+            *wgs = ceil_div(a.S / E + 1, deep ? kReduceBlock * 4 : kReduceBlock);
+        }
+        return 1;
+    }
+    if (s.kind == fsdp_batch::Step::kReduce) {
+        const fsdp_batch::ReduceRec& r = b->reduces[s.index];
+        *kernel = FSDP_KERNEL_REDUCE;
+        *n_upd = 1;
+        *n_uns = 0;
+        const int64_t E = r.dtype == FSDP_F32 ? 4 : 8;
+        const bool deep = wants_deep(r.L, static_cast<int>(r.dtype));
+        *wgs = ceil_div(r.L->S / E + 1, deep ? kReduceBlock * 4 : kReduceBlock);
+        return static_cast<int32_t>(ceil_div(r.L->world_size, kMaxRanks));
+    }
+    const fsdp_batch::UnshardRec& u = b->unshards[s.index];
+    const int32_t n = static_cast<int32_t>(ceil_div(u.L->world_size, kMaxRanks));
+    const int32_t nw = j + 1 < n ? kMaxRanks : u.L->world_size - j * kMaxRanks;
+    *kernel = u.lp ? FSDP_KERNEL_GATHER_LP : (u.dtype == FSDP_F32 ? FSDP_KERNEL_UNSHARD_F32 : FSDP_KERNEL_UNSHARD_LP);
+    *n_upd = 0;
+    *n_uns = 1;
+    *wgs = ceil_div(u.L->S / (!u.lp && u.dtype == FSDP_F32 ? 4 : 8) + 1, kBlock) * nw;
+    return n;
+}
+}  // namespace
+
+int fsdp_batch_launch_count(const fsdp_batch_t* b, int32_t* count)
+{
+    if (!b || !count) return FSDP_ERR_NULL_PTR;
+    int64_t n = 0;
+    int32_t k, nu, ns;
+    int64_t w;
+    for (const fsdp_batch::Step& s : b->steps) n += step_launches(b, s, 0, &k, &nu, &ns, &w);
+    if (n > 0x7FFFFFFF) return FSDP_ERR_OVERFLOW;
+    *count = static_cast<int32_t>(n);
+    return FSDP_OK;
+}
+
+int fsdp_batch_launch_info(const fsdp_batch_t* b, int32_t i, int32_t* kernel, int32_t* n_updates, int32_t* n_unshards,
+                           int64_t* workgroups)
+{
+    if (!b) return FSDP_ERR_NULL_PTR;
+    if (i < 0) return FSDP_ERR_RANK_RANGE;
+    int64_t first = 0;
+    for (const fsdp_batch::Step& s : b->steps) {
+        int32_t k, nu, ns;
+        int64_t w;
+        const int32_t n = step_launches(b, s, 0, &k, &nu, &ns, &w);
+        if (i < first + n) {
+            step_launches(b, s, static_cast<int32_t>(i - first), &k, &nu, &ns, &w);
+            if (kernel) *kernel = k;
+            if (n_updates) *n_updates = nu;
+            if (n_unshards) *n_unshards = ns;
+            if (workgroups) *workgroups = w;
+            return FSDP_OK;
+        }
+        first += n;
+    }
+    return FSDP_ERR_RANK_RANGE;
+}
+
+const char* fsdp_kernel_name(int32_t kernel)
+{
+    switch (kernel) {
+        case FSDP_KERNEL_BATCH: return "batch_kernel";
+        case FSDP_KERNEL_REDUCE: return "reduce_kernel";
+        case FSDP_KERNEL_UNSHARD_LP: return "unshard_lp_kernel";
+        case FSDP_KERNEL_UNSHARD_F32: return "unshard_f32_kernel";
+        case FSDP_KERNEL_GATHER_LP: return "gather_lp_kernel";
+        default: return nullptr;
+    }
 }
 
 int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
@@ -836,124 +1023,53 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
     if (!b) return FSDP_ERR_NULL_PTR;
     if (step < 1) return FSDP_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-
-    // Greedy grouping in insertion order.  A grid takes up to kBatchOps reduce
-    // operations of one kernel kind and up to kBatchOps bf16 unshards, each with
-    // at most kBatchRanks ranks.  Of the operations above kOneLaunchMaxBytes it
-    // takes at most one of each kind, and both kinds together only with fp32
-    // gradients (see the prefetch entry point).  Anything else is issued
-    // through its own entry point.
-    BatchArgs g = {};
-    ReduceKind kind = {kF32, kPreNone};
-    bool have_kind = false;
-    int large_r = 0, large_u = 0;
-    bool pairable = true;          // may a large unshard join the grid's large update?
-    uint32_t r_blocks = 0, u_blocks = 0;
-
-    auto flush = [&]() -> int {
-        if (g.n_reduce == 0 && g.n_unshard == 0) return FSDP_OK;
-        int rc = FSDP_OK;
-        // a grid without reduce operations never enters the reduce code, so any instantiation serves
-        if (g.n_reduce == 0) kind = ReduceKind{kF32, kPreNone};
-        if (g.n_reduce == 1 && g.n_unshard == 0 && large_r > 0) {
-            // the lone update of a unit too large to share a grid goes through the stand-alone kernel,
-            // which may choose the deep rank walk
-            PtrTable tab = {};
-            for (int32_t w = 0; w < kBatchRanks; ++w) tab.p[w] = g.r[0].grads[w];
-            if (kind.gt == kBF16) launch_reduce_pre<kBF16, true>(kind.pre_mode, tab, g.r[0].a, st);
-            else if (kind.gt == kF16) launch_reduce_pre<kF16, true>(kind.pre_mode, tab, g.r[0].a, st);
-            else launch_reduce_pre<kF32, true>(kind.pre_mode, tab, g.r[0].a, st);
-        } else {
-            launch_batch_grid(kind, g, r_blocks + u_blocks, st);
+    // the step-dependent Adam constants, computed once per distinct set of hyper-parameters
+    AdamHyper last_hyper = {};
+    AdamConsts last_consts = {};
+    bool have_consts = false;
+    auto consts_for = [&](const AdamHyper& h) -> const AdamConsts& {
+        if (!have_consts || !(h == last_hyper)) {
+            last_consts = make_adam_consts(step, h.lr, h.beta1, h.beta2, h.eps);
+            last_hyper = h;
+            have_consts = true;
         }
-        rc = launch_status();
-        g = BatchArgs{};
-        have_kind = false;
-        large_r = large_u = 0;
-        pairable = true;
-        r_blocks = u_blocks = 0;
-        return rc;
+        return last_consts;
     };
 
-    for (const fsdp_batch::Op& op : b->order) {
-        if (op.is_reduce) {
-            const fsdp_batch::ReduceRec& r = b->reduces[op.index];
-            const int32_t W = r.L->world_size;
-            const int64_t bytes = dtype_size(r.dtype) * r.L->P + 24 * r.L->S;
-            const int64_t E = r.dtype == FSDP_F32 ? 4 : 8;
-            const int64_t nb = ceil_div(r.L->S / E + 1, kBlock);
-            const bool batchable = W <= kBatchRanks && grid_ok(nb + r_blocks + u_blocks);
-            if (!batchable) {
-                int rc = flush();
-                if (rc != FSDP_OK) return rc;
-                rc = fsdp_reduce_scatter_adam_fused(r.L, r.raw.data(), r.dtype, r.rank, r.pre, r.post, r.out, r.p, r.m, r.v,
-                                                    step, r.lr, r.beta1, r.beta2, r.eps, r.p_lp, hip_stream);
-                if (rc != FSDP_OK) return rc;
-                continue;
-            }
-            const ReduceKind k = {static_cast<int>(r.dtype), pre_mode_of(r.pre)};
-            const bool is_large = bytes > kOneLaunchMaxBytes;
-            if (g.n_reduce == kBatchOps || (have_kind && !(k == kind)) ||
-                (is_large && (large_r > 0 || (large_u > 0 && !(k.gt == kF32 && !deep_walk_pays(kF32, W, r.L->S)))))) {
-                const int rc = flush();
-                if (rc != FSDP_OK) return rc;
-            }
-            kind = k;
-            have_kind = true;
-            large_r += is_large ? 1 : 0;
-            if (is_large) pairable = k.gt == kF32 && !deep_walk_pays(kF32, W, r.L->S);
-            BatchReduceOp& o = g.r[g.n_reduce];
-            for (int32_t w = 0; w < kBatchRanks; ++w) o.grads[w] = r.grads[w < W ? w : W - 1];   // padded for whole groups
-            RsArgs& a = o.a;
-            a = RsArgs{};
-            float recip;
-            a.pre_c = r.pre;
-            if (k.pre_mode == kPreMul) { is_pow2_float(r.pre, &recip); a.pre_c = recip; }
-            a.post_c = r.post;
-            if (is_pow2_float(r.post, &recip)) { a.post_mul = 1; a.post_c = recip; }
-            a.W = W;
-            a.last = 1;
-            a.S = r.L->S;
-            a.out = r.out;
-            a.p = r.p; a.m = r.m; a.v = r.v; a.p_lp = r.p_lp;
-            a.adam = make_adam_consts(step, r.lr, r.beta1, r.beta2, r.eps);
-            r_blocks += static_cast<uint32_t>(nb);
-            g.r_end[g.n_reduce] = r_blocks;
-            ++g.n_reduce;
+    for (const fsdp_batch::Step& s : b->steps) {
+        int rc = FSDP_OK;
+        if (s.kind == fsdp_batch::Step::kReduce) {
+            const fsdp_batch::ReduceRec& r = b->reduces[s.index];
+            rc = fsdp_reduce_scatter_adam_fused(r.L, r.raw.data(), r.dtype, r.rank, r.pre, r.post, r.out, r.p, r.m, r.v,
+                                                step, r.hyper.lr, r.hyper.beta1, r.hyper.beta2, r.hyper.eps, r.p_lp,
+                                                hip_stream);
+        } else if (s.kind == fsdp_batch::Step::kUnshard) {
+            const fsdp_batch::UnshardRec& u = b->unshards[s.index];
+            rc = u.lp ? fsdp_unshard_lp(u.L, u.shards.data(), u.out, hip_stream)
+                      : fsdp_unshard(u.L, reinterpret_cast<const float* const*>(u.shards.data()), u.out, u.dtype,
+                                     hip_stream);
         } else {
-            const fsdp_batch::UnshardRec& u = b->unshards[op.index];
-            const int32_t W = u.L->world_size;
-            const int64_t bytes = (u.lp ? 4 : 6) * u.L->P;
-            const int64_t tiles = ceil_div(u.L->S / 8 + 1, kBlock);
-            const bool batchable = W <= kBatchRanks && (u.lp || u.dtype == FSDP_BF16) &&
-                                   grid_ok(tiles * W + r_blocks + u_blocks);
-            if (!batchable) {
-                int rc = flush();
-                if (rc != FSDP_OK) return rc;
-                rc = u.lp ? fsdp_unshard_lp(u.L, u.shards.data(), u.out, hip_stream)
-                          : fsdp_unshard(u.L, reinterpret_cast<const float* const*>(u.shards.data()), u.out, u.dtype,
-                                         hip_stream);
-                if (rc != FSDP_OK) return rc;
-                continue;
+            const fsdp_batch::Grid& g = b->grids[s.index];
+            BatchArgs a = g.args;
+            for (int32_t i = 0; i < a.n_reduce; ++i) a.r[i].a.adam = consts_for(g.hyper[i]);
+            if (a.n_reduce == 1 && a.n_unshard == 0 && g.large_r > 0) {
+                // the lone update of a unit too large to share a grid goes through the stand-alone kernel,
+                // which may take the deep rank walk
+                PtrTable tab = {};
+                const int32_t W_padded = (a.r[0].a.W + kMaxWideRanks - 1) / kMaxWideRanks * kMaxWideRanks;
+                for (int32_t w = 0; w < W_padded; ++w) tab.p[w] = a.ptrs[a.r[0].ptr0 + w];
+                if (g.kind.gt == kBF16) launch_reduce_pre<kBF16, true>(g.kind.pre_mode, tab, a.r[0].a, g.walk0, st);
+                else if (g.kind.gt == kF16) launch_reduce_pre<kF16, true>(g.kind.pre_mode, tab, a.r[0].a, g.walk0, st);
+                else launch_reduce_pre<kF32, true>(g.kind.pre_mode, tab, a.r[0].a, g.walk0, st);
+            } else {
+                // a grid without reduce members never enters the reduce code, so any instantiation serves
+                launch_batch_grid(a.n_reduce > 0 ? g.kind : ReduceKind{kF32, kPreNone}, a, g.r_blocks + g.u_blocks, st);
             }
-            const bool is_large = bytes > kOneLaunchMaxBytes;
-            if (g.n_unshard == kBatchOps || (is_large && (large_u > 0 || (large_r > 0 && !pairable)))) {
-                const int rc = flush();
-                if (rc != FSDP_OK) return rc;
-            }
-            large_u += is_large ? 1 : 0;
-            BatchUnshardOp& o = g.u[g.n_unshard];
-            for (int32_t w = 0; w < kBatchRanks; ++w) o.shards[w] = u.shards[w < W ? w : W - 1];
-            o.S = u.L->S;
-            o.out = static_cast<uint16_t*>(u.out);
-            o.tiles = static_cast<int32_t>(tiles);
-            o.lp = u.lp ? 1 : 0;
-            u_blocks += static_cast<uint32_t>(tiles * W);
-            g.u_end[g.n_unshard] = u_blocks;
-            ++g.n_unshard;
+            rc = launch_status();
         }
+        if (rc != FSDP_OK) return rc;
     }
-    return flush();
+    return FSDP_OK;
 }
 
 }  // extern "C"

@@ -43,10 +43,18 @@ const char* fsdp_status_string(int status)
 int fsdp_layout_init(const int64_t* dims, const int32_t* ndims, int32_t num_params,
                      int32_t world_size, fsdp_layout_t** out)
 {
+    return fsdp_layout_init_ex(dims, ndims, num_params, world_size, FSDP_WALK_AUTO, out);
+}
+
+int fsdp_layout_init_ex(const int64_t* dims, const int32_t* ndims, int32_t num_params,
+                        int32_t world_size, int32_t reduce_walk, fsdp_layout_t** out)
+{
     if (!out) return FSDP_ERR_NULL_PTR;
     *out = nullptr;
     if (!ndims) return FSDP_ERR_NULL_PTR;
     if (num_params <= 0 || world_size <= 0) return FSDP_ERR_INVALID_ARG;
+    if (reduce_walk != FSDP_WALK_AUTO && reduce_walk != FSDP_WALK_WIDE && reduce_walk != FSDP_WALK_DEEP)
+        return FSDP_ERR_INVALID_ARG;
 
     fsdp_layout* L = new (std::nothrow) fsdp_layout;
     if (!L) return FSDP_ERR_OOM;
@@ -100,6 +108,7 @@ int fsdp_layout_init(const int64_t* dims, const int32_t* ndims, int32_t num_para
             L->S = S;
             L->P = P;
             L->pad = P - acc;
+            L->reduce_walk = reduce_walk;
         }
     }
     if (rc != FSDP_OK) {

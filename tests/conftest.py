@@ -34,14 +34,15 @@ def pytest_generate_tests(metafunc):
 
 
 @pytest.fixture(autouse=True)
-def _reduce_walk(request):
+def _reduce_walk(request, monkeypatch):
+    """The rank walk is a per-layout hint (fsdp_layout_init_ex): under the
+    "deep" parameter every layout the test creates through the package asks for
+    the deep walk.  Only this test's view of the binding is patched."""
     walk = getattr(request, "param", None)
-    if walk is None:
+    if walk != "deep":
         yield
         return
+    import functools
     import paper_2304_11277_amd as F
-    F.fsdp_set_reduce_walk(F.FSDP_WALK_DEEP if walk == "deep" else F.FSDP_WALK_AUTO)
-    try:
-        yield
-    finally:
-        F.fsdp_set_reduce_walk(F.FSDP_WALK_AUTO)
+    monkeypatch.setattr(F, "fsdp_layout_init", functools.partial(F.binding.fsdp_layout_init, reduce_walk=F.FSDP_WALK_DEEP))
+    yield

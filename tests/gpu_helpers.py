@@ -66,18 +66,4 @@ POISON32 = 0x7FC0DEAD - (1 << 32) if 0x7FC0DEAD >= (1 << 31) else 0x7FC0DEAD   #
 POISON16 = 0x7FCD
 
 
-def adam_close(got_p, got_m, got_v, ref_p, ref_m, ref_v, p_old, m_old=None, g=None, beta1=0.9, rel=1e-6):
-    """Tolerance of the Adam parity: relative 1e-6 on m and v, and on p
-    relative to max(|p_new|, |p_old|) because the update can cancel p to near
-    zero.  m is bounded relative to the larger of its two terms for the same
-    reason when the old state is not zero."""
-    ref_p, ref_m, ref_v = (np.asarray(x, dtype=np.float64) for x in (ref_p, ref_m, ref_v))
-    gp, gm, gv = (np.asarray(x, dtype=np.float64) for x in (got_p, got_m, got_v))
-    m_scale = np.maximum(np.abs(ref_m), np.abs(gm))
-    if m_old is not None and g is not None:
-        m_scale = np.maximum(m_scale, np.maximum(np.abs(np.asarray(m_old, np.float64)) * beta1,
-                                                 np.abs(np.asarray(g, np.float64)) * (1 - beta1)))
-    ok_m = np.abs(gm - ref_m) <= rel * m_scale
-    ok_v = np.abs(gv - ref_v) <= rel * np.maximum(np.abs(ref_v), np.abs(gv))
-    ok_p = np.abs(gp - ref_p) <= rel * np.maximum(np.maximum(np.abs(ref_p), np.abs(gp)), np.abs(np.asarray(p_old, np.float64)))
-    return bool(ok_m.all() and ok_v.all() and ok_p.all()), (int((~ok_p).sum()), int((~ok_m).sum()), int((~ok_v).sum()))
+from adam_parity import adam_close, assert_adam_bits, assert_adam_parity  # noqa: E402,F401  (re-exported for the GPU tests)

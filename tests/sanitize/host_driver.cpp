@@ -137,8 +137,14 @@ static void planner_checks()
     CHECK(fsdp_default_divide_factors(8, nullptr, &x) == FSDP_ERR_NULL_PTR);
     CHECK(std::strcmp(fsdp_status_string(FSDP_ERR_BAD_DTYPE), "bad dtype") == 0);
     CHECK(fsdp_status_string(-99) != nullptr);
-    CHECK(fsdp_set_reduce_walk(9) == FSDP_ERR_INVALID_ARG);
-    CHECK(fsdp_set_reduce_walk(FSDP_WALK_AUTO) == FSDP_OK);
+    {
+        const int64_t d1[1] = {5};
+        const int32_t n1[1] = {1};
+        fsdp_layout_t* lw = nullptr;
+        CHECK(fsdp_layout_init_ex(d1, n1, 1, 2, 9, &lw) == FSDP_ERR_INVALID_ARG && lw == nullptr);
+        CHECK(fsdp_layout_init_ex(d1, n1, 1, 2, FSDP_WALK_DEEP, &lw) == FSDP_OK && lw != nullptr);
+        fsdp_layout_destroy(lw);
+    }
 }
 
 // every compute entry point with arguments it must reject before any launch

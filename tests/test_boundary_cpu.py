@@ -310,11 +310,66 @@ def test_binding_rejects_host_tensors(L):
     assert L.lib().fsdp_status_string(-6) == b"rank or parameter index out of range"
 
 
-def test_set_reduce_walk_accepts_only_its_three_values(L):
-    raw = L.lib()
-    for bad in (-1, 3, 100):
-        assert raw.fsdp_set_reduce_walk(bad) == INVALID
-    for ok in (L.FSDP_WALK_WIDE, L.FSDP_WALK_DEEP, L.FSDP_WALK_AUTO):
-        assert raw.fsdp_set_reduce_walk(ok) == OK
-    with pytest.raises(L.FsdpError):
-        L.fsdp_set_reduce_walk(7)
+def test_layout_init_ex_takes_only_the_three_rank_walks(L):
+    for walk in (L.FSDP_WALK_AUTO, L.FSDP_WALK_WIDE, L.FSDP_WALK_DEEP):
+        lay = L.fsdp_layout_init([(4, 3), (3,)], 16, reduce_walk=walk)
+        assert (lay.numel, lay.shard, lay.padded, lay.pad) == (15, 1, 16, 1)
+    for bad in (-1, 3, 99):
+        with pytest.raises(L.FsdpError) as e:
+            L.fsdp_layout_init([(4, 3)], 2, reduce_walk=bad)
+        assert e.value.status == INVALID
+
+
+def test_library_exports_no_process_wide_setter(L):
+    """The library keeps no process-wide tuning state: the rank walk is an option of each layout."""
+    with pytest.raises(AttributeError):
+        L.lib().fsdp_set_reduce_walk
+
+
+def test_pointer_tables_are_checked_before_any_launch(L):
+    """A table built ahead of time is held to the same checks as a list of
+    tensors: device, one dtype, contiguity at construction; the count, the
+    dtype the call expects and the sizes its layout needs at every call."""
+    import torch
+    with pytest.raises(TypeError):
+        L.PtrArray([torch.zeros(8)])                                     # host memory
+    with pytest.raises(TypeError):
+        L.PtrArray([1.0, 2.0])
+    # the remaining checks, on host tensors that stand in for device ones (such a table can never be launched)
+    def tab(ts, **kw):
+        return L.PtrArray(ts, _device_check=False, **kw)
+    with pytest.raises(TypeError):
+        tab([torch.zeros(8), torch.zeros(8, dtype=torch.bfloat16)])      # mixed dtypes
+    with pytest.raises(ValueError):
+        tab([torch.zeros(4, 4).t()])                                     # not contiguous
+    lay = L.fsdp_layout_init([(4, 3), (3,)], 4)                          # N 15, S 4, P 16
+    flat = torch.zeros(16, dtype=torch.bfloat16)
+    good = tab([torch.zeros(4) for _ in range(4)])
+    assert good.dtype == torch.float32 and good.numels == [4, 4, 4, 4] and not good.device_checked
+    from paper_2304_11277_amd import binding
+    with pytest.raises(TypeError, match="device check"):
+        binding._ptr_table(good, torch.float32, lay.shard, 4, "shard_ptrs")
+    good.device_checked = True                                           # look at the checks behind that one
+    assert binding._ptr_table(good, torch.float32, lay.shard, 4, "shard_ptrs") is good
+    with pytest.raises(ValueError, match="expected 4 entries"):
+        binding._ptr_table(tab([torch.zeros(4)] * 3), torch.float32, lay.shard, 4, "shard_ptrs")
+    short = tab([torch.zeros(4), torch.zeros(3), torch.zeros(4), torch.zeros(4)])
+    short.device_checked = True
+    with pytest.raises(ValueError, match=r"shard_ptrs\[1\]: needs at least 4"):
+        binding._ptr_table(short, torch.float32, lay.shard, 4, "shard_ptrs")
+    wrong = tab([torch.zeros(4, dtype=torch.float16)] * 4)
+    wrong.device_checked = True
+    with pytest.raises(TypeError, match="expected torch.float32"):
+        binding._ptr_table(wrong, torch.float32, lay.shard, 4, "shard_ptrs")
+    # gradient tables: the dtype comes from the table, the size must cover the padded flat buffer
+    g_short = tab([torch.zeros(15)] * 4)
+    g_short.device_checked = True
+    with pytest.raises(ValueError, match="needs at least 16"):
+        binding._grad_table(lay, g_short)
+    g_int = tab([torch.zeros(16, dtype=torch.int32)] * 4)
+    g_int.device_checked = True
+    with pytest.raises(TypeError, match="not supported"):
+        binding._grad_table(lay, g_int)
+    # through a public entry point: the unchecked table is refused before the library is called
+    with pytest.raises(TypeError):
+        L.fsdp_unshard(lay, good.__class__([torch.zeros(4) for _ in range(4)], _device_check=False), flat)

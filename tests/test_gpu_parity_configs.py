@@ -14,7 +14,7 @@ import torch
 
 import oracle
 import workloads
-from gpu_helpers import adam_close, first_diff, load_product, np_bits, np_f32, same_bits
+from gpu_helpers import assert_adam_parity, first_diff, load_product, np_bits, np_f32, same_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -22,6 +22,14 @@ BENCH_RANK = 0      # the rank bench.py times
 BENCH_DEPTH = 6     # bench.py's default --depth
 
 CASES = [(c, u) for c in range(workloads.NUM_CONFIGS) for u in workloads.config(c).distinct_units]
+
+
+def _other_walk(F, W, S, grad_dtype):
+    """The rank walk that FSDP_WALK_AUTO does not take for this unit (the
+    library's rule: deep from 8 ranks on when the shard fills 2048 deep
+    workgroups of 256 lanes x 4 chunks of 4 fp32 or 8 16-bit elements)."""
+    auto_deep = W >= 8 and S >= 8 * 256 * 256 * 4 * (4 if grad_dtype == "f32" else 8)
+    return F.FSDP_WALK_WIDE if auto_deep else F.FSDP_WALK_DEEP
 
 
 def _ranks(cfg, W):
@@ -114,36 +122,25 @@ def test_config_unit_matches_oracle(F, cfg, unit_index):
         F.fsdp_reduce_scatter_adam_fused(lay, grads, r, pre, post, None, p2, m2, v2, 1, *hp, None)
         torch.cuda.synchronize()
         z = np.zeros(S, np.float32)
-        rp, rm, rv = oracle.adam_f32(h_shards[r], ref_g, z, z, 1, *hp)
         gp, gm, gv = np_f32(p), np_f32(m), np_f32(v)
-        ok, bad = adam_close(gp, gm, gv, rp, rm, rv, h_shards[r])
-        assert ok, f"Adam rank {r} vs fp32 oracle: {bad}"
-        dp, dm, dv = oracle.adam_f64(h_shards[r], ref_g, z, z, 1, *hp)
-        ok, bad = adam_close(gp, gm, gv, dp, dm, dv, h_shards[r])
-        assert ok, f"Adam rank {r} vs fp64 oracle: {bad}"
-        exact = same_bits(gp.view(np.uint32), rp.view(np.uint32))
+        rp, rm, rv = assert_adam_parity(gp, gm, gv, h_shards[r], ref_g, z, z, 1, hp, f"Adam rank {r}")
         for a, b, n in ((p, p2, "p"), (m, m2, "m"), (v, v2, "v")):
             assert same_bits(np_bits(a), np_bits(b)), f"fused {n} differs from the two-call path at rank {r}"
         if lay.pad and r == W - 1:
             assert not np_bits(p)[S - lay.pad:].any()
         if r == BENCH_RANK:
             bench_ref = (rp.copy(), rm.copy(), rv.copy(), np_bits(p2).copy(), np_bits(m2).copy(), np_bits(v2).copy())
-            if gdt == torch.float32:
-                # the other rank walk of the fp32 kernels at full size: same bits
-                auto_deep = W >= 8 and S >= 8 * 256 * 256 * 4 * 4
-                F.fsdp_set_reduce_walk(F.FSDP_WALK_WIDE if auto_deep else F.FSDP_WALK_DEEP)
-                try:
-                    p3, m3, v3 = shards[r].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
-                    F.fsdp_reduce_scatter_adam_fused(lay, grads, r, pre, post, None, p3, m3, v3, 1, *hp, None)
-                    torch.cuda.synchronize()
-                finally:
-                    F.fsdp_set_reduce_walk(F.FSDP_WALK_AUTO)
-                for a, b, n in ((p3, p2, "p"), (m3, m2, "m"), (v3, v2, "v")):
-                    assert same_bits(np_bits(a), np_bits(b)), f"{n}: the two rank walks differ at rank {r}"
-                del p3, m3, v3
-        print(f"[step] rank {r}: reduce-scatter bit-exact, Adam within 1e-6 (bit-identical to fp32 oracle: {exact}), "
-              f"fused == two calls", flush=True)
-        del p, m, v, p2, m2, v2, rp, rm, rv, dp, dm, dv, gp, gm, gv, ref_g
+            # the rank walk the library does not choose at this size, forced through the layout: same bits
+            lay_other = F.fsdp_layout_init(unit.shapes, W, reduce_walk=_other_walk(F, W, S, wl.grad_dtype))
+            p3, m3, v3 = shards[r].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
+            F.fsdp_reduce_scatter_adam_fused(lay_other, grads, r, pre, post, None, p3, m3, v3, 1, *hp, None)
+            torch.cuda.synchronize()
+            for a, b, n in ((p3, p2, "p"), (m3, m2, "m"), (v3, v2, "v")):
+                assert same_bits(np_bits(a), np_bits(b)), f"{n}: the two rank walks differ at rank {r}"
+            del p3, m3, v3
+        print(f"[step] rank {r}: reduce-scatter bit-exact, Adam bit-identical to the fp32 oracle and within 1e-6 of "
+              f"the fp64 one, fused == two calls", flush=True)
+        del p, m, v, p2, m2, v2, rp, rm, rv, gp, gm, gv, ref_g
 
     # ---- the launch configuration bench.py times by default: one batch holding the fused
     # reduce-scatter + Adam of `depth` units and the unshards of `depth` units (here: copies of this unit)
@@ -164,18 +161,166 @@ def test_config_unit_matches_oracle(F, cfg, unit_index):
     batch.launch(1)
     torch.cuda.synchronize()
     for j, (pb, mb, vb) in enumerate(outs):
-        ok, bad = adam_close(np_f32(pb), np_f32(mb), np_f32(vb), rp, rm, rv, h_shards[BENCH_RANK])
-        assert ok, f"batch update {j} vs fp32 oracle: {bad}"
+        for a, b, n in ((pb, rp, "p"), (mb, rm, "m"), (vb, rv, "v")):
+            assert same_bits(np_bits(a), b.view(np.uint32)), f"batch update {j}: {n} differs from the fp32 oracle"
         for a, b, n in ((pb, p2b, "p"), (mb, m2b, "m"), (vb, v2b, "v")):
             assert same_bits(np_bits(a), b), f"batch update {j}: {n} differs from the fused call"
     for j, fb in enumerate(flats):
         got = np_bits(fb)
         assert same_bits(got, ref_flat), f"batch unshard {j}: " + first_diff(got, ref_flat)
-    print(f"[step] batch of {BENCH_DEPTH}+{BENCH_DEPTH} operations: updates within 1e-6 of the oracle and equal to "
+    print(f"[step] batch of {BENCH_DEPTH}+{BENCH_DEPTH} operations: updates bit-identical to the fp32 oracle and to "
           "the fused call, unshards bit-exact", flush=True)
     batch.close()
     del outs, flats, batch, ref_flat, bench_ref
     del grads, shards, base, h_shards
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def _poisoned(n, dtype):
+    t = torch.empty(n, dtype=dtype, device="cuda")
+    t.view(torch.int16 if dtype in (torch.bfloat16, torch.float16) else torch.int32).fill_(
+        0x7FCD if dtype in (torch.bfloat16, torch.float16) else 0x7FC00001)
+    return t
+
+
+@pytest.mark.parametrize("cfg,unit_index", CASES, ids=[f"cfg{c}-unit{u}" for c, u in CASES])
+def test_config_unit_variants_match_oracle(F, cfg, unit_index):
+    """The variants of the path that bench.py also times, at the unit's full
+    size: the other gradient dtype (under the rank walk the library chooses at
+    that size), the fp32 and fp16 unshard (Sec. 3.2.1, 4.4), the bf16 shard
+    hand-off as batch members (Sec. 4.4), and the hybrid (Sec. 3.2.2),
+    accumulate (Sec. 3.3.4) and unscale (Sec. 4.4) forms of the reduce-scatter."""
+    wl = workloads.config(cfg)
+    unit = wl.units[unit_index]
+    W = wl.world_size
+    hp = (wl.lr, wl.beta1, wl.beta2, wl.eps)
+    r = BENCH_RANK
+    print(f"\n[case] variants of {wl.name} unit {unit.name} W={W}", flush=True)
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S, P, N = lay.shard, lay.padded, lay.numel
+    pre, post = F.fsdp_default_divide_factors(W)
+    params = workloads.gen_params(unit, unit_index, device="cuda")
+    base = torch.empty(W * S, dtype=torch.float32, device="cuda")
+    shards = [base[w * S:(w + 1) * S] for w in range(W)]
+    F.fsdp_flatten_shard(lay, params, shards)
+    torch.cuda.synchronize()
+    del params
+    h_shards = [np_f32(s) for s in shards]          # flatten_shard itself is compared with the oracle in the test above
+
+    # ---- unshard to fp32 and to fp16
+    for dt, ref_fn in ((torch.float32, oracle.unshard_f32), (torch.float16, oracle.unshard_f16)):
+        flat = _poisoned(P, dt)
+        F.fsdp_unshard(lay, shards, flat)
+        torch.cuda.synchronize()
+        ref = ref_fn(h_shards)
+        got = np_bits(flat)
+        ref = ref.view(np.uint32) if ref.dtype == np.float32 else ref
+        assert same_bits(got, ref), f"unshard to {dt}: " + first_diff(got, ref)
+        del flat, got, ref
+    print("[step] unshard to fp32 and fp16 bit-exact", flush=True)
+
+    # ---- the other gradient dtype: fused reduce-scatter + Adam with both optional outputs, rank 0
+    other = "bf16" if wl.grad_dtype == "f32" else "f32"
+    odt = torch.bfloat16 if other == "bf16" else torch.float32
+    grads = []
+    for w in range(W):
+        g = torch.empty(P, dtype=odt, device="cuda")
+        workloads.gen_rank_grad(P, N, w, unit_index, other, device="cuda", outlier_frac=wl.outlier_frac,
+                                outlier_scale=wl.outlier_scale, out=g)
+        grads.append(g)
+    torch.cuda.synchronize()
+    h_slices = [(np_f32 if other == "f32" else np_bits)(g[r * S:(r + 1) * S]) for g in grads]
+    ref_g = oracle.reduce_slices(h_slices, pre, post)
+    p, m, v = shards[r].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
+    g_out, lp_out = _poisoned(S, torch.float32), _poisoned(S, torch.bfloat16)
+    F.fsdp_reduce_scatter_adam_fused(lay, grads, r, pre, post, g_out, p, m, v, 1, *hp, lp_out)
+    torch.cuda.synchronize()
+    got = np_bits(g_out)
+    assert same_bits(got, ref_g.view(np.uint32)), f"{other} gradients, reduce-scatter: " + first_diff(got, ref_g.view(np.uint32))
+    z = np.zeros(S, np.float32)
+    rp, _, _ = assert_adam_parity(np_f32(p), np_f32(m), np_f32(v), h_shards[r], ref_g, z, z, 1, hp, f"{other} gradients")
+    assert same_bits(np_bits(lp_out), oracle.cast_bf16(rp)), "bf16 copy of the updated shard"
+    lay_other = F.fsdp_layout_init(unit.shapes, W, reduce_walk=_other_walk(F, W, S, other))
+    p3, m3, v3 = shards[r].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
+    F.fsdp_reduce_scatter_adam_fused(lay_other, grads, r, pre, post, None, p3, m3, v3, 1, *hp, None)
+    torch.cuda.synchronize()
+    for a, b, n in ((p3, p, "p"), (m3, m, "m"), (v3, v, "v")):
+        assert same_bits(np_bits(a), np_bits(b)), f"{other} gradients, {n}: the two rank walks differ"
+    del p3, m3, v3
+    print(f"[step] {other} gradients: reduce-scatter bit-exact, Adam bit-identical (both rank walks), bf16 copy of the "
+          "new shard bit-exact", flush=True)
+
+    # ---- the same update and the gather of the ranks' bf16 shards as members of one batch (bench.py --mode batch-lp)
+    lp_base = _poisoned(W * S, torch.bfloat16)
+    lps = [lp_base[w * S:(w + 1) * S] for w in range(W)]
+    for w in range(W):
+        F.fsdp_cast_shard(lay, shards[w], lps[w])
+    torch.cuda.synchronize()
+    h_lps = [oracle.cast_bf16(h) for h in h_shards]
+    assert same_bits(np_bits(lp_base), np.concatenate(h_lps)), "cast_shard"
+    p2, m2, v2 = shards[r].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
+    flat = _poisoned(P, torch.bfloat16)
+    b_upd, b_gather = F.Batch(), F.Batch()
+    b_upd.add_reduce_scatter_adam(lay, grads, r, pre, post, None, p2, m2, v2, *hp, lps[r])
+    b_gather.add_unshard_lp(lay, lps, flat)
+    b_upd.launch(1)
+    b_gather.launch(1)
+    torch.cuda.synchronize()
+    for a, b, n in ((p2, p, "p"), (m2, m, "m"), (v2, v, "v")):
+        assert same_bits(np_bits(a), np_bits(b)), f"batch member: {n} differs from the fused call"
+    h_lps[r] = oracle.cast_bf16(rp)
+    ref = oracle.gather_lp(h_lps)
+    got = np_bits(flat)
+    assert same_bits(got, ref), "gather of the bf16 shards after the update: " + first_diff(got, ref)
+    b_upd.close()
+    b_gather.close()
+    del flat, lp_base, lps, h_lps, p2, m2, v2, got, ref
+    print("[step] bf16 shard hand-off as batch members bit-exact", flush=True)
+
+    # ---- accumulate (out += reduce-scatter) and unscale (+ the non-finite flag) on the same gradients
+    acc0 = torch.empty(S, device="cuda").normal_(0.0, 1e-3, generator=torch.Generator(device="cuda").manual_seed(7))
+    h_acc0 = np_f32(acc0).copy()
+    F.fsdp_reduce_scatter_accumulate(lay, grads, r, pre, post, acc0)
+    torch.cuda.synchronize()
+    ref = oracle.accumulate(h_acc0, ref_g)
+    assert same_bits(np_bits(acc0), ref.view(np.uint32)), "accumulate: " + first_diff(np_bits(acc0), ref.view(np.uint32))
+    flag = torch.zeros(1, device="cuda")
+    out = _poisoned(S, torch.float32)
+    inv_scale = 1.0 / 1024.0
+    F.fsdp_reduce_scatter_unscale(lay, grads, r, pre, post, inv_scale, out, flag)
+    torch.cuda.synchronize()
+    ref, ref_flag = oracle.unscale_check(ref_g, inv_scale)
+    assert same_bits(np_bits(out), ref.view(np.uint32)) and float(flag.item()) == ref_flag == 0.0, "unscale"
+    # one Inf in the last element of one rank's slice: the flag must come up
+    k = r * S + S - 1
+    saved = grads[W // 2][k].clone()
+    grads[W // 2][k] = float("inf")
+    F.fsdp_reduce_scatter_unscale(lay, grads, r, pre, post, inv_scale, out, flag)
+    torch.cuda.synchronize()
+    grads[W // 2][k] = saved
+    assert float(flag.item()) == 1.0, "a non-finite sum in the last element must set the flag"
+    del acc0, out, ref
+    print("[step] accumulate and unscale bit-exact", flush=True)
+
+    # ---- hybrid sharding: two sharded groups of F ranks (G * F <= 64); the second group holds the same
+    # buffers in reverse rank order, so the inner sums differ between the groups
+    Fs = W if 2 * W <= 64 else 32
+    lay_h = lay if Fs == W else F.fsdp_layout_init(unit.shapes, Fs)
+    Sh = lay_h.shard
+    hg = grads if Fs == W else [g[:lay_h.padded] for g in grads[:Fs]]
+    if lay_h.padded > P:                     # a different sharding factor may pad more than the buffers hold
+        hg = [torch.cat([g, torch.zeros(lay_h.padded - P, dtype=odt, device="cuda")]) for g in grads[:Fs]]
+    table = list(hg) + list(reversed(hg))
+    pre_h, post_h = F.fsdp_default_divide_factors(2 * Fs)
+    out = _poisoned(Sh, torch.float32)
+    F.fsdp_reduce_scatter_hybrid(lay_h, table, 2, r, pre_h, post_h, out)
+    torch.cuda.synchronize()
+    sl = [(np_f32 if other == "f32" else np_bits)(g[r * Sh:(r + 1) * Sh]) for g in table]
+    ref = oracle.reduce_slices_hybrid(sl, 2, Fs, pre_h, post_h)
+    assert same_bits(np_bits(out), ref.view(np.uint32)), "hybrid: " + first_diff(np_bits(out), ref.view(np.uint32))
+    print(f"[step] hybrid reduce-scatter (2 groups of {Fs}) bit-exact", flush=True)
+    del grads, hg, table, sl, out, ref, shards, base, h_shards, h_slices
     gc.collect()
     torch.cuda.empty_cache()
 
@@ -238,11 +383,9 @@ def test_unit_with_more_than_2_31_elements(F):
     assert same_bits(got, ref_g.view(np.uint32)), "reduce-scatter: " + first_diff(got, ref_g.view(np.uint32))
     del got, gs, grads
     z = np.zeros(S, np.float32)
-    rp, rm, rv = oracle.adam_f32(h_shards[r], ref_g, z, z, 1, *hp)
-    ok, bad = adam_close(np_f32(p2), np_f32(m2), np_f32(v2), rp, rm, rv, h_shards[r])
-    assert ok, f"fused update vs fp32 oracle: {bad}"
+    assert_adam_parity(np_f32(p2), np_f32(m2), np_f32(v2), h_shards[r], ref_g, z, z, 1, hp, "fused update")
     assert not np_bits(p2)[S - 1:].any(), "the pad element must stay zero"
-    print("[step] reduce-scatter bit-exact, fused update within 1e-6", flush=True)
+    print("[step] reduce-scatter bit-exact, fused update bit-identical to the fp32 oracle", flush=True)
     del p2, m2, v2, shards, base, h_shards
     gc.collect()
     torch.cuda.empty_cache()

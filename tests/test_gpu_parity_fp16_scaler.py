@@ -8,7 +8,7 @@ import torch
 
 import oracle
 import workloads
-from gpu_helpers import (POISON16, POISON32, adam_close, carve, first_diff, load_product, np_bits, np_f32, same_bits)
+from gpu_helpers import (POISON16, POISON32, assert_adam_bits, assert_adam_parity, carve, first_diff, load_product, np_bits, np_f32, same_bits)
 from test_gpu_parity_small import EDGE_BITS, alloc_shards, big_unit, make_params
 
 pytestmark = pytest.mark.gpu
@@ -141,8 +141,7 @@ def test_reduce_scatter_unscale_and_sharded_flag(F, bad):
     else:
         z = np.zeros(S, np.float32)
         rp, rm, rv = oracle.adam_f32(hp, np_f32(outs[0]), z, z, 1, 1e-4, 0.9, 0.999, 1e-8)
-        ok, badc = adam_close(np_f32(p), np_f32(m), np_f32(v), rp, rm, rv, hp)
-        assert ok, badc
+        assert_adam_bits(np_f32(p), np_f32(m), np_f32(v), rp, rm, rv)
 
 
 def test_grad_scaler_update_sequence(F):

@@ -130,9 +130,8 @@ def test_accumulate_then_fused_adam_equals_oracle_chain(F):
     F.fsdp_shard_adam_step(lay, p, acc, m, v, 2, 1e-4, 0.9, 0.999, 1e-8)
     torch.cuda.synchronize()
     rp, rm, rv = oracle.adam_f32(hp, h_acc, hm, hv, 2, 1e-4, 0.9, 0.999, 1e-8)
-    from gpu_helpers import adam_close
-    ok, bad = adam_close(np_f32(p), np_f32(m), np_f32(v), rp, rm, rv, hp, hm, h_acc)
-    assert ok, bad
+    from gpu_helpers import assert_adam_bits
+    assert_adam_bits(np_f32(p), np_f32(m), np_f32(v), rp, rm, rv)
 
 
 @pytest.mark.parametrize("W", [1, 3, 8, 12, 100])

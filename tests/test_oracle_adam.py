@@ -132,3 +132,80 @@ def test_checkpoint_resume():
     q2, n2, w2 = oracle.adam_f32(*[saved[0]], g2, saved[1], saved[2], 2, LR, B1, B2, EPS)
     for a, b in ((p2, q2), (m2, n2), (v2, w2)):
         assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+# ---- the tolerance the parity tests use, checked between the oracle's two evaluations ----------
+# (t, bit patterns of p, g, m, v): inputs, found by a CPU sweep over p ~ N(0, 0.02), g, m ~ N(0, 1e-3),
+# v ~ U(0, 1e-6), for which the binary32 and the binary64 evaluation of the same update differ by more
+# than 1e-6 * max(|p_new|, |p_old|): |p| is tiny and the two terms of the new m nearly cancel.
+_WITNESSES = [
+    (2, 0xB298DB91, 0x3AC1C4E4, 0xB92D34EF, 0x353A0473),
+    (2, 0xB35498CF, 0x3AB0688E, 0xB91B23CB, 0x3422755C),
+    (9, 0xB3E2742E, 0xBA8383A8, 0x38E6178F, 0x334241A0),
+    (300, 0x3382BC3B, 0x3A81C64B, 0xB8DEE612, 0x350BADD7),
+    (300, 0x34D5DD87, 0xBB1DF0C9, 0x399661A1, 0x35014421),
+]
+
+
+def test_tolerance_needs_the_update_scale_between_binary32_and_binary64():
+    from adam_parity import adam_close, adam_scales
+    hp = (1e-4, 0.9, 0.999, 1e-8)
+    for t, *bits in _WITNESSES:
+        p, g, m, v = (np.array([b], dtype=np.uint32).view(np.float32) for b in bits)
+        assert abs(float(p[0])) < 2e-6 and float(m[0]) * float(g[0]) < 0          # tiny p, cancelling m
+        rp, rm, rv = oracle.adam_f32(p, g, m, v, t, *hp)
+        dp, dm, dv = oracle.adam_f64(p, g, m, v, t, *hp)
+        ok, bad = adam_close(rp, rm, rv, dp, dm, dv, p, m, g)
+        assert not ok and bad[0] == 1 and bad[1:] == (0, 0), (t, bad)             # p alone is beyond the naive bound
+        rel = abs(float(rp[0]) - float(dp[0])) / max(abs(float(dp[0])), abs(float(p[0])))
+        assert 1e-6 < rel < 5e-6
+        _, U = adam_scales(p, g, m, dv, t, *hp)
+        ok, bad = adam_close(rp, rm, rv, dp, dm, dv, p, m, g, update_scale=U)
+        assert ok, (t, bad)
+
+
+@pytest.mark.parametrize("t", [1, 2, 9, 300])
+def test_binary32_oracle_within_tolerance_of_binary64(t):
+    """4 M elements of the GPU sweep's distribution, plus rows with p = 0 and
+    |p| <= lr, where the bound is a bound on the update itself."""
+    from adam_parity import adam_close, adam_scales
+    hp = (1e-4, 0.9, 0.999, 1e-8)
+    rng = np.random.default_rng(100 + t)
+    n = 1 << 22
+    p = rng.normal(0, 0.02, n).astype(np.float32)
+    p[: n // 8] = 0.0
+    p[n // 8: n // 4] = rng.uniform(-1e-4, 1e-4, n // 4 - n // 8).astype(np.float32)
+    g = rng.normal(0, 1e-3, n).astype(np.float32)
+    m = rng.normal(0, 1e-3, n).astype(np.float32) if t > 1 else np.zeros(n, np.float32)
+    v = rng.uniform(0, 1e-6, n).astype(np.float32) if t > 1 else np.zeros(n, np.float32)
+    rp, rm, rv = oracle.adam_f32(p, g, m, v, t, *hp)
+    dp, dm, dv = oracle.adam_f64(p, g, m, v, t, *hp)
+    _, U = adam_scales(p, g, m, dv, t, *hp)
+    ok, bad = adam_close(rp, rm, rv, dp, dm, dv, p, m, g, update_scale=U)
+    assert ok, bad
+    # on the p = 0 rows the bound is relative to the update: |dp32 - dp64| <= 2e-6 * s * M / d
+    z = slice(0, n // 8)
+    assert (np.abs(rp[z].astype(np.float64) - dp[z]) <= 1e-6 * np.maximum(U[z], np.abs(dp[z]))).all()
+
+
+def test_tolerance_with_update_scale_rejects_the_other_adam_readings():
+    """At p = 0 the bound discriminates the reading taken (eps outside the root,
+    bias corrections applied): each other reading moves the update by far more."""
+    from adam_parity import adam_close, adam_scales
+    lr, b1, b2, eps = 1e-4, 0.9, 0.999, 1e-8
+    rng = np.random.default_rng(9)
+    n = 4096
+    p = np.zeros(n, np.float32)
+    g = rng.normal(0, 1e-3, n).astype(np.float32)
+    m = rng.normal(0, 1e-3, n).astype(np.float32)
+    v = rng.uniform(0, 1e-6, n).astype(np.float32)
+    t = 3
+    dp, dm, dv = oracle.adam_f64(p, g, m, v, t, lr, b1, b2, eps)
+    _, U = adam_scales(p, g, m, dv, t, lr, b1, b2, eps)
+    bc1, bc2 = 1 - float(np.float32(b1)) ** t, 1 - float(np.float32(b2)) ** t
+    inside = -(lr / bc1) * dm / (np.sqrt(dv / bc2 + eps))                 # eps inside the root
+    no_bc2 = -(lr / bc1) * dm / (np.sqrt(dv) + eps)                       # second bias correction dropped
+    eps_scaled = -(lr / bc1) * dm / ((np.sqrt(dv) + eps) / np.sqrt(bc2))  # eps added before the correction
+    for other in (inside, no_bc2, eps_scaled):
+        ok, bad = adam_close(other, dm, dv, dp, dm, dv, p, m, g, update_scale=U)
+        assert not ok and bad[0] > n // 2

@@ -26,7 +26,14 @@ MUTANTS = [
     ("cast_half_up", "(u + 0x7FFFu + lsb) >> 16", "(u + 0x8000u) >> 16"),
     ("cast_half_down", "(u + 0x7FFFu + lsb) >> 16", "(u + 0x7FFFu) >> 16"),
     ("cast_nan_not_special", "(u & 0x007FFFFFu) != 0u)", "(u & 0x007FFFFFu) != 0u && 0)"),
-    ("gather_reversed", "flat_lp + (int64_t)w * S);", "flat_lp + (int64_t)(W - 1 - w) * S);"),
+    ("gather_reversed", "orc_cast_bf16(shards[w], S, flat_lp + (int64_t)w * S);",
+     "orc_cast_bf16(shards[w], S, flat_lp + (int64_t)(W - 1 - w) * S);"),
+    ("gather_f16_reversed", "orc_cast_f16(shards[w], S, flat_lp + (int64_t)w * S);",
+     "orc_cast_f16(shards[w], S, flat_lp + (int64_t)(W - 1 - w) * S);"),
+    ("gather_f16_ignores_rank", "orc_cast_f16(shards[w], S, flat_lp + (int64_t)w * S);",
+     "orc_cast_f16(shards[0], S, flat_lp + (int64_t)w * S);"),
+    ("gather_f16_casts_to_bf16", "orc_cast_f16(shards[w], S, flat_lp + (int64_t)w * S);",
+     "orc_cast_bf16(shards[w], S, flat_lp + (int64_t)w * S);"),
     ("reduce_acc_from_zero", "float acc = slices[0][k] / pre;", "float acc = 0.0f + slices[0][k] / pre;"),
     ("reduce_reverse_order",
      "float acc = slices[0][k] / pre;\n        for (int32_t w = 1; w < W; ++w) acc = acc + slices[w][k] / pre;",
@@ -102,6 +109,7 @@ def _pins():
         t_hyb.test_accumulation_with_and_without_communication_agree_on_integers,
         t_f16.test_f16_hand_vectors,
         t_f16.test_f16_nearest_neighbour_exact,
+        lambda: t_f16.test_unshard_f16_is_cast_of_the_concatenated_shards(3),
         t_f16.test_f16_upcast_all_patterns_against_numpy,
         t_f16.test_f16_reduce_is_upcast_then_fp32_reduce,
         t_f16.test_unscale_check_against_torch,
