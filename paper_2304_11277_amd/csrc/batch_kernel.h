@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kBlock) void batch_kernel(BatchArgs b)
         int32_t i = 0;
         uint32_t start = 0;
         while (bid >= b.r_end[i]) { start = b.r_end[i]; ++i; }     // uniform, at most kBatchOps - 1 steps
-        reduce_body<GT, PRE, true, false, kBlock>(b.ptrs + b.r[i].ptr0, b.r[i].a, bid - start);
+        reduce_body<GT, PRE, true, false, kBlock, true>(b.ptrs + b.r[i].ptr0, b.r[i].a, bid - start);
     } else {
         bid -= n_red_blocks;
         int32_t i = 0;

@@ -132,7 +132,7 @@ __device__ __forceinline__ void load_batch(const void* const* grads, int32_t w0,
 // Adds the first n ranks of a batch, in rank order, to every chunk.  Hybrid
 // sharding (Sec. 3.2.2): acc is the inner sum of the current sharded group;
 // after every `group` ranks it is folded into outer and restarted at -0.0f.
-template <int GT, int PRE, int G, int C, int E>
+template <int GT, int PRE, int G, int C, int E, bool HYBRID>
 __device__ __forceinline__ void add_batch(const u32x4 (&x)[G][C], int32_t n, float pre_c, int32_t group,
                                           int32_t& cnt, float (&acc)[C][E], float (&outer)[C][E])
 {
@@ -153,7 +153,7 @@ __device__ __forceinline__ void add_batch(const u32x4 (&x)[G][C], int32_t n, flo
 #pragma unroll
                 for (int e = 0; e < E; ++e) acc[j][e] = acc[j][e] + pre_scale<PRE>(t[e], pre_c);
             }
-            if (group > 0 && ++cnt == group) {   // uniform
+            if (HYBRID && group > 0 && ++cnt == group) {   // uniform
 #pragma unroll
                 for (int j = 0; j < C; ++j) {
 #pragma unroll
@@ -174,12 +174,18 @@ __device__ __forceinline__ void add_batch(const u32x4 (&x)[G][C], int32_t n, flo
 // partial sum instead.  A lane whose later chunks fall past the end computes
 // them on a copy of its first chunk (no predicated loads: predicates made the
 // compiler serialise them) and skips their stores.
-template <int GT, int PRE, bool FUSED, bool DEEP, int B>
+//
+// PLAIN instantiations serve the launches that use none of the variants (no
+// hybrid groups, no accumulation, no unscaling, no carried partial sum): the
+// second set of accumulators and the old gradient then take no registers.
+template <int GT, int PRE, bool FUSED, bool DEEP, int B, bool PLAIN>
 __device__ __forceinline__ void reduce_body(const void* const* grads, const RsArgs& a, uint32_t bid)
 {
     using Shape = WalkShape<GT, FUSED, DEEP>;
     constexpr int E = Shape::E, G = Shape::G, C = Shape::C;
     constexpr int Q = E / 4;
+    const int32_t group = PLAIN ? 0 : a.group;
+    const bool cont = !PLAIN && a.cont, accum = !PLAIN && a.accum, unscale = !PLAIN && a.unscale;
     // The chunk grid is aligned on the primary fp32 output.
     float* __restrict__ master = FUSED ? a.p : a.out;
     const int64_t S = a.S;
@@ -201,7 +207,7 @@ __device__ __forceinline__ void reduce_body(const void* const* grads, const RsAr
         int32_t cnt = 0;
 #pragma unroll
         for (int j = 0; j < C; ++j) {
-            if (a.cont) {
+            if (cont) {
 #pragma unroll
                 for (int q = 0; q < Q; ++q) {
                     const f32x4 t = *reinterpret_cast<const f32x4_a4*>(a.out + k[j] + 4 * q);
@@ -215,24 +221,26 @@ __device__ __forceinline__ void reduce_body(const void* const* grads, const RsAr
             for (int e = 0; e < E; ++e) outer[j][e] = -0.0f;
         }
 
-        // The optimizer state (and the accumulated gradient) of the lane's chunks,
-        // fetched ahead of the rank walk or after it (WalkShape::kStateFirst).
+        // The optimizer state (and the accumulated gradient) of the lane's chunks:
+        // fetched ahead of the rank walk (WalkShape::kStateFirst) or after it, and
+        // then one chunk ahead of the chunk being updated, so that the state of
+        // at most two chunks is held in registers at a time.
         f32x4 pv[C][Q], mv[C][Q], vv[C][Q], old[C][Q];
-        auto fetch_state = [&]() {
+        auto fetch_state = [&](int j) {
 #pragma unroll
-            for (int j = 0; j < C; ++j) {
-#pragma unroll
-                for (int q = 0; q < Q; ++q) {
-                    if constexpr (FUSED) {
-                        pv[j][q] = *reinterpret_cast<const f32x4*>(a.p + k[j] + 4 * q);
-                        mv[j][q] = *reinterpret_cast<const f32x4_a4*>(a.m + k[j] + 4 * q);
-                        vv[j][q] = *reinterpret_cast<const f32x4_a4*>(a.v + k[j] + 4 * q);
-                    }
-                    if (a.accum) old[j][q] = *reinterpret_cast<const f32x4_a4*>(a.out + k[j] + 4 * q);
+            for (int q = 0; q < Q; ++q) {
+                if constexpr (FUSED) {
+                    pv[j][q] = *reinterpret_cast<const f32x4*>(a.p + k[j] + 4 * q);
+                    mv[j][q] = *reinterpret_cast<const f32x4_a4*>(a.m + k[j] + 4 * q);
+                    vv[j][q] = *reinterpret_cast<const f32x4_a4*>(a.v + k[j] + 4 * q);
                 }
+                if (accum) old[j][q] = *reinterpret_cast<const f32x4_a4*>(a.out + k[j] + 4 * q);
             }
         };
-        if constexpr (Shape::kStateFirst) fetch_state();
+        if constexpr (Shape::kStateFirst) {
+#pragma unroll
+            for (int j = 0; j < C; ++j) fetch_state(j);
+        }
 
         u32x4 xa[G][C], xb[G][C];
         const int32_t nbatch = (W + G - 1) / G;
@@ -240,17 +248,20 @@ __device__ __forceinline__ void reduce_body(const void* const* grads, const RsAr
         for (int32_t b = 0; b < nbatch; b += 2) {
             const bool has_b = b + 1 < nbatch;
             if (has_b) load_batch<GT, G, C>(grads, (b + 1) * G, k, xb);
-            add_batch<GT, PRE, G, C, E>(xa, W - b * G, a.pre_c, a.group, cnt, acc, outer);
+            add_batch<GT, PRE, G, C, E, !PLAIN>(xa, W - b * G, a.pre_c, group, cnt, acc, outer);
             if (b + 2 < nbatch) load_batch<GT, G, C>(grads, (b + 2) * G, k, xa);
-            if (has_b) add_batch<GT, PRE, G, C, E>(xb, W - (b + 1) * G, a.pre_c, a.group, cnt, acc, outer);
+            if (has_b) add_batch<GT, PRE, G, C, E, !PLAIN>(xb, W - (b + 1) * G, a.pre_c, group, cnt, acc, outer);
         }
 
-        if constexpr (!Shape::kStateFirst) fetch_state();
+        if constexpr (!Shape::kStateFirst) fetch_state(0);
 #pragma unroll
         for (int j = 0; j < C; ++j) {
+            if constexpr (!Shape::kStateFirst) {
+                if (j + 1 < C) fetch_state(j + 1);
+            }
             if (!live[j]) continue;
             float (&r)[E] = acc[j];
-            if (a.group > 0) {   // every sharded group has been folded: the outer sum is the result
+            if (group > 0) {   // every sharded group has been folded: the outer sum is the result
 #pragma unroll
                 for (int e = 0; e < E; ++e) r[e] = outer[j][e];
             }
@@ -258,7 +269,7 @@ __device__ __forceinline__ void reduce_body(const void* const* grads, const RsAr
 #pragma unroll
                 for (int e = 0; e < E; ++e) r[e] = post_scale(r[e], a);
             }
-            if (a.accum) {
+            if (accum) {
 #pragma unroll
                 for (int q = 0; q < Q; ++q) {
                     r[4 * q] = old[j][q].x + r[4 * q];
@@ -267,7 +278,7 @@ __device__ __forceinline__ void reduce_body(const void* const* grads, const RsAr
                     r[4 * q + 3] = old[j][q].w + r[4 * q + 3];
                 }
             }
-            if (a.unscale) {   // sharded gradient scaler (Sec. 4.4): check, then unscale
+            if (unscale) {   // sharded gradient scaler (Sec. 4.4): check, then unscale
                 bool bad = false;
 #pragma unroll
                 for (int e = 0; e < E; ++e) {
@@ -314,22 +325,22 @@ __device__ __forceinline__ void reduce_body(const void* const* grads, const RsAr
         const int t = threadIdx.x;
         if (t < nrag) {
             const int64_t k = t < head ? t : tail0 + (t - head);
-            const float old_r = a.accum ? a.out[k] : 0.0f;
-            float r = a.cont ? a.out[k] : -0.0f;
+            const float old_r = accum ? a.out[k] : 0.0f;
+            float r = cont ? a.out[k] : -0.0f;
             float outer_r = -0.0f;
             int32_t cnt = 0;
             for (int32_t w = 0; w < W; ++w) {
                 r = r + pre_scale<PRE>(load_grad<GT>(grads[w], k), a.pre_c);
-                if (a.group > 0 && ++cnt == a.group) {
+                if (group > 0 && ++cnt == group) {
                     outer_r = outer_r + r;
                     r = -0.0f;
                     cnt = 0;
                 }
             }
-            if (a.group > 0) r = outer_r;
+            if (group > 0) r = outer_r;
             if (a.last) r = post_scale(r, a);
-            if (a.accum) r = old_r + r;
-            if (a.unscale) {
+            if (accum) r = old_r + r;
+            if (unscale) {
                 if ((f2u(r) & 0x7F800000u) == 0x7F800000u) *a.found_inf = 1.0f;
                 r = r * a.inv_scale;
             }
@@ -344,10 +355,10 @@ __device__ __forceinline__ void reduce_body(const void* const* grads, const RsAr
     }
 }
 
-template <int GT, int PRE, bool FUSED, bool DEEP, int B>
+template <int GT, int PRE, bool FUSED, bool DEEP, int B, bool PLAIN>
 __global__ __launch_bounds__(B) void reduce_kernel(PtrTable grads, RsArgs a)
 {
-    reduce_body<GT, PRE, FUSED, DEEP, B>(grads.p, a, blockIdx.x);
+    reduce_body<GT, PRE, FUSED, DEEP, B, PLAIN>(grads.p, a, blockIdx.x);
 }
 
 // Backward prefetching (Sec. 3.3.2) as one launch: the first n_reduce
@@ -362,7 +373,7 @@ __global__ __launch_bounds__(kBlock) void reduce_adam_unshard_kernel(PtrTable gr
                                                                       int32_t tiles_per_shard)
 {
     if (blockIdx.x < n_reduce)
-        reduce_body<GT, PRE, true, false, kBlock>(grads.p, a, blockIdx.x);
+        reduce_body<GT, PRE, true, false, kBlock, true>(grads.p, a, blockIdx.x);
     else
         unshard_lp_body<kBF16>(shards.p, S_next, out_base, tiles_per_shard, blockIdx.x - n_reduce);
 }
