@@ -69,6 +69,9 @@ def parse_args():
                          "Infinity Cache, 1 for the others (their steps already cycle through far more than that)")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
                     help="run only N launches of a plain 256 MiB copy kernel (calibrates rocprofv3 --pmc byte counters)")
+    ap.add_argument("--probe-mix", action="store_true",
+                    help="run only the read / write mix probe: 16 streams of a GPT-3-175B block's rank slice read in "
+                         "lock step as the reduce-scatter reads them, with and without the fp32 result written")
     ap.add_argument("--next-rows", action="store_true",
                     help="measure the kernels beyond the hot path (hybrid-sharding reduce, gradient accumulation, "
                          "fp16 / fp32 unshard, unscale) on the workload's largest unit and print their own JSON line")
@@ -112,6 +115,7 @@ def load_probe():
     lib.fsdp_probe_copy.argtypes = [vp, vp, i64, vp]
     lib.fsdp_probe_read.argtypes = [vp, i64, vp, vp]
     lib.fsdp_probe_write.argtypes = [vp, i64, ctypes.c_float, vp]
+    lib.fsdp_probe_streams.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, ctypes.c_int, vp, vp]
     return lib
 
 
@@ -173,6 +177,57 @@ def probe_copy(n, torch):
     assert bool((bufs[0][1] == 1).all())
     print(json.dumps({"probe": "copy", "launches": n, "bytes_read_per_launch": nbytes,
                       "bytes_written_per_launch": nbytes}), flush=True)
+
+
+def probe_mix(torch):
+    """What a small write stream costs next to many read streams.  The rank
+    walk of the reduce-scatter on the GPT-3-175B block reads the rank's slice
+    (113,256,192 bf16 = 226.5 MB) of 16 gradient buffers and writes 453 MB of
+    fp32 sums.  Timed here with almost no arithmetic: the reads alone, the
+    reads plus the write, and the write alone; a half-duplex memory would take
+    t(reads) + t(write) for the mix."""
+    lib = load_probe()
+    nbytes = 226512384
+    st = torch.cuda.current_stream().cuda_stream
+    out = torch.zeros(nbytes // 2, dtype=torch.float32, device="cuda")
+    res = {}
+    for n in (2, 4, 8, 16):
+        bufs = [torch.zeros(nbytes // 2, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+        tab = (ctypes.c_void_p * n)(*[b.data_ptr() for b in bufs])
+
+        def timed(fn):
+            for _ in range(2):
+                fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            a.record()
+            for _ in range(6):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) * 1e3 / 6
+
+        def run(store):
+            rc = lib.fsdp_probe_streams(tab, n, nbytes, store, out.data_ptr(), st)
+            assert rc == 0, rc
+
+        def write_only():
+            rc = lib.fsdp_probe_write(out.data_ptr(), 2 * nbytes, 0.0, st)
+            assert rc == 0, rc
+
+        t_r, t_rw, t_w = timed(lambda: run(0)), timed(lambda: run(1)), timed(write_only)
+        res[f"{n}_streams"] = {
+            "read_bytes": n * nbytes, "write_bytes": 2 * nbytes, "reads_only_us": round(t_r, 1),
+            "reads_and_write_us": round(t_rw, 1), "write_only_us": round(t_w, 1),
+            "reads_only_GBps": round(n * nbytes / t_r / 1e3, 1),
+            "mix_GBps": round((n + 2) * nbytes / t_rw / 1e3, 1),
+            "half_duplex_model_us": round(t_r + t_w, 1),
+        }
+        log(f"[probe-mix] {n} streams: reads alone {t_r:.1f} us ({n * nbytes / t_r / 1e3:.0f} GB/s), with the write "
+            f"{t_rw:.1f} us ({(n + 2) * nbytes / t_rw / 1e3:.0f} GB/s), write alone {t_w:.1f} us")
+        del bufs
+        torch.cuda.empty_cache()
+    print(json.dumps({"probe": "read/write mix", "stream_bytes": nbytes, "results": res}), flush=True)
 
 
 # ---------------------------------------------------------------------------
@@ -675,6 +730,9 @@ def main():
     torch.cuda.set_device(0)
     if args.probe_copy:
         probe_copy(args.probe_copy, torch)
+        return
+    if args.probe_mix:
+        probe_mix(torch)
         return
     if args.next_rows:
         wl = workloads.config(1 if args.config is None else args.config)

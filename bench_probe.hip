@@ -36,6 +36,37 @@ __global__ __launch_bounds__(256) void fsdp_probe_write_kernel(f32x4* __restrict
     if (i < nvec) __builtin_nontemporal_store(f32x4{value, value, value, value}, dst + i);
 }
 
+// The rank walk's memory traffic with almost no arithmetic around it: every
+// lane reads 16 bytes (8 bf16) at the same offset of each of n streams, in
+// order, sums them in fp32, and (store != 0) writes its 8 sums as fp32, or
+// (store == 0) nothing.  bench.py --probe-mix times both forms: what the same
+// reads cost with and without the small write stream next to them.
+struct ProbeStreams {
+    const uint32_t* p[64];
+};
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void fsdp_probe_streams_kernel(ProbeStreams t, int n, int64_t nvec, int store,
+                                                                 float* __restrict__ out)
+{
+    const int64_t c = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (c >= nvec) return;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = -0.0f;
+    for (int w = 0; w < n; ++w) {
+        const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t.p[w]) + c);
+        acc[0] += __uint_as_float(x.x << 16); acc[1] += __uint_as_float(x.x & 0xFFFF0000u);
+        acc[2] += __uint_as_float(x.y << 16); acc[3] += __uint_as_float(x.y & 0xFFFF0000u);
+        acc[4] += __uint_as_float(x.z << 16); acc[5] += __uint_as_float(x.z & 0xFFFF0000u);
+        acc[6] += __uint_as_float(x.w << 16); acc[7] += __uint_as_float(x.w & 0xFFFF0000u);
+    }
+    // without the store the sums are kept alive by a comparison that zero-filled streams never satisfy
+    if (store != 0 || acc[0] == 12345.678f) {
+        __builtin_nontemporal_store(f32x4{acc[0], acc[1], acc[2], acc[3]}, reinterpret_cast<f32x4*>(out + c * 8));
+        __builtin_nontemporal_store(f32x4{acc[4], acc[5], acc[6], acc[7]}, reinterpret_cast<f32x4*>(out + c * 8 + 4));
+    }
+}
+
 namespace {
 bool bad_buffer(const void* p, int64_t nbytes)
 {
@@ -70,5 +101,22 @@ extern "C" int fsdp_probe_write(void* dst, int64_t nbytes, float value, void* hi
     const int64_t nvec = nbytes / 16;
     hipLaunchKernelGGL(fsdp_probe_write_kernel, dim3(static_cast<uint32_t>((nvec + 255) / 256)), dim3(256), 0,
                        static_cast<hipStream_t>(hip_stream), static_cast<f32x4*>(dst), nvec, value);
+    return static_cast<int>(hipGetLastError());
+}
+
+// streams: host array of n (1..64) device buffers of nbytes each (16-byte aligned, nbytes a multiple of 16);
+// out: device, 2 * nbytes bytes (written only when store != 0).
+extern "C" int fsdp_probe_streams(const void* const* streams, int n, int64_t nbytes, int store, float* out,
+                                  void* hip_stream)
+{
+    if (!streams || n < 1 || n > 64 || bad_buffer(out, nbytes)) return static_cast<int>(hipErrorInvalidValue);
+    ProbeStreams t = {};
+    for (int w = 0; w < n; ++w) {
+        if (bad_buffer(streams[w], nbytes)) return static_cast<int>(hipErrorInvalidValue);
+        t.p[w] = static_cast<const uint32_t*>(streams[w]);
+    }
+    const int64_t nvec = nbytes / 16;
+    hipLaunchKernelGGL(fsdp_probe_streams_kernel, dim3(static_cast<uint32_t>((nvec + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), t, n, nvec, store, out);
     return static_cast<int>(hipGetLastError());
 }

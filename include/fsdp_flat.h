@@ -221,7 +221,7 @@ int fsdp_grad_accumulate(const fsdp_layout_t* layout, float* grad_acc, const voi
 
 /* ---- Sec. 4.4: the low-precision copy of the local shard, kept per rank -----
  * fsdp_cast_shard: lp_shard_out[k] = cast(shard[k]) (bf16 or fp16) for the S elements of
- * one fp32 shard (the "full-to-low-precision cast per FlatParameter").
+ * one fp32 shard (the one cast per FlatParameter that Sec. 4.4 places before the forward pass).
  * fsdp_reduce_scatter_adam_fused can also write it (p_lp_out) while the updated
  * shard is still in registers, which saves this pass in every later iteration.
  * fsdp_unshard_lp: the AllGather in the low precision, flat_out[w * S + k] =
@@ -274,13 +274,17 @@ int fsdp_grad_scaler_update(float* scale, int32_t* growth_tracker, const float* 
  * (Sec. 3.2.1).  A batch records fused reduce-scatter + Adam operations and
  * unshards that do NOT depend on each other (e.g. the updates of units i..i+2
  * and the prefetched unshards of units i+3..i+5, Sec. 3.3.2 / 3.3.3) and issues
- * them in as few grids as possible: up to 6 + 6 operations share one grid.
+ * them in as few grids as possible: up to 6 + 6 operations share one grid, their
+ * rank pointers one pool of 376 (twelve 8-rank members fit, and so does one
+ * 64-rank update next to one 64-rank unshard).
  * Results are bit-identical to issuing the operations one by one.  Operations
- * that cannot share a grid (W > 32, fp32 / fp16 unshard output, a second
+ * that cannot share a grid (W > 64, fp32 / fp16 unshard output, a second
  * operation of the same kind above 128 MiB, an update above 128 MiB next to an
  * unshard above 128 MiB unless the gradients are fp32 and the shard has fewer
  * than 8.4 M elements, different gradient dtype or divide mode) are issued
- * through their own entry points, in order.
+ * through their own kernels, in order.  The grids are planned and their kernel
+ * arguments written while the batch is recorded; a launch only fills in the
+ * Adam constants that depend on the step count.
  * The batch copies the pointer tables; layouts and device buffers must stay
  * valid while the batch is used.  A batch may be launched any number of times;
  * `step` is the Adam step count (after increment) of every update in it.  A

@@ -244,8 +244,23 @@ static void validation_checks()
             CHECK(fsdp_batch_add_reduce_scatter_adam(b, L, tab.data(), FSDP_F32, 0, 1.0f, 1.0f, out, p, m, v, 1e-3f, 1.5f,
                                                      0.999f, 1e-8f, nullptr) == FSDP_ERR_INVALID_ARG);
             CHECK(fsdp_batch_launch(b, 0, nullptr) == FSDP_ERR_INVALID_ARG);
+            // the recorded plan, read back launch by launch
+            int32_t n_launches = -1;
+            CHECK(fsdp_batch_launch_count(b, &n_launches) == FSDP_OK && n_launches > 0);
+            for (int32_t i = 0; i < n_launches; ++i) {
+                int32_t kernel = -1, nu = -1, ns = -1;
+                int64_t wgs = -1;
+                CHECK(fsdp_batch_launch_info(b, i, &kernel, &nu, &ns, &wgs) == FSDP_OK);
+                CHECK(fsdp_kernel_name(kernel) != nullptr && nu >= 0 && ns >= 0 && nu + ns >= 1 && wgs >= 1);
+                CHECK(fsdp_batch_launch_info(b, i, nullptr, nullptr, nullptr, nullptr) == FSDP_OK);
+            }
+            CHECK(fsdp_batch_launch_info(b, n_launches, nullptr, nullptr, nullptr, nullptr) == FSDP_ERR_RANK_RANGE);
+            CHECK(fsdp_batch_launch_info(b, -1, nullptr, nullptr, nullptr, nullptr) == FSDP_ERR_RANK_RANGE);
+            CHECK(fsdp_batch_launch_count(b, nullptr) == FSDP_ERR_NULL_PTR);
             CHECK(fsdp_batch_clear(b) == FSDP_OK);
+            CHECK(fsdp_batch_launch_count(b, &n_launches) == FSDP_OK && n_launches == 0);
         }
+        CHECK(fsdp_kernel_name(-1) == nullptr && fsdp_kernel_name(FSDP_KERNEL_GATHER_LP) != nullptr);
         CHECK(fsdp_batch_launch(b, 1, nullptr) == FSDP_OK);        // an empty batch launches nothing
         CHECK(fsdp_batch_launch(nullptr, 1, nullptr) == FSDP_ERR_NULL_PTR);
         CHECK(fsdp_batch_clear(nullptr) == FSDP_ERR_NULL_PTR);

@@ -373,3 +373,90 @@ def test_pointer_tables_are_checked_before_any_launch(L):
     # through a public entry point: the unchecked table is refused before the library is called
     with pytest.raises(TypeError):
         L.fsdp_unshard(lay, good.__class__([torch.zeros(4) for _ in range(4)], _device_check=False), flat)
+
+
+def _plan(raw, b):
+    n = ctypes.c_int32()
+    assert raw.fsdp_batch_launch_count(b, ctypes.byref(n)) == OK
+    out = []
+    for i in range(n.value):
+        k, nu, ns, wg = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int64()
+        assert raw.fsdp_batch_launch_info(b, i, ctypes.byref(k), ctypes.byref(nu), ctypes.byref(ns), ctypes.byref(wg)) == OK
+        out.append((raw.fsdp_kernel_name(k.value).decode(), nu.value, ns.value, wg.value))
+    assert raw.fsdp_batch_launch_info(b, n.value, None, None, None, None) == -6
+    return out
+
+
+def test_batches_are_planned_while_they_are_recorded(L):
+    """The grouping rules of fsdp_batch_*, read back through
+    fsdp_batch_launch_count / _info with fake device addresses (nothing is
+    launched): which operations share a grid and which kernel each launch is."""
+    raw = L.lib()
+    f, i64 = ctypes.c_float, ctypes.c_int64
+    hyper = (f(1e-4), f(0.9), f(0.999), f(1e-8))
+    addr = [0x100000]
+
+    def table(n):
+        vals = [addr[0] + 0x1000 * j for j in range(n)]
+        addr[0] += 0x1000 * n
+        return _table(vals)
+
+    def add_update(b, h, W, dt=0, rank=0):
+        p, m, v, g = (ctypes.c_void_p(addr[0] + 0x100 * j) for j in range(4))
+        addr[0] += 0x1000
+        return raw.fsdp_batch_add_reduce_scatter_adam(b, h, table(W), dt, rank, f(4.0), f(W / 4.0), g, p, m, v, *hyper, None)
+
+    def add_unshard(b, h, W, dt=1):
+        return raw.fsdp_batch_add_unshard(b, h, table(W), ctypes.c_void_p(0x7000000), dt)
+
+    b = ctypes.c_void_p()
+    assert raw.fsdp_batch_create(ctypes.byref(b)) == OK
+    assert _plan(raw, b) == []
+    # a GPT-2-small block over 8 ranks: six updates and six unshards share one grid, a seventh update opens another
+    rc, small = _init(raw, workloads.config(0).units[0].shapes, 8)
+    S = 885984
+    for _ in range(6):
+        assert add_update(b, small, 8) == OK and add_unshard(b, small, 8) == OK
+    assert _plan(raw, b) == [("batch_kernel", 6, 6, 6 * (S // 4 // 256 + 1) + 6 * 8 * (S // 8 // 256 + 1))]
+    assert add_update(b, small, 8) == OK
+    assert [p[:3] for p in _plan(raw, b)] == [("batch_kernel", 6, 6), ("batch_kernel", 1, 0)]
+    # another gradient dtype cannot join the open grid; an fp32 unshard goes through its own kernel
+    assert add_update(b, small, 8, dt=1) == OK
+    assert add_unshard(b, small, 8, dt=0) == OK
+    assert [p[:3] for p in _plan(raw, b)][2:] == [("batch_kernel", 1, 0), ("unshard_f32_kernel", 0, 1)]
+    assert raw.fsdp_batch_clear(b) == OK and _plan(raw, b) == []
+    # 65 ranks: each operation is split over two launches of its own kernel
+    rc, wide = _init(raw, [(100000,)], 65)
+    assert add_update(b, wide, 65) == OK and add_unshard(b, wide, 65) == OK
+    assert [p[0] for p in _plan(raw, b)] == ["reduce_kernel", "reduce_kernel", "unshard_lp_kernel", "unshard_lp_kernel"]
+    assert _plan(raw, b)[3][3] == 1 * (100000 // 65 // 8 // 256 + 1)          # the second unshard launch carries one rank
+    raw.fsdp_batch_clear(b)
+    # 64 ranks fit one grid (the pointer pool holds 64 + 64)
+    rc, w64 = _init(raw, [(100000,)], 64)
+    assert add_update(b, w64, 64, dt=1) == OK and add_unshard(b, w64, 64) == OK
+    assert [p[:3] for p in _plan(raw, b)] == [("batch_kernel", 1, 1)]
+    raw.fsdp_batch_clear(b)
+    # the 1.3B block, fp32 gradients: a large update pairs with a large unshard
+    rc, mid = _init(raw, workloads.config(2).units[0].shapes, 12)
+    assert add_update(b, mid, 12) == OK and add_unshard(b, mid, 12) == OK
+    assert [p[:3] for p in _plan(raw, b)] == [("batch_kernel", 1, 1)]
+    raw.fsdp_batch_clear(b)
+    # the GPT-3-175B block, bf16 gradients: no pairing; the lone update takes the stand-alone kernel and its deep walk
+    rc, big = _init(raw, workloads.config(4).units[0].shapes, 16)
+    S = 113256192
+    assert add_update(b, big, 16, dt=1) == OK and add_unshard(b, big, 16) == OK
+    assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(S // 8 + 1) // 1024)), ("batch_kernel", 0, 1, 16 * (S // 8 // 256 + 1))]
+    raw.fsdp_batch_clear(b)
+    # ... unless its layout asks for the wide walk
+    hw = ctypes.c_void_p()
+    shapes = workloads.config(4).units[0].shapes
+    flat = [d for s in shapes for d in s]
+    assert raw.fsdp_layout_init_ex((ctypes.c_int64 * len(flat))(*flat), (ctypes.c_int32 * len(shapes))(*[len(s) for s in shapes]),
+                                   len(shapes), 16, L.FSDP_WALK_WIDE, ctypes.byref(hw)) == OK
+    assert add_update(b, hw, 16, dt=1) == OK
+    assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(S // 8 + 1) // 256))]
+    assert raw.fsdp_kernel_name(99) is None
+    assert raw.fsdp_batch_launch_count(None, None) == NULL
+    raw.fsdp_batch_destroy(b)
+    for h in (small, wide, w64, mid, big, hw):
+        raw.fsdp_layout_destroy(h)
