@@ -92,6 +92,9 @@ def test_f16_all_patterns_against_torch():
         mine = oracle.cast_f16_bits(first, chunk)
         u = np.arange(first, first + chunk, dtype=np.uint32)
         ref = torch.from_numpy(u.view(np.int32)).view(torch.float32).to(torch.float16).view(torch.int16).numpy().view(np.uint16)
+        if (first >> 23) & 0xFF != 0xFF and ((first + chunk - 1) >> 23) & 0xFF != 0xFF:
+            assert np.array_equal(mine, ref), hex(first)          # no NaN pattern in this chunk
+            continue
         nan = ((u & 0x7F800000) == 0x7F800000) & ((u & 0x007FFFFF) != 0)
         assert np.array_equal(mine[~nan], ref[~nan]), hex(first)
         if nan.any():
