@@ -564,6 +564,45 @@ def run_config(cfg, args, F, torch, workloads, headline, traffic_table):
                     f"{alg / avg_us / 1e3:.1f} GB/s algorithmic, {tch / avg_us / 1e3:.1f} GB/s touched")
     rec["kernels"] = per_kernel
 
+    # ---- per FSDP unit: each distinct unit shape alone, as two launches (unshard, then the fused
+    # reduce-scatter + Adam through their own entry points), over all units of that shape in order
+    per_unit = []
+    if not args.no_kernel_timing and not lp_handoff and all(s.W <= 64 for s in states):
+        flat0 = torch.empty(max(s.P for s in states), dtype=torch.bfloat16, device="cuda")
+        with torch.cuda.stream(main_s):
+            seen = []
+            for s0 in states:
+                if s0.unit_shapes in seen:
+                    continue
+                seen.append(s0.unit_shapes)
+                same = [s for sts in reps_states for s in sts if s.unit_shapes == s0.unit_shapes]
+
+                def unit_pass(s):
+                    F.fsdp_unshard(s.lay, s.shard_tab, flat0[:s.P])
+                    F.fsdp_reduce_scatter_adam_fused(s.lay, s.grad_tab, rank, pre, post, None, s.shards[rank], s.m, s.v, 2,
+                                                     *hp, None)
+
+                for s in same:
+                    unit_pass(s)
+                n_rep = max(3, min(100, int(25e3 / max(1.0, len(same) * s0.b_total / 6e6))))    # about 25 ms
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(n_rep):
+                    for s in same:
+                        unit_pass(s)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / n_rep / len(same)
+                per_unit.append({"unit": s0.name, "count": len([s for s in states if s.unit_shapes == s0.unit_shapes]),
+                                 "bytes_algorithmic": s0.b_total, "gpu_ms": round(us / 1e3, 5),
+                                 "gpu_GBps": round(s0.b_total / us / 1e3, 1),
+                                 "pct_of_8TBps": round(100 * s0.b_total / us / 1e3 / HBM_PEAK_GBPS, 2),
+                                 "launches": 2})
+                log(f"[bench] {wl.name} unit {s0.name} alone (2 launches): {us:.1f} us, {s0.b_total / us / 1e3:.1f} GB/s")
+        del flat0
+    rec["units_alone"] = per_unit
+
     cpu = None
     if first is not None:
         cpu = first.oracle_leg(wl, pre, post, rank, hp)
