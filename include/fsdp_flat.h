@@ -17,7 +17,10 @@
  *    owns only fsdp_layout_t (host memory).
  *  - Compute calls are asynchronous on hip_stream (a hipStream_t passed as
  *    void*; NULL = the default stream) of the current device.  They never
- *    synchronise, never allocate and may be captured in a HIP graph.
+ *    synchronise, never allocate and may be captured in a HIP graph (kernel
+ *    arguments, the Adam step count and its bias corrections among them, are
+ *    then fixed at capture: re-capture, or update the graph's kernel nodes, to
+ *    advance the step).
  *  - Device buffers need only element alignment (4 B for fp32, 2 B for bf16),
  *    so contiguous shards base + w * S with odd S are legal.  Buffers of
  *    different roles must not overlap.
