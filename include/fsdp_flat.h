@@ -83,9 +83,11 @@ void fsdp_layout_destroy(fsdp_layout_t* layout);           /* NULL is a no-op */
  *   FSDP_WALK_WIDE: a lane owns one 16-byte chunk (and loads one to four ranks
  *                   at a time, by gradient dtype);
  *   FSDP_WALK_DEEP: a lane owns four chunks and loads one rank at a time;
- *   FSDP_WALK_AUTO (what fsdp_layout_init uses): deep from eight ranks on when
- *                   the shard has at least 8.4 M fp32 or 16.8 M 16-bit
- *                   elements, else wide.
+ *   FSDP_WALK_AUTO (what fsdp_layout_init uses): the library's choice, from
+ *                   measurements on MI355X: deep when the shard fills at
+ *                   least 360 deep workgroups (1.5 M fp32 or 2.9 M 16-bit
+ *                   elements) and the unit has 16 ranks or more, or 8 to 15
+ *                   ranks and fewer than 640 deep workgroups; else wide.
  * The hint applies to the stand-alone reduce kernels (fsdp_reduce_scatter_local,
  * _adam_fused, _hybrid, _accumulate, _unscale, the two-launch form of
  * _prefetch_unshard and a batch's lone large update); kernels that share a grid

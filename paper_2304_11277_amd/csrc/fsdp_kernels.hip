@@ -101,23 +101,45 @@ void pad_rank_table(PtrTable& tab, int32_t n)
     for (int32_t j = n; j % kMaxWideRanks != 0; ++j) tab.p[j] = tab.p[n - 1];
 }
 
-// The deep rank walk pays from eight rank streams on when the shard is large.
-// fp32 gradients, against the wide walk (one rank per batch): -8 % at 3.2 M
-// elements per shard and 64 ranks, -1 % at 4.2 M and 12 ranks, +1 % at 8.4 M and
-// 16.8 M, +3 % at 33.6 M, +9 % at 113 M and 16 ranks.  bf16 gradients (wide walk
-// with four ranks per batch): +1 to +3 % at 3.2 M and 64 ranks (386 workgroups),
-// +7 % at 113 M and 16 ranks.  The bound below is eight deep workgroups per
-// compute unit (256 of them on MI355X): 8.4 M fp32 or 16.8 M 16-bit elements.
+// Which rank walk the library takes by itself.  Measured on MI355X with the
+// fused kernels over cold buffers (ratio of the deep walk's time to the wide
+// one's; a deep workgroup covers 1024 chunks, MI355X has 256 compute units):
+//   below ~1.4 deep workgroups per compute unit the deep walk starves the chip
+//     (1 M elements: 1.2-1.8 with 16-bit gradients, 1.1-1.2 with fp32);
+//   from there to ~2.5 per compute unit it wins at every rank count
+//     (3-4 M 16-bit elements: 0.88-0.98; 2 M fp32: 0.92-0.93);
+//   beyond that it keeps winning with many rank streams (64 ranks: 0.90-0.98 up
+//     to 113 M elements), is even at 16 ranks (0.97-1.02; the GPT-3-175B block:
+//     1156-1162 us against 1158-1188 us, fp32 gradients 1796 against 1853 us)
+//     and loses at 8 ranks (1.02-1.10 from 6 M to 32 M elements).
+// Below eight ranks the two are within noise of each other and the wide walk,
+// with four times the workgroups, is kept.
 constexpr int32_t kDeepMinRanks = 8;
-constexpr int64_t kDeepMinBlocks = 8 * 256;
+constexpr int32_t kDeepAlwaysRanks = 16;      // from this many ranks on, deep at every size above the minimum
+constexpr int64_t kDeepMinBlocks = 360;       // ~1.4 deep workgroups per compute unit
+constexpr int64_t kDeepFewRanksMaxBlocks = 640;
 
 // does the library's own choice of rank walk fall on the deep one?
 inline bool deep_walk_pays(int gt, int32_t W, int64_t S)
 {
     const int64_t E = gt == kF32 ? 4 : 8;
     const int64_t deep_blocks = ceil_div(S / E + 1, kReduceBlock * WalkShape<kF32, true, true>::C);
-    return W >= kDeepMinRanks && deep_blocks >= kDeepMinBlocks;
+    if (W < kDeepMinRanks || deep_blocks < kDeepMinBlocks) return false;
+    return W >= kDeepAlwaysRanks || deep_blocks < kDeepFewRanksMaxBlocks;
 }
+// May a fused update above kOneLaunchMaxBytes share a grid with an unshard above
+// it?  Measured: with fp32 gradients (34 registers in the shared kernel) pairing
+// a 336 MB update with a 302 MB unshard is 5 % faster than two launches, and 6 %
+// on 64-rank units of 3.2 M elements; from 8.4 M elements per shard on the
+// stand-alone kernel is the better one, and with 16-bit gradients (86 registers)
+// pairing changes nothing.  A layout that asks for the deep walk gets the
+// stand-alone kernel.
+constexpr int64_t kPairMaxShard = 8 * 256 * 1024 * 4;      // 8.4 M elements
+inline bool pairs_with_large_unshard(const fsdp_layout_t* L, int gt)
+{
+    return gt == kF32 && L->reduce_walk != FSDP_WALK_DEEP && L->S < kPairMaxShard;
+}
+
 // would a stand-alone reduce kernel of this unit take the deep walk (the layout's hint, else the library's choice)?
 inline bool wants_deep(const fsdp_layout_t* L, int gt)
 {
@@ -473,7 +495,7 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* L, const void
     const int64_t reduce_bytes = dtype_size(grad_dtype) * L->P + 24 * L->S;
     const int64_t unshard_bytes = 6 * N->P;
     const bool small_half = (reduce_bytes < unshard_bytes ? reduce_bytes : unshard_bytes) <= kOneLaunchMaxBytes;
-    const bool pair_large = grad_dtype == FSDP_F32 && !wants_deep(L, kF32);
+    const bool pair_large = pairs_with_large_unshard(L, static_cast<int>(grad_dtype));
     const bool one_launch = (small_half || pair_large) && L->world_size <= kMaxRanks &&
                             N->world_size <= kMaxRanks &&
                             next_out_dtype == FSDP_BF16 && grid_ok(n_reduce + n_unshard);
@@ -905,18 +927,18 @@ int fsdp_batch_add_reduce_scatter_adam(fsdp_batch_t* b, const fsdp_layout_t* L, 
         }
         const ReduceKind k = {static_cast<int>(grad_dtype), pre_mode_of(pre_div)};
         const bool is_large = bytes > kOneLaunchMaxBytes;
-        const bool pairs_with_large_unshard = k.gt == kF32 && !wants_deep(L, kF32);
+        const bool pairable = pairs_with_large_unshard(L, k.gt);
         fsdp_batch::Grid* g = b->open_grid();
         if (!g || g->args.n_reduce == kBatchOps || (g->args.n_reduce > 0 && !(k == g->kind)) ||
             g->n_ptrs + W_padded > kBatchPtrs || !grid_ok(nb + g->r_blocks + g->u_blocks) ||
-            (is_large && (g->large_r > 0 || (g->large_u > 0 && !pairs_with_large_unshard))))
+            (is_large && (g->large_r > 0 || (g->large_u > 0 && !pairable))))
             g = b->new_grid();
         if (g->args.n_reduce == 0) {
             g->kind = k;
             g->walk0 = L->reduce_walk;
         }
         g->large_r += is_large ? 1 : 0;
-        if (is_large) g->pairable = pairs_with_large_unshard;
+        if (is_large) g->pairable = pairable;
         BatchReduceOp& o = g->args.r[g->args.n_reduce];
         o.ptr0 = g->n_ptrs;
         const int64_t off = static_cast<int64_t>(rank) * L->S * dtype_size(grad_dtype);

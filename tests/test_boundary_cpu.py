@@ -447,6 +447,19 @@ def test_batches_are_planned_while_they_are_recorded(L):
     assert add_update(b, big, 16, dt=1) == OK and add_unshard(b, big, 16) == OK
     assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(S // 8 + 1) // 1024)), ("batch_kernel", 0, 1, 16 * (S // 8 // 256 + 1))]
     raw.fsdp_batch_clear(b)
+    # the library's own choice of walk for a lone large update (measured rule): the Llama-7B block over 64 ranks
+    # takes the deep walk (386 workgroups of 1024 chunks), a 16 M-element shard over 8 ranks the wide one
+    rc, llama = _init(raw, workloads.config(3).units[0].shapes, 64)
+    S3 = 3162240
+    assert add_update(b, llama, 64, dt=1) == OK
+    assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(S3 // 8 + 1) // 1024))]
+    raw.fsdp_batch_clear(b)
+    rc, w8 = _init(raw, [(8 * 16000000,)], 8)
+    assert add_update(b, w8, 8, dt=1) == OK
+    assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(16000000 // 8 + 1) // 256))]
+    raw.fsdp_batch_clear(b)
+    raw.fsdp_layout_destroy(llama)
+    raw.fsdp_layout_destroy(w8)
     # ... unless its layout asks for the wide walk
     hw = ctypes.c_void_p()
     shapes = workloads.config(4).units[0].shapes

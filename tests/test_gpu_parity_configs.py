@@ -24,14 +24,6 @@ BENCH_DEPTH = 6     # bench.py's default --depth
 CASES = [(c, u) for c in range(workloads.NUM_CONFIGS) for u in workloads.config(c).distinct_units]
 
 
-def _other_walk(F, W, S, grad_dtype):
-    """The rank walk that FSDP_WALK_AUTO does not take for this unit (the
-    library's rule: deep from 8 ranks on when the shard fills 2048 deep
-    workgroups of 256 lanes x 4 chunks of 4 fp32 or 8 16-bit elements)."""
-    auto_deep = W >= 8 and S >= 8 * 256 * 256 * 4 * (4 if grad_dtype == "f32" else 8)
-    return F.FSDP_WALK_WIDE if auto_deep else F.FSDP_WALK_DEEP
-
-
 def _ranks(cfg, W):
     return list(range(W)) if cfg <= 2 else [0, 1, W - 1]
 
@@ -130,14 +122,15 @@ def test_config_unit_matches_oracle(F, cfg, unit_index):
             assert not np_bits(p)[S - lay.pad:].any()
         if r == BENCH_RANK:
             bench_ref = (rp.copy(), rm.copy(), rv.copy(), np_bits(p2).copy(), np_bits(m2).copy(), np_bits(v2).copy())
-            # the rank walk the library does not choose at this size, forced through the layout: same bits
-            lay_other = F.fsdp_layout_init(unit.shapes, W, reduce_walk=_other_walk(F, W, S, wl.grad_dtype))
-            p3, m3, v3 = shards[r].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
-            F.fsdp_reduce_scatter_adam_fused(lay_other, grads, r, pre, post, None, p3, m3, v3, 1, *hp, None)
-            torch.cuda.synchronize()
-            for a, b, n in ((p3, p2, "p"), (m3, m2, "m"), (v3, v2, "v")):
-                assert same_bits(np_bits(a), np_bits(b)), f"{n}: the two rank walks differ at rank {r}"
-            del p3, m3, v3
+            # both rank walks forced through the layout (one of them is the library's own choice): same bits
+            for walk in (F.FSDP_WALK_WIDE, F.FSDP_WALK_DEEP):
+                lay_w = F.fsdp_layout_init(unit.shapes, W, reduce_walk=walk)
+                p3, m3, v3 = shards[r].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
+                F.fsdp_reduce_scatter_adam_fused(lay_w, grads, r, pre, post, None, p3, m3, v3, 1, *hp, None)
+                torch.cuda.synchronize()
+                for a, b, n in ((p3, p2, "p"), (m3, m2, "m"), (v3, v2, "v")):
+                    assert same_bits(np_bits(a), np_bits(b)), f"{n}: rank walk {walk} differs at rank {r}"
+                del p3, m3, v3
         print(f"[step] rank {r}: reduce-scatter bit-exact, Adam bit-identical to the fp32 oracle and within 1e-6 of "
               f"the fp64 one, fused == two calls", flush=True)
         del p, m, v, p2, m2, v2, rp, rm, rv, gp, gm, gv, ref_g
@@ -241,13 +234,14 @@ def test_config_unit_variants_match_oracle(F, cfg, unit_index):
     z = np.zeros(S, np.float32)
     rp, _, _ = assert_adam_parity(np_f32(p), np_f32(m), np_f32(v), h_shards[r], ref_g, z, z, 1, hp, f"{other} gradients")
     assert same_bits(np_bits(lp_out), oracle.cast_bf16(rp)), "bf16 copy of the updated shard"
-    lay_other = F.fsdp_layout_init(unit.shapes, W, reduce_walk=_other_walk(F, W, S, other))
-    p3, m3, v3 = shards[r].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
-    F.fsdp_reduce_scatter_adam_fused(lay_other, grads, r, pre, post, None, p3, m3, v3, 1, *hp, None)
-    torch.cuda.synchronize()
-    for a, b, n in ((p3, p, "p"), (m3, m, "m"), (v3, v, "v")):
-        assert same_bits(np_bits(a), np_bits(b)), f"{other} gradients, {n}: the two rank walks differ"
-    del p3, m3, v3
+    for walk in (F.FSDP_WALK_WIDE, F.FSDP_WALK_DEEP):
+        lay_w = F.fsdp_layout_init(unit.shapes, W, reduce_walk=walk)
+        p3, m3, v3 = shards[r].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
+        F.fsdp_reduce_scatter_adam_fused(lay_w, grads, r, pre, post, None, p3, m3, v3, 1, *hp, None)
+        torch.cuda.synchronize()
+        for a, b, n in ((p3, p, "p"), (m3, m, "m"), (v3, v, "v")):
+            assert same_bits(np_bits(a), np_bits(b)), f"{other} gradients, {n}: rank walk {walk} differs"
+        del p3, m3, v3
     print(f"[step] {other} gradients: reduce-scatter bit-exact, Adam bit-identical (both rank walks), bf16 copy of the "
           "new shard bit-exact", flush=True)
 
