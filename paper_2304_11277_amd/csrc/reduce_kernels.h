@@ -96,8 +96,10 @@ __device__ __forceinline__ float post_scale(float x, const RsArgs& a)
 //         after the walk; 3-9 % faster than G = 4 from 7 M-element units up),
 //         2 resp. 1 for the reduce-scatter alone (13 % faster than G = 4 at 64
 //         ranks: the more rank streams, the shallower the best queue per lane).
-//   deep  (G = 1, C = 4): one rank stream at a time, four chunks of it.  Used
-//         with many ranks on large shards (another 1-9 %).
+//   deep  (G = 1, C = 4): one rank stream at a time, four chunks of it, so a
+//         workgroup reads 16 KiB of a rank in one piece.  Taken from about 1.4
+//         such workgroups per compute unit on when there are many ranks (the
+//         host's rule and its measurements: deep_walk_pays).
 // The host pads the pointer table to a multiple of kMaxWideRanks with copies of
 // the last pointer, so loads never need a predicate; the padding's adds are
 // skipped.
