@@ -36,8 +36,16 @@ PROBE_SRC = os.path.join(ROOT, "bench_probe.hip")
 PROBE_LIB = os.path.join(ROOT, "libbench_probe.so")
 
 
+VERBOSE = False
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def vlog(*a):
+    if VERBOSE:
+        log(*a)
 
 
 def parse_args():
@@ -89,6 +97,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (timing and parity)")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the plain copy / read / write kernels")
+    ap.add_argument("--detail-json", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"),
+                    help="file that receives every figure of the run (the line on stdout is a compact view); '' = none")
+    ap.add_argument("--verbose", action="store_true", help="log per-kernel and per-unit lines as they are measured")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
                     help="HBM bytes per launch by `workload:kernel`, from rocprofv3 --pmc runs (see profiles/)")
     return ap.parse_args()
@@ -438,7 +449,7 @@ def run_config(cfg, args, F, torch, workloads, headline, traffic_table):
         reps_launches.append(build_launches(F, states, flats, args, depth, rank, pre, post, hp))
     states, launches = reps_states[0], reps_launches[0]
     torch.cuda.synchronize()
-    log(f"[bench] {wl.name}: {len(states)} units, W={wl.world_size}, grads {wl.grad_dtype}, mode {args.mode}, "
+    vlog(f"[bench] {wl.name}: {len(states)} units, W={wl.world_size}, grads {wl.grad_dtype}, mode {args.mode}, "
         f"{len(launches)} launches per step, setup {time.time() - t0:.1f}s, HBM in use "
         f"{torch.cuda.memory_allocated() / 2**30:.2f} GiB")
 
@@ -560,7 +571,7 @@ def run_config(cfg, args, F, torch, workloads, headline, traffic_table):
                     "GBps_touched": round(tch / (avg_us * 1e-6) / 1e9, 1),
                     "hbm_bytes_per_launch": traffic_table.get(f"{wl.name}:{name}") if args.mode == "batch" else None,
                 }
-                log(f"[bench] {wl.name} kernel {name}: {per_step_launches} per step, avg {avg_us:.2f} us, "
+                vlog(f"[bench] {wl.name} kernel {name}: {per_step_launches} per step, avg {avg_us:.2f} us, "
                     f"{alg / avg_us / 1e3:.1f} GB/s algorithmic, {tch / avg_us / 1e3:.1f} GB/s touched")
     rec["kernels"] = per_kernel
 
@@ -599,7 +610,7 @@ def run_config(cfg, args, F, torch, workloads, headline, traffic_table):
                                  "gpu_GBps": round(s0.b_total / us / 1e3, 1),
                                  "pct_of_8TBps": round(100 * s0.b_total / us / 1e3 / HBM_PEAK_GBPS, 2),
                                  "launches": 2})
-                log(f"[bench] {wl.name} unit {s0.name} alone (2 launches): {us:.1f} us, {s0.b_total / us / 1e3:.1f} GB/s")
+                vlog(f"[bench] {wl.name} unit {s0.name} alone (2 launches): {us:.1f} us, {s0.b_total / us / 1e3:.1f} GB/s")
         del flat0
     rec["units_alone"] = per_unit
 
@@ -665,8 +676,7 @@ class FirstStepCheck:
                 del res
             passes += 1
         out = {"value": round(done / spent / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": f"{passes} passes over all {len(self.units)} units of {wl.name}, {spent:.2f} s of oracle time "
-                         f"(unshard + rank-0 reduce-scatter + Adam per unit)",
+               "sample": f"{passes} passes over the {len(self.units)} unit(s) of {wl.name}, {spent:.1f} s",
                "oracle_ms_all_cores": per_unit_ms}
         # the same on one host thread: units in order until about 8 s are spent (reported beside the all-cores figure)
         threads = oracle.num_threads()
@@ -753,7 +763,9 @@ def next_rows(args, wl, F, torch, workloads):
 
 
 def main():
+    global VERBOSE
     args = parse_args()
+    VERBOSE = args.verbose or args.config is not None
     if args.gpus != 1:
         print("bench.py: this build simulates all W ranks on ONE GPU; --gpus must be 1 "
               "(no multi-GPU figure exists for it)", file=sys.stderr)
@@ -837,7 +849,43 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu, "measured_ceilings": ceilings, "units_table": units_table,
         "kernels": head["kernels"], "configs": records,
     }
-    print(json.dumps(out), flush=True)
+    # Everything measured goes to a file; the ONE line on stdout is a compact view of it (harnesses keep
+    # only the tail of a run's output).
+    if args.detail_json:
+        try:
+            os.makedirs(os.path.dirname(os.path.abspath(args.detail_json)), exist_ok=True)
+            with open(args.detail_json, "w") as fh:
+                json.dump(out, fh, indent=1)
+        except OSError as e:
+            log(f"[bench] could not write {args.detail_json}: {e}")
+    print(json.dumps(compact(out), separators=(",", ":")), flush=True)
+
+
+def compact(out):
+    """The JSON line: the contract's keys in full, per-kernel and per-configuration records reduced to their figures."""
+    def kern(ks):
+        return {k: {"n": v["launches_per_step"], "avg_us": v["avg_us"], "GBps": v["GBps"], "GBps_touched": v["GBps_touched"],
+                    "hbm_bytes": v["hbm_bytes_per_launch"]} for k, v in ks.items()}
+    line = dict(out)
+    line["config"] = {k: out["config"][k] for k in ("workload", "units", "world_size", "grad_dtype", "mode",
+                                                    "launches_per_step", "alg_bytes_per_step", "touched_bytes_per_step")}
+    if out["measured_ceilings"]:
+        line["measured_ceilings"] = {k: out["measured_ceilings"][k] for k in ("copy_GBps", "read_GBps", "write_GBps")}
+    line["kernels"] = kern(out["kernels"])
+    line["units_table"] = [{k: (v["reduce_scatter+adam"] if k == "parity" and isinstance(v, dict) else v)
+                            for k, v in u.items()} for u in out["units_table"]]
+    line["configs"] = []
+    for c in out["configs"]:
+        r = {"workload": c["workload"], "us_per_step": c["us_per_step"], "us_min": c["us_per_step_min"],
+             "us_median": c["us_per_step_median"], "GBps": c["GBps"], "pct_of_hbm_peak": c["pct_of_hbm_peak"],
+             "launches": c["launches_per_step"], "kernel_us": {k: v["avg_us"] for k, v in c["kernels"].items()}}
+        if c.get("warm_one_replica"):
+            r["cold_replicas"] = c["buffer_replicas"]
+            r["warm_us_median"] = c["warm_one_replica"]["us_per_step_median"]
+        if c.get("note"):
+            r["note"] = "launch-bound (two dependent launches)"
+        line["configs"].append(r)
+    return line
 
 
 if __name__ == "__main__":
