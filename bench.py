@@ -872,8 +872,9 @@ def compact(out):
     if out["measured_ceilings"]:
         line["measured_ceilings"] = {k: out["measured_ceilings"][k] for k in ("copy_GBps", "read_GBps", "write_GBps")}
     line["kernels"] = kern(out["kernels"])
-    line["units_table"] = [{k: (v["reduce_scatter+adam"] if k == "parity" and isinstance(v, dict) else v)
-                            for k, v in u.items()} for u in out["units_table"]]
+    if out["units_table"]:
+        line["units_table"] = [{k: (v["reduce_scatter+adam"] if k == "parity" and isinstance(v, dict) else v)
+                                for k, v in u.items()} for u in out["units_table"]]
     line["configs"] = []
     for c in out["configs"]:
         r = {"workload": c["workload"], "us_per_step": c["us_per_step"], "us_min": c["us_per_step_min"],
