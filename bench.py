@@ -90,6 +90,10 @@ def parse_args():
                          "the forward pass and once before its backward; the metric's bytes count both")
     ap.add_argument("--grad-dtype", choices=["f32", "bf16"], default=None,
                     help="override the workload's gradient dtype (the fp32 / bf16 variants of every configuration)")
+    ap.add_argument("--rank", type=int, default=0,
+                    help="the rank whose share of the reduce-scatter and of the optimizer step is timed (default 0; "
+                         "with a shard size that is not a multiple of 4, other ranks' gradient slices are not "
+                         "16-byte aligned)")
     ap.add_argument("--walk", choices=["auto", "wide", "deep"], default="auto",
                     help="rank walk of the stand-alone reduce-scatter kernels (the layouts' fsdp_layout_init_ex hint)")
     ap.add_argument("--grad-sets", type=int, default=0,
@@ -422,7 +426,9 @@ def run_config(cfg, args, F, torch, workloads, headline, traffic_table):
         units = [workloads.Unit(f"{u.name}x{args.unit_scale}", tuple(u.shapes) * args.unit_scale) for u in units]
     pre, post = F.fsdp_default_divide_factors(wl.world_size)
     hp = (wl.lr, wl.beta1, wl.beta2, wl.eps)
-    rank = 0
+    rank = args.rank
+    if not 0 <= rank < wl.world_size:
+        raise SystemExit(f"bench.py: --rank {rank} is outside 0..{wl.world_size - 1} of {wl.name}")
     batched = args.mode in ("batch", "batch-lp")
     lp_handoff = args.mode in ("lp", "batch-lp")
     # Configuration 0 is one 99 MB unit: run over and over it would stay in the
