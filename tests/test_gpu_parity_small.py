@@ -580,3 +580,28 @@ def test_fig3_worked_example_on_gpu(F):
     views = F.fsdp_views(lay, flat)
     assert tuple(views[0].shape) == (3, 4) and tuple(views[1].shape) == (3,)
     assert views[0].float().flatten().tolist() == [float(i) for i in range(1, 13)]
+
+
+def test_readme_usage_block_runs_and_matches_oracle(F):
+    """The usage example printed in README.md, executed as it stands."""
+    import os
+    import re
+    text = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "README.md")).read()
+    blocks = re.findall(r"```python\n(.*?)```", text, flags=re.S)
+    assert len(blocks) == 1
+    torch.manual_seed(11)
+    ns = {}
+    exec(compile(blocks[0], "README.md", "exec"), ns)
+    torch.cuda.synchronize()
+    lay, W, rank = ns["lay"], ns["W"], ns["rank"]
+    S = lay.shard
+    # the views show the bf16 cast of the parameters as they were before the update
+    for view, param in zip(ns["views"], ns["params"]):
+        assert view.shape == param.shape
+        assert same_bits(np_bits(view.contiguous()).ravel(), oracle.cast_bf16(np_f32(param).ravel()))
+    # the rank's shard after step 1 from zero state
+    flat32 = np.concatenate([np_f32(p).ravel() for p in ns["params"]] + [np.zeros(lay.pad, np.float32)])
+    g = oracle.reduce_scatter([np_f32(x) for x in ns["grads"]], rank, ns["pre"], ns["post"])
+    z = np.zeros(S, np.float32)
+    rp, rm, rv = oracle.adam_f32(flat32[rank * S:(rank + 1) * S], g, z, z, 1, 1e-4, 0.9, 0.999, 1e-8)
+    assert_adam_bits(np_f32(ns["shards"][rank]), np_f32(ns["m"]), np_f32(ns["v"]), rp, rm, rv)
