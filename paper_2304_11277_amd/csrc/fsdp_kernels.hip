@@ -487,11 +487,11 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* L, const void
     const int64_t n_unshard = tiles * N->world_size;
     // Sharing a grid pays while the fixed cost of a launch (about 2 us of ramp
     // and drain) is visible next to the smaller half.  For large halves it
-    // still pays with fp32 gradients (5 % on 300 MB halves: the fp32 reduce body
-    // needs 20 registers) up to the shard size from which the stand-alone kernel
-    // would take the deep walk, which is worth more; with 16-bit gradients the
-    // shared kernel's register budget (52) costs a large unshard more than the
-    // launch saves (5 % slower).
+    // still pays with fp32 gradients (5 % on 300 MB halves; the shared kernel
+    // then needs 34 registers) up to the shard size given by
+    // pairs_with_large_unshard; with 16-bit gradients (84 registers) sharing a
+    // grid gains nothing on large halves, and their updates keep the
+    // stand-alone kernel, which may take the deep walk.
     const int64_t reduce_bytes = dtype_size(grad_dtype) * L->P + 24 * L->S;
     const int64_t unshard_bytes = 6 * N->P;
     const bool small_half = (reduce_bytes < unshard_bytes ? reduce_bytes : unshard_bytes) <= kOneLaunchMaxBytes;
