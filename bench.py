@@ -80,6 +80,9 @@ def parse_args():
     ap.add_argument("--probe-mix", action="store_true",
                     help="run only the read / write mix probe: 16 streams of a GPT-3-175B block's rank slice read in "
                          "lock step as the reduce-scatter reads them, with and without the fp32 result written")
+    ap.add_argument("--probe-small", action="store_true",
+                    help="run only the small-launch probe: plain kernels carrying the traffic of configuration 0's two "
+                         "launches, over rotating (cold) buffers")
     ap.add_argument("--next-rows", action="store_true",
                     help="measure the kernels beyond the hot path (hybrid-sharding reduce, gradient accumulation, "
                          "fp16 / fp32 unshard, unscale) on the workload's largest unit and print their own JSON line")
@@ -243,6 +246,66 @@ def probe_mix(torch):
         del bufs
         torch.cuda.empty_cache()
     print(json.dumps({"probe": "read/write mix", "stream_bytes": nbytes, "results": res}), flush=True)
+
+
+def probe_small(torch):
+    """What plain streaming kernels take for the traffic of configuration 0's
+    two launches (one GPT-2-small block over 8 ranks: the unshard reads 28.4 MB
+    and writes 14.2 MB, the fused update reads 39.0 MB and writes 10.6 MB),
+    launched back to back over 12 rotating sets of buffers like the timed
+    steps: the floor that launch ramp and drain leave at this size."""
+    lib = load_probe()
+    st = torch.cuda.current_stream().cuda_stream
+    R = 12
+
+    def timed(fn, reps=300):
+        for i in range(2 * R):
+            fn(i)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(reps):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / reps
+
+    res = {}
+
+    def streams(tag, n, nbytes, store):
+        sets = []
+        for _ in range(R):
+            srcs = [torch.zeros(nbytes // 2, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+            out = torch.zeros(nbytes // 2, dtype=torch.float32, device="cuda")
+            sets.append((srcs, out, (ctypes.c_void_p * n)(*[x.data_ptr() for x in srcs])))
+
+        def fn(i):
+            rc = lib.fsdp_probe_streams(sets[i % R][2], n, nbytes, store, sets[i % R][1].data_ptr(), st)
+            assert rc == 0, rc
+
+        us = timed(fn)
+        moved = n * nbytes + (2 * nbytes if store else 0)
+        res[tag] = {"streams": n, "read_bytes": n * nbytes, "written_bytes": 2 * nbytes if store else 0,
+                    "us": round(us, 2), "GBps": round(moved / us / 1e3, 1)}
+        log(f"[probe-small] {tag}: {us:.2f} us, {moved / 1e6:.1f} MB, {moved / us / 1e3:.0f} GB/s")
+
+    def copy(tag, nbytes):
+        bufs = [(torch.zeros(nbytes // 4, device="cuda"), torch.zeros(nbytes // 4, device="cuda")) for _ in range(R)]
+
+        def fn(i):
+            rc = lib.fsdp_probe_copy(bufs[i % R][1].data_ptr(), bufs[i % R][0].data_ptr(), nbytes, st)
+            assert rc == 0, rc
+
+        us = timed(fn)
+        res[tag] = {"read_bytes": nbytes, "written_bytes": nbytes, "us": round(us, 2), "GBps": round(2 * nbytes / us / 1e3, 1)}
+        log(f"[probe-small] {tag}: {us:.2f} us, {2 * nbytes / 1e6:.1f} MB, {2 * nbytes / us / 1e3:.0f} GB/s")
+
+    copy("empty_launch", 16)
+    streams("unshard_traffic_4_streams_28.4MB_read_14.2MB_written", 4, 7087872, 1)
+    copy("copy_of_the_same_total_21.3MB_each_way", 21263616)
+    streams("update_traffic_11_streams_39.0MB_read_7.1MB_written", 11, 3543936, 1)
+    copy("copy_of_the_same_total_23.0MB_each_way", 23035584)
+    print(json.dumps({"probe": "small launches", "rotating_sets": R, "results": res}), flush=True)
 
 
 # ---------------------------------------------------------------------------
@@ -790,6 +853,9 @@ def main():
         return
     if args.probe_mix:
         probe_mix(torch)
+        return
+    if args.probe_small:
+        probe_small(torch)
         return
     if args.next_rows:
         wl = workloads.config(1 if args.config is None else args.config)
