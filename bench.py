@@ -80,6 +80,9 @@ def parse_args():
     ap.add_argument("--probe-mix", action="store_true",
                     help="run only the read / write mix probe: 16 streams of a GPT-3-175B block's rank slice read in "
                          "lock step as the reduce-scatter reads them, with and without the fp32 result written")
+    ap.add_argument("--probe-update", action="store_true",
+                    help="run only the update probe: the library's fused reduce-scatter + Adam and a plain kernel with "
+                         "the same memory traffic, on the same buffers (--config 3 or 4: 16-bit gradients)")
     ap.add_argument("--probe-small", action="store_true",
                     help="run only the small-launch probe: plain kernels carrying the traffic of configuration 0's two "
                          "launches, over rotating (cold) buffers")
@@ -134,6 +137,7 @@ def load_probe():
     lib.fsdp_probe_read.argtypes = [vp, i64, vp, vp]
     lib.fsdp_probe_write.argtypes = [vp, i64, ctypes.c_float, vp]
     lib.fsdp_probe_streams.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, ctypes.c_int, vp, vp]
+    lib.fsdp_probe_update.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, vp, vp, vp, vp]
     return lib
 
 
@@ -246,6 +250,66 @@ def probe_mix(torch):
         del bufs
         torch.cuda.empty_cache()
     print(json.dumps({"probe": "read/write mix", "stream_bytes": nbytes, "results": res}), flush=True)
+
+
+def probe_update(cfg, F, torch, workloads):
+    """The fused reduce-scatter + Adam of a configuration's largest unit next
+    to a plain kernel that moves the same bytes through the same buffers (W
+    rank slices of 16-bit gradients read; p, m, v read and written in place)
+    with almost no arithmetic: what the memory system gives this traffic,
+    whatever the kernel.  The two are timed alternately, three rounds."""
+    lib = load_probe()
+    wl = workloads.config(cfg)
+    assert wl.grad_dtype == "bf16", "the update probe reads 16-bit gradient streams: --config 3 or 4"
+    W = wl.world_size
+    unit = max(wl.units, key=lambda u: sum(workloads.numel(x) for x in u.shapes))
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S, P = lay.shard, lay.padded
+    assert (2 * S) % 16 == 0
+    pre, post = F.fsdp_default_divide_factors(W)
+    hp = (wl.lr, wl.beta1, wl.beta2, wl.eps)
+    st = torch.cuda.current_stream().cuda_stream
+    touched = 2 * W * S + 24 * S
+    nsets = max(1, min(8, int(2e9 // touched) + 1))          # rotate while one launch moves less than 2 GB
+    sets = []
+    for i in range(nsets):
+        grads = [workloads.gen_rank_grad(P, lay.numel, w, i, "bf16", device="cuda") for w in range(W)]
+        state = [torch.empty(S, device="cuda").normal_(0, 0.02), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")]
+        tab = (ctypes.c_void_p * W)(*[g.data_ptr() for g in grads])          # rank 0's slices start at the buffers' bases
+        sets.append((F.PtrArray(grads), state, tab))
+
+    def library(i):
+        tabs, (p, m, v), _ = sets[i % nsets]
+        F.fsdp_reduce_scatter_adam_fused(lay, tabs, 0, pre, post, None, p, m, v, 2, *hp, None)
+
+    def plain(i):
+        _, (p, m, v), tab = sets[i % nsets]
+        rc = lib.fsdp_probe_update(tab, W, 2 * S, p.data_ptr(), m.data_ptr(), v.data_ptr(), st)
+        assert rc == 0, rc
+
+    reps = max(6, min(60, int(20e9 // touched)))
+
+    def timed(fn):
+        for i in range(nsets + 1):
+            fn(i)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(reps):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / reps
+
+    rounds = []
+    for _ in range(3):
+        t_lib, t_plain = timed(library), timed(plain)
+        rounds.append({"library_us": round(t_lib, 1), "plain_us": round(t_plain, 1)})
+        log(f"[probe-update] {wl.name}: library {t_lib:.1f} us ({touched / t_lib / 1e3:.0f} GB/s touched), plain kernel "
+            f"{t_plain:.1f} us ({touched / t_plain / 1e3:.0f} GB/s)")
+    print(json.dumps({"probe": "fused update against a plain kernel with the same traffic", "workload": wl.name,
+                      "unit": unit.name, "world_size": W, "touched_bytes": touched, "rotating_sets": nsets,
+                      "rounds": rounds}), flush=True)
 
 
 def probe_small(torch):
@@ -856,6 +920,9 @@ def main():
         return
     if args.probe_small:
         probe_small(torch)
+        return
+    if args.probe_update:
+        probe_update(4 if args.config is None else args.config, F, torch, workloads)
         return
     if args.next_rows:
         wl = workloads.config(1 if args.config is None else args.config)

@@ -67,6 +67,40 @@ __global__ __launch_bounds__(256) void fsdp_probe_streams_kernel(ProbeStreams t,
     }
 }
 
+// The fused update's memory traffic with almost no arithmetic: the rank walk
+// above (n streams of 16-bit values, 16 bytes per lane and stream), then three
+// fp32 arrays of the same element count read and written in place (plain
+// accesses), eight elements per lane.  What the memory system gives this mix of
+// many read streams and three read-modify-write streams, whatever the kernel.
+__global__ __launch_bounds__(256) void fsdp_probe_update_kernel(ProbeStreams t, int n, int64_t nvec, float* __restrict__ p,
+                                                                float* __restrict__ m, float* __restrict__ v)
+{
+    const int64_t c = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (c >= nvec) return;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = -0.0f;
+    for (int w = 0; w < n; ++w) {
+        const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t.p[w]) + c);
+        acc[0] += __uint_as_float(x.x << 16); acc[1] += __uint_as_float(x.x & 0xFFFF0000u);
+        acc[2] += __uint_as_float(x.y << 16); acc[3] += __uint_as_float(x.y & 0xFFFF0000u);
+        acc[4] += __uint_as_float(x.z << 16); acc[5] += __uint_as_float(x.z & 0xFFFF0000u);
+        acc[6] += __uint_as_float(x.w << 16); acc[7] += __uint_as_float(x.w & 0xFFFF0000u);
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        f32x4* pp = reinterpret_cast<f32x4*>(p + c * 8 + 4 * q);
+        f32x4* pm = reinterpret_cast<f32x4*>(m + c * 8 + 4 * q);
+        f32x4* pv = reinterpret_cast<f32x4*>(v + c * 8 + 4 * q);
+        const f32x4 g = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        const f32x4 mk = *pm * 0.9f + g;
+        const f32x4 vk = *pv * 0.999f + g * g;
+        *pp = *pp - mk * 0.0001f;
+        *pm = mk;
+        *pv = vk;
+    }
+}
+
 namespace {
 bool bad_buffer(const void* p, int64_t nbytes)
 {
@@ -118,5 +152,22 @@ extern "C" int fsdp_probe_streams(const void* const* streams, int n, int64_t nby
     const int64_t nvec = nbytes / 16;
     hipLaunchKernelGGL(fsdp_probe_streams_kernel, dim3(static_cast<uint32_t>((nvec + 255) / 256)), dim3(256), 0,
                        static_cast<hipStream_t>(hip_stream), t, n, nvec, store, out);
+    return static_cast<int>(hipGetLastError());
+}
+
+// As fsdp_probe_streams, plus p, m, v: device, 2 * nbytes bytes each (fp32, one per 16-bit stream value), updated in place.
+extern "C" int fsdp_probe_update(const void* const* streams, int n, int64_t nbytes, float* p, float* m, float* v,
+                                 void* hip_stream)
+{
+    if (!streams || n < 1 || n > 64 || bad_buffer(p, nbytes) || bad_buffer(m, nbytes) || bad_buffer(v, nbytes))
+        return static_cast<int>(hipErrorInvalidValue);
+    ProbeStreams t = {};
+    for (int w = 0; w < n; ++w) {
+        if (bad_buffer(streams[w], nbytes)) return static_cast<int>(hipErrorInvalidValue);
+        t.p[w] = static_cast<const uint32_t*>(streams[w]);
+    }
+    const int64_t nvec = nbytes / 16;
+    hipLaunchKernelGGL(fsdp_probe_update_kernel, dim3(static_cast<uint32_t>((nvec + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), t, n, nvec, p, m, v);
     return static_cast<int>(hipGetLastError());
 }
