@@ -605,3 +605,67 @@ def test_readme_usage_block_runs_and_matches_oracle(F):
     z = np.zeros(S, np.float32)
     rp, rm, rv = oracle.adam_f32(flat32[rank * S:(rank + 1) * S], g, z, z, 1, 1e-4, 0.9, 0.999, 1e-8)
     assert_adam_bits(np_f32(ns["shards"][rank]), np_f32(ns["m"]), np_f32(ns["v"]), rp, rm, rv)
+
+
+def test_host_threads_share_a_layout_and_a_batch(F):
+    """Calls that share a layout (and launches of an unmodified batch) are
+    independent across host threads and streams: four threads, each on its own
+    stream with its own outputs and optimizer state, give the bits of the same
+    calls issued one after the other from one thread."""
+    import threading
+    W, r, iters, nthreads = 8, 5, 40, 4
+    unit = big_unit()
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S, P, N = lay.shard, lay.padded, lay.numel
+    pre, post = F.fsdp_default_divide_factors(W)
+    params = make_params(unit, 77, misalign=False)
+    shards, _ = alloc_shards(W, S, "contig_odd")
+    F.fsdp_flatten_shard(lay, params, shards)
+    shard_tab = F.PtrArray(shards)
+    grad_tab = F.PtrArray(make_grads(W, P, N, torch.bfloat16, 4100))
+    batch = F.Batch()
+    batch_flat = carve(P, torch.bfloat16, 0, fill=POISON16)
+    batch.add_unshard(lay, shard_tab, batch_flat)
+    torch.cuda.synchronize()
+
+    def fresh_state():
+        g = torch.Generator(device="cuda")
+        g.manual_seed(4200)
+        return (torch.empty(S, device="cuda").normal_(0, 0.02, generator=g), torch.zeros(S, device="cuda"),
+                torch.zeros(S, device="cuda"), carve(P, torch.bfloat16, 1, fill=POISON16))
+
+    def work(state, stream):
+        p, m, v, flat = state
+        for t in range(1, iters + 1):
+            F.fsdp_unshard(lay, shard_tab, flat, stream=stream)
+            batch.launch(t, stream=stream)
+            F.fsdp_reduce_scatter_adam_fused(lay, grad_tab, r, pre, post, None, p, m, v, t, LR, B1, B2, EPS, None,
+                                             stream=stream)
+
+    ref = fresh_state()
+    work(ref, None)
+    torch.cuda.synchronize()
+    states = [fresh_state() for _ in range(nthreads)]
+    streams = [torch.cuda.Stream() for _ in range(nthreads)]
+    torch.cuda.synchronize()
+    errors = []
+
+    def body(i):
+        try:
+            work(states[i], streams[i])
+        except Exception as e:       # surfaced below: an exception in a thread must fail the test
+            errors.append(e)
+
+    threads = [threading.Thread(target=body, args=(i,)) for i in range(nthreads)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for i, st in enumerate(states):
+        for got, want, name in zip(st, ref, ("p", "m", "v", "flat")):
+            assert same_bits(np_bits(got), np_bits(want)), f"thread {i} {name}: {first_diff(np_bits(got), np_bits(want))}"
+    assert same_bits(np_bits(batch_flat), np_bits(ref[3]))
+    assert same_bits(np_bits(ref[3]), oracle.unshard_bf16([np_f32(s) for s in shards]))
+    batch.close()
