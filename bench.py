@@ -134,6 +134,7 @@ def load_probe():
     lib = ctypes.CDLL(build_probe(force=False))
     vp, i64 = ctypes.c_void_p, ctypes.c_int64
     lib.fsdp_probe_copy.argtypes = [vp, vp, i64, vp]
+    lib.fsdp_probe_memcpy.argtypes = [vp, vp, i64, vp]
     lib.fsdp_probe_read.argtypes = [vp, i64, vp, vp]
     lib.fsdp_probe_write.argtypes = [vp, i64, ctypes.c_float, vp]
     lib.fsdp_probe_streams.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, ctypes.c_int, vp, vp]
@@ -173,9 +174,11 @@ def measure_ceilings(torch):
                                                              st)), 2 * nbytes),
         "read_GBps": timed(lambda i: chk(lib.fsdp_probe_read(bufs[i % 4].data_ptr(), nbytes, sink.data_ptr(), st)), nbytes),
         "write_GBps": timed(lambda i: chk(lib.fsdp_probe_write(bufs[i % 4].data_ptr(), nbytes, 0.0, st)), nbytes),
+        "hipMemcpyAsync_d2d_GBps": timed(lambda i: chk(lib.fsdp_probe_memcpy(bufs[(i + 1) % 4].data_ptr(), bufs[i % 4].data_ptr(),
+                                                                             nbytes, st)), 2 * nbytes),
         "buffer_bytes": nbytes,
-        "note": "plain nontemporal streaming kernels of bench_probe.hip, same run, HIP events; copy counts bytes read + "
-                "bytes written",
+        "note": "plain nontemporal streaming kernels of bench_probe.hip and the runtime's own device-to-device copy, same "
+                "run, HIP events; the copies count bytes read + bytes written",
     }
     assert float(sink.item()) == 0.0
     del bufs
@@ -947,7 +950,7 @@ def main():
     ceilings = None if args.no_ceilings else measure_ceilings(torch)
     if ceilings:
         log(f"[bench] ceilings of this box: copy {ceilings['copy_GBps']} GB/s, read-only {ceilings['read_GBps']} GB/s, "
-            f"write-only {ceilings['write_GBps']} GB/s")
+            f"write-only {ceilings['write_GBps']} GB/s; hipMemcpyAsync device-to-device {ceilings['hipMemcpyAsync_d2d_GBps']} GB/s")
 
     head = next(r for r in records if r["workload"] == workloads.config(head_cfg).name)
     roofline = None
@@ -1009,7 +1012,8 @@ def compact(out):
     line["config"] = {k: out["config"][k] for k in ("workload", "units", "world_size", "grad_dtype", "mode",
                                                     "launches_per_step", "alg_bytes_per_step", "touched_bytes_per_step")}
     if out["measured_ceilings"]:
-        line["measured_ceilings"] = {k: out["measured_ceilings"][k] for k in ("copy_GBps", "read_GBps", "write_GBps")}
+        line["measured_ceilings"] = {k: out["measured_ceilings"][k] for k in ("copy_GBps", "read_GBps", "write_GBps",
+                                                                                 "hipMemcpyAsync_d2d_GBps")}
     line["kernels"] = kern(out["kernels"])
     if out["units_table"]:
         line["units_table"] = [{k: (v["reduce_scatter+adam"] if k == "parity" and isinstance(v, dict) else v)

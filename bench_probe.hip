@@ -171,3 +171,11 @@ extern "C" int fsdp_probe_update(const void* const* streams, int n, int64_t nbyt
                        static_cast<hipStream_t>(hip_stream), t, n, nvec, p, m, v);
     return static_cast<int>(hipGetLastError());
 }
+
+// The runtime's own device-to-device copy of the same buffers, for comparison with the copy kernel above.
+extern "C" int fsdp_probe_memcpy(void* dst, const void* src, int64_t nbytes, void* hip_stream)
+{
+    if (bad_buffer(dst, nbytes) || bad_buffer(src, nbytes)) return static_cast<int>(hipErrorInvalidValue);
+    return static_cast<int>(hipMemcpyAsync(dst, src, static_cast<size_t>(nbytes), hipMemcpyDeviceToDevice,
+                                           static_cast<hipStream_t>(hip_stream)));
+}
