@@ -978,7 +978,7 @@ def main():
             "parity": cpu.get("parity_first_step") if cpu else None,
         }]
     out = {
-        "metric": "effective HBM GB/s per FSDP unit pass: unshard + reduce-scatter + Adam",
+        "metric": "effective HBM GB/s (and % of peak) per FSDP unit: unshard + reduce-scatter + Adam",
         "value": head["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(head["us_per_step"] / 1e3, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
