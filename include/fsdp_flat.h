@@ -274,7 +274,7 @@ int fsdp_grad_scaler_update(float* scale, int32_t* growth_tracker, const float* 
 
 /* ---- batches of independent operations in few launches ----------------------
  * For units as small as a transformer block one kernel launch costs about as
- * much as a third of the data movement (an empty kernel takes ~2 us back to
+ * much as a third of the data movement (an empty kernel takes ~3 us back to
  * back on MI355X), which is the paper's point about many small collectives
  * (Sec. 3.2.1).  A batch records fused reduce-scatter + Adam operations and
  * unshards that do NOT depend on each other (e.g. the updates of units i..i+2
