@@ -107,7 +107,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (timing and parity)")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the plain copy / read / write kernels")
-    ap.add_argument("--detail-json", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"),
+    ap.add_argument("--detail-json", default=os.path.join(ROOT, "bench_detail.json"),
                     help="file that receives every figure of the run (the line on stdout is a compact view); '' = none")
     ap.add_argument("--verbose", action="store_true", help="log per-kernel and per-unit lines as they are measured")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
