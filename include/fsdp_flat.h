@@ -204,7 +204,8 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* layout, const
  * out[k] = (inner_0 + inner_1 + ... ) / post in group order (eq. (1): the sum
  * over all ranks as a sum over groups of group sums; in binary32 this two-level
  * order is its own result).  num_groups = 1 equals fsdp_reduce_scatter_local bit
- * for bit.  Requires num_groups * F <= FSDP_MAX_RANKS_PER_LAUNCH. */
+ * for bit.  Requires F <= FSDP_MAX_RANKS_PER_LAUNCH; more ranks in total than
+ * that are taken as several launches of whole groups, with the same bits. */
 int fsdp_reduce_scatter_hybrid(const fsdp_layout_t* layout, const void* const* grad_ptrs,
                                fsdp_dtype_t grad_dtype, int32_t num_groups, int32_t rank,
                                float pre_div, float post_div, float* grad_shard_out, void* hip_stream);
@@ -248,7 +249,6 @@ int fsdp_unshard_lp(const fsdp_layout_t* layout, const void* const* lp_shard_ptr
  * of the result: if it is Inf or NaN, *found_inf = 1.0f (the flag is only ever
  * set, the caller clears it before the first unit); then it is multiplied by
  * inv_scale (= 1 / scale, finite, > 0) and stored.  found_inf: dev, one float.
- * Requires W <= FSDP_MAX_RANKS_PER_LAUNCH.
  * fsdp_found_inf_combine: the all-reduce (max) of the ranks' flags:
  * found_inf_ptrs is a host array of num_ranks (<= 64) dev flags, each of which
  * receives the maximum.  (Simulated ranks may also simply share one flag.)

@@ -204,8 +204,15 @@ int reduce_driver(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dty
                   const AdamConsts& adam, hipStream_t st, const ReduceOpts& opt = ReduceOpts())
 {
     const int32_t W = L->world_size * opt.num_groups;
-    // these variants keep their state in one launch
-    if ((opt.num_groups > 1 || opt.accumulate || opt.unscale) && W > kMaxRanks) return FSDP_ERR_INVALID_ARG;
+    // Accumulation needs the old value of out[] until the end, so it cannot carry a partial sum there.
+    if (opt.accumulate && W > kMaxRanks) return FSDP_ERR_INVALID_ARG;
+    // More ranks than one launch takes: several launches, the partial sum carried in out[].  With hybrid
+    // groups a launch takes whole groups, so that only the sum over the groups is carried.
+    int32_t per_launch = kMaxRanks;
+    if (opt.num_groups > 1) {
+        if (L->world_size > kMaxRanks) return FSDP_ERR_INVALID_ARG;
+        per_launch = kMaxRanks / L->world_size * L->world_size;
+    }
     const int64_t S = L->S;
     const int64_t esz = dtype_size(grad_dtype);
     if (!grid_ok(ceil_div(S / 4 + 1, kBlock))) return FSDP_ERR_OVERFLOW;
@@ -219,8 +226,8 @@ int reduce_driver(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dty
     int32_t post_mul = 0;
     if (is_pow2_float(post, &recip)) { post_mul = 1; post_c = recip; }
 
-    for (int32_t w0 = 0; w0 < W; w0 += kMaxRanks) {
-        const int32_t nw = W - w0 < kMaxRanks ? W - w0 : kMaxRanks;
+    for (int32_t w0 = 0; w0 < W; w0 += per_launch) {
+        const int32_t nw = W - w0 < per_launch ? W - w0 : per_launch;
         PtrTable tab = {};
         for (int32_t j = 0; j < nw; ++j)
             tab.p[j] = static_cast<const char*>(grad_ptrs[w0 + j]) + static_cast<int64_t>(rank) * S * esz;
@@ -231,7 +238,7 @@ int reduce_driver(const fsdp_layout_t* L, const void* const* grad_ptrs, fsdp_dty
         a.last = w0 + nw == W;
         a.group = opt.num_groups > 1 ? L->world_size : 0;
         a.accum = opt.accumulate ? 1 : 0;
-        a.unscale = opt.unscale ? 1 : 0;
+        a.unscale = opt.unscale && a.last ? 1 : 0;     // the check and the unscaling act on the finished sum
         a.inv_scale = opt.inv_scale;
         a.found_inf = opt.found_inf;
         a.pre_c = pre_c;

@@ -58,7 +58,8 @@ __device__ __forceinline__ float load_grad(const void* base, int64_t k)
 
 struct RsArgs {
     int32_t W;            // ranks in this launch's table
-    int32_t cont;         // 1: accumulator continues from out[] (a later launch of a split W)
+    int32_t cont;         // 1: the sum continues from out[] (a later launch of a split W; with hybrid groups the
+                          // launches split between groups and out[] carries the sum over the groups so far)
     int32_t last;         // 1: apply the post divide (and Adam) in this launch
     int32_t post_mul;     // 1: post is a power of two, post_c holds its exact reciprocal
     int32_t group;        // hybrid sharding: ranks per sharded group (inner sums are folded into an
@@ -209,18 +210,22 @@ __device__ __forceinline__ void reduce_body(const void* const* grads, const RsAr
         int32_t cnt = 0;
 #pragma unroll
         for (int j = 0; j < C; ++j) {
-            if (cont) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                acc[j][e] = -0.0f;
+                outer[j][e] = -0.0f;
+            }
+            if (cont) {   // the carried partial sum: the flat sum, or with hybrid groups the sum over the groups so far
 #pragma unroll
                 for (int q = 0; q < Q; ++q) {
                     const f32x4 t = *reinterpret_cast<const f32x4_a4*>(a.out + k[j] + 4 * q);
-                    acc[j][4 * q] = t.x; acc[j][4 * q + 1] = t.y; acc[j][4 * q + 2] = t.z; acc[j][4 * q + 3] = t.w;
+                    if (group > 0) {   // uniform
+                        outer[j][4 * q] = t.x; outer[j][4 * q + 1] = t.y; outer[j][4 * q + 2] = t.z; outer[j][4 * q + 3] = t.w;
+                    } else {
+                        acc[j][4 * q] = t.x; acc[j][4 * q + 1] = t.y; acc[j][4 * q + 2] = t.z; acc[j][4 * q + 3] = t.w;
+                    }
                 }
-            } else {
-#pragma unroll
-                for (int e = 0; e < E; ++e) acc[j][e] = -0.0f;
             }
-#pragma unroll
-            for (int e = 0; e < E; ++e) outer[j][e] = -0.0f;
         }
 
         // The optimizer state (and the accumulated gradient) of the lane's chunks:
@@ -328,8 +333,8 @@ __device__ __forceinline__ void reduce_body(const void* const* grads, const RsAr
         if (t < nrag) {
             const int64_t k = t < head ? t : tail0 + (t - head);
             const float old_r = accum ? a.out[k] : 0.0f;
-            float r = cont ? a.out[k] : -0.0f;
-            float outer_r = -0.0f;
+            float r = cont && group == 0 ? a.out[k] : -0.0f;
+            float outer_r = cont && group > 0 ? a.out[k] : -0.0f;
             int32_t cnt = 0;
             for (int32_t w = 0; w < W; ++w) {
                 r = r + pre_scale<PRE>(load_grad<GT>(grads[w], k), a.pre_c);

@@ -224,7 +224,13 @@ def test_compute_entry_points_reject_bad_arguments_before_launch(L):
     assert hy(h, good8, 5, 2, 0, f(2), f(4), buf, st) == BAD_DTYPE
     assert hy(h, _table([0x10000 + 64 * i for i in range(7)] + [None]), 0, 2, 0, f(2), f(4), buf, st) == NULL
     many68 = _table([0x10000 + 64 * i for i in range(68)])
-    assert hy(h, many68, 0, 17, 0, f(2), f(34), buf, st) == INVALID          # 17 groups x 4 ranks > 64
+    # more ranks than one launch takes are split between sharded groups; a group larger than a launch cannot be
+    rc65, h65 = _init(raw, [(4, 3), (3,)], 65)
+    assert rc65 == OK
+    many130 = _table([0x10000 + 64 * i for i in range(130)])
+    assert hy(h65, many130, 0, 2, 0, f(2), f(65), buf, st) == INVALID        # sharded groups of 65 ranks
+    assert raw.fsdp_reduce_scatter_accumulate(h65, many130, 0, 0, f(5), f(13), buf, st) == INVALID   # 65 ranks, one launch only
+    raw.fsdp_layout_destroy(h65)
     ra = raw.fsdp_reduce_scatter_accumulate
     assert ra(h, good4, 0, 0, f(2), f(2), None, st) == NULL
     assert ra(h, good4, 0, 9, f(2), f(2), buf, st) == RANK_RANGE

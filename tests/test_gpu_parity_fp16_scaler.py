@@ -144,6 +144,45 @@ def test_reduce_scatter_unscale_and_sharded_flag(F, bad):
         assert_adam_bits(np_f32(p), np_f32(m), np_f32(v), rp, rm, rv)
 
 
+@pytest.mark.parametrize("gdt", ["f16", "bf16"])
+def test_reduce_scatter_unscale_over_more_ranks_than_one_launch(F, gdt):
+    """W = 100: the sum is carried over two launches and the check and the
+    unscaling act on the finished sum.  An Inf sits in rank 80's buffer inside
+    rank 3's slice; with bf16 gradients ranks 10 and 88 hold 3e38 at one
+    position of rank 99's slice, so the fp32 sum overflows in the second launch."""
+    unit = workloads.ragged_unit()
+    W = 100
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S, P, N = lay.shard, lay.padded, lay.numel
+    pre, post = 1.0, 100.0
+    inv = float(np.float32(1.0 / 512.0))
+    if gdt == "f16":
+        grads = make_f16_grads(W, P, N, 190, scale=512.0)
+    else:
+        grads = [workloads.gen_rank_grad(P, N, w, 3, "bf16", device="cuda", std=0.5) for w in range(W)]
+    grads[80][3 * S + min(5, S - 1)] = float("inf")
+    if gdt == "bf16":
+        for w in (10, 88):
+            grads[w][99 * S] = 3.0e38
+    host = [np_bits(g) for g in grads]
+    reduce_slices = oracle.reduce_slices_f16 if gdt == "f16" else oracle.reduce_slices
+    seen = []
+    for r in (0, 3, 99):
+        out = carve(S, torch.float32, r % 3, fill=POISON32)
+        flag = torch.zeros(1, device="cuda")
+        F.fsdp_reduce_scatter_unscale(lay, grads, r, pre, post, inv, out, flag)
+        torch.cuda.synchronize()
+        red = reduce_slices([h[r * S:(r + 1) * S] for h in host], pre, post)
+        ref_g, ref_f = oracle.unscale_check(red, inv)
+        got = np_bits(out)
+        fin = np.isfinite(ref_g)
+        assert same_bits(got[fin], ref_g.view(np.uint32)[fin]), f"rank {r}: {first_diff(got[fin], ref_g.view(np.uint32)[fin])}"
+        assert np.array_equal(np_f32(out)[~fin], ref_g[~fin], equal_nan=True)
+        assert float(flag.item()) == ref_f, r
+        seen.append(ref_f)
+    assert seen == ([0.0, 1.0, 0.0] if gdt == "f16" else [0.0, 1.0, 1.0])
+
+
 def test_grad_scaler_update_sequence(F):
     rng = np.random.default_rng(3)
     scale = torch.tensor([65536.0], device="cuda")

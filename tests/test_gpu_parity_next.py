@@ -21,7 +21,10 @@ def F():
 
 @pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("G,Fs,pre,post", [(1, 8, 4.0, 2.0), (2, 8, 4.0, 4.0), (4, 2, 2.0, 4.0), (3, 4, 4.0, 3.0),
-                                           (8, 8, 8.0, 8.0), (2, 3, 1.0, 6.0), (5, 1, 1.0, 5.0), (16, 4, 8.0, 8.0)])
+                                           (8, 8, 8.0, 8.0), (2, 3, 1.0, 6.0), (5, 1, 1.0, 5.0), (16, 4, 8.0, 8.0),
+                                           # more than 64 ranks: several launches of whole groups
+                                           (16, 8, 16.0, 8.0), (3, 40, 8.0, 15.0), (2, 64, 8.0, 16.0), (70, 1, 7.0, 10.0),
+                                           (9, 12, 4.0, 27.0)])
 def test_hybrid_reduce_scatter_bit_exact(F, gdt, G, Fs, pre, post):
     unit = big_unit() if G * Fs <= 16 else workloads.ragged_unit()
     lay = F.fsdp_layout_init(unit.shapes, Fs)            # sharding factor F, world = G * F ranks
@@ -52,12 +55,12 @@ def test_hybrid_order_witness_on_gpu(F):
     assert bool((out == 0.0).all())
 
 
-def test_hybrid_rejects_too_many_ranks(F):
-    lay = F.fsdp_layout_init([(100,)], 8)
-    grads = [torch.zeros(lay.padded, device="cuda") for _ in range(72)]
+def test_hybrid_rejects_a_group_larger_than_one_launch(F):
+    lay = F.fsdp_layout_init([(100,)], 65)
+    grads = [torch.zeros(lay.padded, device="cuda") for _ in range(130)]
     out = torch.empty(lay.shard, device="cuda")
     with pytest.raises(F.FsdpError) as e:
-        F.fsdp_reduce_scatter_hybrid(lay, grads, 9, 0, 1.0, 1.0, out)
+        F.fsdp_reduce_scatter_hybrid(lay, grads, 2, 0, 1.0, 1.0, out)
     assert e.value.status == -1
 
 
