@@ -250,8 +250,8 @@ int fsdp_unshard_lp(const fsdp_layout_t* layout, const void* const* lp_shard_ptr
  * set, the caller clears it before the first unit); then it is multiplied by
  * inv_scale (= 1 / scale, finite, > 0) and stored.  found_inf: dev, one float.
  * fsdp_found_inf_combine: the all-reduce (max) of the ranks' flags:
- * found_inf_ptrs is a host array of num_ranks (<= 64) dev flags, each of which
- * receives the maximum.  (Simulated ranks may also simply share one flag.)
+ * found_inf_ptrs is a host array of num_ranks dev flags, each of which
+ * receives the maximum (more than FSDP_MAX_RANKS_PER_LAUNCH flags take several launches).  (Simulated ranks may also simply share one flag.)
  * fsdp_shard_adam_step_guarded: fsdp_shard_adam_step that reads *found_inf on
  * the device and leaves p, m, v untouched when it is non-zero.
  * fsdp_grad_scaler_update: dynamic loss scaling on the device: *found_inf != 0

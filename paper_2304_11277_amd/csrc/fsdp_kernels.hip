@@ -676,16 +676,38 @@ int fsdp_reduce_scatter_unscale(const fsdp_layout_t* L, const void* const* grad_
 int fsdp_found_inf_combine(float* const* found_inf_ptrs, int32_t num_ranks, void* hip_stream)
 {
     if (!found_inf_ptrs) return FSDP_ERR_NULL_PTR;
-    if (num_ranks <= 0 || num_ranks > kMaxRanks) return FSDP_ERR_INVALID_ARG;
-    FlagTable tab = {};
+    if (num_ranks <= 0) return FSDP_ERR_INVALID_ARG;
     for (int32_t i = 0; i < num_ranks; ++i) {
         if (!found_inf_ptrs[i]) return FSDP_ERR_NULL_PTR;
         if (misaligned(found_inf_ptrs[i], 4)) return FSDP_ERR_INVALID_ARG;
-        tab.p[i] = found_inf_ptrs[i];
     }
-    hipLaunchKernelGGL(found_inf_combine_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), tab,
-                       num_ranks);
-    return launch_status();
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    // one launch: every flag of the table (an optional carried flag, then `count` of the caller's from `first` on)
+    // becomes the maximum over the table
+    auto combine = [&](float* carried, int32_t first, int32_t count) {
+        FlagTable tab = {};
+        int32_t k = 0;
+        if (carried) tab.p[k++] = carried;
+        for (int32_t i = 0; i < count; ++i) tab.p[k++] = found_inf_ptrs[first + i];
+        hipLaunchKernelGGL(found_inf_combine_kernel, dim3(1), dim3(64), 0, st, tab, k);
+        return launch_status();
+    };
+    if (num_ranks <= kMaxRanks) return combine(nullptr, 0, num_ranks);
+    // More flags than one table holds: a forward sweep in which each table also holds a flag of the table before
+    // (the running maximum), then a backward sweep that hands the last table's result to the earlier ones.
+    const int32_t per = kMaxRanks - 1;
+    int32_t last_first = 0;
+    for (int32_t first = 0; first < num_ranks; first += per) {
+        const int32_t count = num_ranks - first < per ? num_ranks - first : per;
+        const int rc = combine(first > 0 ? found_inf_ptrs[first - per] : nullptr, first, count);
+        if (rc != FSDP_OK) return rc;
+        last_first = first;
+    }
+    for (int32_t first = last_first - per; first >= 0; first -= per) {
+        const int rc = combine(found_inf_ptrs[last_first], first, per);
+        if (rc != FSDP_OK) return rc;
+    }
+    return FSDP_OK;
 }
 
 int fsdp_grad_scaler_update(float* scale, int32_t* growth_tracker, const float* found_inf, float growth_factor,

@@ -253,7 +253,9 @@ def test_compute_entry_points_reject_bad_arguments_before_launch(L):
     assert us(h, good4, 2, 0, f(2), f(2), f(0.5), buf, ctypes.c_void_p(0x60002), st) == INVALID
     assert raw.fsdp_found_inf_combine(None, 4, st) == NULL
     assert raw.fsdp_found_inf_combine(good4, 0, st) == INVALID
-    assert raw.fsdp_found_inf_combine(many68, 65, st) == INVALID
+    assert raw.fsdp_found_inf_combine(_table([0x10000 + 64 * i for i in range(66)] + [None, 0x20000]), 68, st) == NULL
+    assert raw.fsdp_found_inf_combine(_table([0x10000 + 64 * i for i in range(66)] + [0x20002]), 67, st) == INVALID
+    assert raw.fsdp_found_inf_combine(many68, -1, st) == INVALID
     assert raw.fsdp_found_inf_combine(with_null, 4, st) == NULL
     assert raw.fsdp_shard_adam_step_guarded(h, p, g, m, v, i64(1), *ok_h, None, st) == NULL
     assert raw.fsdp_shard_adam_step_guarded(h, p, g, m, v, i64(0), *ok_h, flag, st) == INVALID

@@ -183,6 +183,19 @@ def test_reduce_scatter_unscale_over_more_ranks_than_one_launch(F, gdt):
     assert seen == ([0.0, 1.0, 0.0] if gdt == "f16" else [0.0, 1.0, 1.0])
 
 
+@pytest.mark.parametrize("n,set_at", [(150, [140]), (150, [3]), (150, []), (64, [63]), (65, [64]), (127, [0, 126]), (1, [0])])
+def test_found_inf_combine_over_any_number_of_ranks(F, n, set_at):
+    """The all-reduce of the ranks' flags, also for more flags than one launch takes."""
+    flags = [torch.zeros(1, device="cuda") for _ in range(n)]
+    for i in set_at:
+        flags[i].fill_(1.0)
+    F.fsdp_found_inf_combine(flags)
+    torch.cuda.synchronize()
+    want = oracle.found_inf_combine([1.0 if i in set_at else 0.0 for i in range(n)])
+    assert want == (1.0 if set_at else 0.0)
+    assert [float(f.item()) for f in flags] == [want] * n
+
+
 def test_grad_scaler_update_sequence(F):
     rng = np.random.default_rng(3)
     scale = torch.tensor([65536.0], device="cuda")
