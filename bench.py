@@ -865,10 +865,14 @@ def next_rows(args, wl, F, torch, workloads):
         d["flat16"] = torch.empty(P, dtype=torch.float16, device="cuda")
         d["flat32"] = torch.empty(P, dtype=torch.float32, device="cuda")
         d["flag"] = torch.zeros(1, device="cuda")
+        d["p"], d["m"], d["v"] = (torch.zeros(S, device="cuda") for _ in range(3))
         sets.append(d)
     rows = {
         "reduce_scatter_hybrid": (lambda d: F.fsdp_reduce_scatter_hybrid(lay, d["grads"], G, 0, pre, post, d["out"]),
                                   gb * S * W * G + 4 * S),
+        "reduce_scatter_hybrid_adam_fused": (lambda d: F.fsdp_reduce_scatter_hybrid_adam_fused(
+            lay, d["grads"], G, 0, pre, post, None, d["p"], d["m"], d["v"], 2, wl.lr, wl.beta1, wl.beta2, wl.eps, None),
+                                             gb * S * W * G + 4 * S + 28 * S),
         "reduce_scatter_accumulate": (lambda d: F.fsdp_reduce_scatter_accumulate(lay, d["flat"], 0, pre, post, d["out"]),
                                       gb * P + 8 * S),
         "grad_accumulate": (lambda d: F.fsdp_grad_accumulate(lay, d["acc"], d["flat"].tensors[0]), (8 + gb) * P),

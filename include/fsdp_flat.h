@@ -209,6 +209,18 @@ int fsdp_reduce_scatter_adam_prefetch_unshard(const fsdp_layout_t* layout, const
 int fsdp_reduce_scatter_hybrid(const fsdp_layout_t* layout, const void* const* grad_ptrs,
                                fsdp_dtype_t grad_dtype, int32_t num_groups, int32_t rank,
                                float pre_div, float post_div, float* grad_shard_out, void* hip_stream);
+/* The same reduction with the sharded Adam step (Sec. 5.4) applied to the result
+ * while it is in registers: what fsdp_reduce_scatter_adam_fused is to
+ * fsdp_reduce_scatter_local, with the same outputs, options and bits as
+ * fsdp_reduce_scatter_hybrid followed by fsdp_shard_adam_step.  grad_shard_out
+ * may be NULL unless num_groups * F > FSDP_MAX_RANKS_PER_LAUNCH (it then carries
+ * the sum over the groups between launches); p_lp_out may be NULL. */
+int fsdp_reduce_scatter_hybrid_adam_fused(const fsdp_layout_t* layout, const void* const* grad_ptrs,
+                                          fsdp_dtype_t grad_dtype, int32_t num_groups, int32_t rank,
+                                          float pre_div, float post_div, float* grad_shard_out,
+                                          float* p_shard, float* exp_avg, float* exp_avg_sq, int64_t step,
+                                          float lr, float beta1, float beta2, float eps, void* p_lp_out,
+                                          void* hip_stream);
 
 /* ---- Sec. 3.3.4 gradient accumulation --------------------------------------
  * With communication: every micro-batch is reduce-scattered and added to the

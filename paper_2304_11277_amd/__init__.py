@@ -27,6 +27,7 @@ from .binding import (  # noqa: F401
     fsdp_grad_accumulate,
     fsdp_reduce_scatter_accumulate,
     fsdp_reduce_scatter_hybrid,
+    fsdp_reduce_scatter_hybrid_adam_fused,
     fsdp_reduce_scatter_local,
     fsdp_reduce_scatter_unscale,
     fsdp_shard_adam_step,

@@ -231,6 +231,14 @@ def test_compute_entry_points_reject_bad_arguments_before_launch(L):
     assert hy(h65, many130, 0, 2, 0, f(2), f(65), buf, st) == INVALID        # sharded groups of 65 ranks
     assert raw.fsdp_reduce_scatter_accumulate(h65, many130, 0, 0, f(5), f(13), buf, st) == INVALID   # 65 ranks, one launch only
     raw.fsdp_layout_destroy(h65)
+    hf = raw.fsdp_reduce_scatter_hybrid_adam_fused
+    assert hf(h, good8, 0, 2, 0, f(2), f(4), None, None, m, v, i64(1), *ok_h, None, st) == NULL
+    assert hf(h, None, 0, 2, 0, f(2), f(4), None, p, m, v, i64(1), *ok_h, None, st) == NULL
+    assert hf(h, good8, 0, 0, 0, f(2), f(4), None, p, m, v, i64(1), *ok_h, None, st) == INVALID
+    assert hf(h, good8, 0, 2, 4, f(2), f(4), None, p, m, v, i64(1), *ok_h, None, st) == RANK_RANGE
+    assert hf(h, good8, 0, 2, 0, f(2), f(4), None, p, m, v, i64(0), *ok_h, None, st) == INVALID
+    assert hf(h, good8, 9, 2, 0, f(2), f(4), None, p, m, v, i64(1), *ok_h, None, st) == BAD_DTYPE
+    assert hf(h, many68, 0, 17, 0, f(2), f(34), None, p, m, v, i64(1), *ok_h, None, st) == NULL   # 68 ranks: the shard carries the sum
     ra = raw.fsdp_reduce_scatter_accumulate
     assert ra(h, good4, 0, 0, f(2), f(2), None, st) == NULL
     assert ra(h, good4, 0, 9, f(2), f(2), buf, st) == RANK_RANGE

@@ -45,6 +45,57 @@ def test_hybrid_reduce_scatter_bit_exact(F, gdt, G, Fs, pre, post):
             assert same_bits(np_bits(flat), got)
 
 
+@pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("G,Fs,pre,post,with_outputs", [(2, 8, 4.0, 4.0, True), (4, 4, 4.0, 4.0, False), (3, 5, 1.0, 15.0, True),
+                                                        (16, 8, 16.0, 8.0, True), (3, 40, 8.0, 15.0, True)])
+def test_hybrid_reduce_scatter_fused_with_adam(F, gdt, G, Fs, pre, post, with_outputs):
+    """Sec. 3.2.2 reduction with the Adam step applied in the same launch: the
+    bits of fsdp_reduce_scatter_hybrid followed by fsdp_shard_adam_step, and of
+    the oracle's two steps, at t = 3 from non-zero state."""
+    from gpu_helpers import POISON16, assert_adam_bits
+    unit = big_unit() if G * Fs <= 16 else workloads.ragged_unit()
+    lay = F.fsdp_layout_init(unit.shapes, Fs)
+    S, P, N = lay.shard, lay.padded, lay.numel
+    grads = make_grads(G * Fs, P, N, gdt, 2300 + G * Fs, elem_offset=1)
+    host = [np_grad(g) for g in grads]
+    hp = (1e-4, 0.9, 0.999, 1e-8)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(61)
+    for r in sorted({0, Fs - 1}):
+        p = carve(S, torch.float32, 0)
+        p.normal_(0, 0.02, generator=gen)
+        m = carve(S, torch.float32, 1)
+        m.normal_(0, 1e-3, generator=gen)
+        v = carve(S, torch.float32, 3)
+        v.uniform_(0, 1e-6, generator=gen)
+        p2, m2, v2 = p.clone(), m.clone(), v.clone()
+        h_p, h_m, h_v = np_f32(p).copy(), np_f32(m).copy(), np_f32(v).copy()
+        g_out = carve(S, torch.float32, 2, fill=POISON32) if with_outputs else None
+        lp_out = carve(S, torch.bfloat16, 1, fill=POISON16) if with_outputs else None
+        F.fsdp_reduce_scatter_hybrid_adam_fused(lay, grads, G, r, pre, post, g_out, p, m, v, 3, *hp, lp_out)
+        gs = torch.empty(S, device="cuda")
+        F.fsdp_reduce_scatter_hybrid(lay, grads, G, r, pre, post, gs)
+        F.fsdp_shard_adam_step(lay, p2, gs, m2, v2, 3, *hp)
+        torch.cuda.synchronize()
+        for a, b, name in ((p, p2, "p"), (m, m2, "m"), (v, v2, "v")):
+            assert same_bits(np_bits(a), np_bits(b)), f"rank {r} {name}: {first_diff(np_bits(a), np_bits(b))}"
+        ref_g = oracle.reduce_slices_hybrid([h[r * S:(r + 1) * S] for h in host], G, Fs, pre, post)
+        rp, rm, rv = oracle.adam_f32(h_p, ref_g, h_m, h_v, 3, *hp)
+        assert_adam_bits(np_f32(p), np_f32(m), np_f32(v), rp, rm, rv)
+        if with_outputs:
+            assert same_bits(np_bits(g_out), ref_g.view(np.uint32))
+            assert same_bits(np_bits(lp_out), oracle.cast_bf16(np_f32(p)))
+
+
+def test_hybrid_fused_needs_the_gradient_shard_beyond_one_launch(F):
+    lay = F.fsdp_layout_init([(100,)], 8)
+    grads = [torch.zeros(lay.padded, device="cuda") for _ in range(72)]
+    p, m, v = (torch.zeros(lay.shard, device="cuda") for _ in range(3))
+    with pytest.raises(F.FsdpError) as e:
+        F.fsdp_reduce_scatter_hybrid_adam_fused(lay, grads, 9, 0, 1.0, 1.0, None, p, m, v, 1, 1e-4, 0.9, 0.999, 1e-8, None)
+    assert e.value.status == -2
+
+
 def test_hybrid_order_witness_on_gpu(F):
     """(1e8, 1 | -1e8, 1): group sums first gives 0, flat rank order gives 1."""
     lay = F.fsdp_layout_init([(3000,)], 2)
