@@ -230,6 +230,18 @@ int fsdp_reduce_scatter_hybrid_adam_fused(const fsdp_layout_t* layout, const voi
 int fsdp_reduce_scatter_accumulate(const fsdp_layout_t* layout, const void* const* grad_ptrs,
                                    fsdp_dtype_t grad_dtype, int32_t rank, float pre_div,
                                    float post_div, float* grad_shard_acc, void* hip_stream);
+/* The last micro-batch of an accumulation with communication: the same update
+ * of grad_shard_acc (read and written; it ends holding the whole accumulated
+ * gradient) and, in the same launch, the sharded Adam step (Sec. 5.4) on that
+ * gradient: the bits of fsdp_reduce_scatter_accumulate followed by
+ * fsdp_shard_adam_step.  p_lp_out may be NULL.  Requires
+ * W <= FSDP_MAX_RANKS_PER_LAUNCH. */
+int fsdp_reduce_scatter_accumulate_adam_fused(const fsdp_layout_t* layout, const void* const* grad_ptrs,
+                                              fsdp_dtype_t grad_dtype, int32_t rank, float pre_div,
+                                              float post_div, float* grad_shard_acc, float* p_shard,
+                                              float* exp_avg, float* exp_avg_sq, int64_t step, float lr,
+                                              float beta1, float beta2, float eps, void* p_lp_out,
+                                              void* hip_stream);
 /* Without communication: the rank adds a micro-batch's unsharded gradient to
  * its own unsharded fp32 accumulator, grad_acc[k] = grad_acc[k] + grad_add[k]
  * for the P elements of the flat gradient (grad_add: fp32 or bf16), and

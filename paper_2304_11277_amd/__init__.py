@@ -26,6 +26,7 @@ from .binding import (  # noqa: F401
     fsdp_reduce_scatter_adam_prefetch_unshard,
     fsdp_grad_accumulate,
     fsdp_reduce_scatter_accumulate,
+    fsdp_reduce_scatter_accumulate_adam_fused,
     fsdp_reduce_scatter_hybrid,
     fsdp_reduce_scatter_hybrid_adam_fused,
     fsdp_reduce_scatter_local,

@@ -70,6 +70,8 @@ _SIGNATURES = {
     "fsdp_reduce_scatter_hybrid_adam_fused": [_vp, _pp, ctypes.c_int, _i32, _i32, _f32, _f32, _vp, _vp, _vp, _vp, _i64,
                                               _f32, _f32, _f32, _f32, _vp, _vp],
     "fsdp_reduce_scatter_accumulate": [_vp, _pp, ctypes.c_int, _i32, _f32, _f32, _vp, _vp],
+    "fsdp_reduce_scatter_accumulate_adam_fused": [_vp, _pp, ctypes.c_int, _i32, _f32, _f32, _vp, _vp, _vp, _vp, _i64,
+                                                  _f32, _f32, _f32, _f32, _vp, _vp],
     "fsdp_grad_accumulate": [_vp, _vp, _vp, ctypes.c_int, _vp],
     "fsdp_cast_shard": [_vp, _vp, _vp, ctypes.c_int, _vp],
     "fsdp_reduce_scatter_unscale": [_vp, _pp, ctypes.c_int, _i32, _f32, _f32, _f32, _vp, _vp, _vp],
@@ -411,6 +413,23 @@ def fsdp_reduce_scatter_accumulate(layout: Layout, grad_ptrs, rank: int, pre_div
            lib().fsdp_reduce_scatter_accumulate(layout.handle, tab.array, gdt, int(rank), float(pre_div),
                                                 float(post_div), _vp(grad_shard_acc.data_ptr()),
                                                 _stream_handle(stream)))
+
+
+def fsdp_reduce_scatter_accumulate_adam_fused(layout: Layout, grad_ptrs, rank: int, pre_div: float, post_div: float,
+                                              grad_shard_acc: torch.Tensor, p_shard, exp_avg, exp_avg_sq, step: int,
+                                              lr: float, beta1: float, beta2: float, eps: float,
+                                              p_lp_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    tab, gdt = _grad_table(layout, grad_ptrs)
+    S = layout.shard
+    acc = _dev_tensor(grad_shard_acc, torch.float32, S, "grad_shard_acc")
+    lp = _dev_tensor(p_lp_out, torch.bfloat16, S, "p_lp_out") if p_lp_out is not None else None
+    ptrs = [_dev_tensor(t, torch.float32, S, n) for t, n in
+            ((p_shard, "p_shard"), (exp_avg, "exp_avg"), (exp_avg_sq, "exp_avg_sq"))]
+    _check("fsdp_reduce_scatter_accumulate_adam_fused",
+           lib().fsdp_reduce_scatter_accumulate_adam_fused(layout.handle, tab.array, gdt, int(rank), float(pre_div),
+                                                           float(post_div), _vp(acc), *[_vp(x) for x in ptrs],
+                                                           int(step), float(lr), float(beta1), float(beta2),
+                                                           float(eps), _vp(lp), _stream_handle(stream)))
 
 
 def fsdp_grad_accumulate(layout: Layout, grad_acc: torch.Tensor, grad_add: torch.Tensor, stream=None) -> None:

@@ -611,6 +611,27 @@ int fsdp_reduce_scatter_accumulate(const fsdp_layout_t* L, const void* const* gr
                          nullptr, nullptr, none, static_cast<hipStream_t>(hip_stream), opt);
 }
 
+int fsdp_reduce_scatter_accumulate_adam_fused(const fsdp_layout_t* L, const void* const* grad_ptrs,
+                                              fsdp_dtype_t grad_dtype, int32_t rank, float pre_div, float post_div,
+                                              float* grad_shard_acc, float* p_shard, float* exp_avg, float* exp_avg_sq,
+                                              int64_t step, float lr, float beta1, float beta2, float eps,
+                                              void* p_lp_out, void* hip_stream)
+{
+    int rc = check_reduce_args(L, grad_ptrs, grad_dtype, rank, pre_div, post_div);
+    if (rc != FSDP_OK) return rc;
+    if (!grad_shard_acc || !p_shard || !exp_avg || !exp_avg_sq) return FSDP_ERR_NULL_PTR;
+    rc = check_adam_args(step, lr, beta1, beta2, eps);
+    if (rc != FSDP_OK) return rc;
+    if (misaligned(grad_shard_acc, 4) || misaligned(p_shard, 4) || misaligned(exp_avg, 4) || misaligned(exp_avg_sq, 4) ||
+        (p_lp_out && misaligned(p_lp_out, 2)))
+        return FSDP_ERR_INVALID_ARG;
+    const AdamConsts c = make_adam_consts(step, lr, beta1, beta2, eps);
+    ReduceOpts opt;
+    opt.accumulate = true;
+    return reduce_driver(L, grad_ptrs, grad_dtype, rank, pre_div, post_div, grad_shard_acc, true, p_shard, exp_avg,
+                         exp_avg_sq, static_cast<uint16_t*>(p_lp_out), c, static_cast<hipStream_t>(hip_stream), opt);
+}
+
 int fsdp_grad_accumulate(const fsdp_layout_t* L, float* grad_acc, const void* grad_add, fsdp_dtype_t add_dtype,
                          void* hip_stream)
 {

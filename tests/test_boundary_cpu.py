@@ -243,6 +243,12 @@ def test_compute_entry_points_reject_bad_arguments_before_launch(L):
     assert ra(h, good4, 0, 0, f(2), f(2), None, st) == NULL
     assert ra(h, good4, 0, 9, f(2), f(2), buf, st) == RANK_RANGE
     assert ra(h, good4, 0, 0, f(0), f(2), buf, st) == INVALID
+    raf = raw.fsdp_reduce_scatter_accumulate_adam_fused
+    assert raf(h, good4, 0, 0, f(2), f(2), None, p, m, v, i64(1), *ok_h, None, st) == NULL     # the accumulator is required
+    assert raf(h, good4, 0, 0, f(2), f(2), buf, p, None, v, i64(1), *ok_h, None, st) == NULL
+    assert raf(h, good4, 0, 4, f(2), f(2), buf, p, m, v, i64(1), *ok_h, None, st) == RANK_RANGE
+    assert raf(h, good4, 0, 0, f(2), f(2), buf, p, m, v, i64(0), *ok_h, None, st) == INVALID
+    assert raf(h, good4, 0, 0, f(2), f(2), buf, p, m, v, i64(1), f(1e-4), f(1.0), f(0.999), f(1e-8), None, st) == INVALID
     assert raw.fsdp_cast_shard(None, buf, buf, 1, st) == NULL
     assert raw.fsdp_cast_shard(h, None, buf, 1, st) == NULL
     assert raw.fsdp_cast_shard(h, buf, None, 2, st) == NULL

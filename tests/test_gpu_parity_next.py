@@ -161,6 +161,54 @@ def test_gradient_accumulation_without_communication(F, gdt, off):
     assert same_bits(np_bits(out), oracle.reduce_scatter(h_accs, 2, 2.0, 2.0).view(np.uint32))
 
 
+@pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("W", [1, 3, 8, 12, 64])
+def test_last_micro_batch_accumulates_and_steps_in_one_launch(F, gdt, W):
+    """Two micro-batches accumulated, the third accumulated and followed by the
+    Adam step inside the same launch: the bits of the separate calls and of the
+    oracle's chain, at t = 2 from non-zero state."""
+    from gpu_helpers import POISON16, assert_adam_bits
+    unit = big_unit() if W <= 12 else workloads.ragged_unit()
+    lay = F.fsdp_layout_init(unit.shapes, W)
+    S, P, N = lay.shard, lay.padded, lay.numel
+    pre, post = F.fsdp_default_divide_factors(W)
+    hp = (1e-4, 0.9, 0.999, 1e-8)
+    r = W // 2
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(71 + W)
+    p = carve(S, torch.float32, 0)
+    p.normal_(0, 0.02, generator=gen)
+    m = carve(S, torch.float32, 1)
+    m.normal_(0, 1e-3, generator=gen)
+    v = carve(S, torch.float32, 2)
+    v.uniform_(0, 1e-6, generator=gen)
+    p2, m2, v2 = p.clone(), m.clone(), v.clone()
+    h_p, h_m, h_v = np_f32(p).copy(), np_f32(m).copy(), np_f32(v).copy()
+    acc = carve(S, torch.float32, 3)
+    acc.zero_()
+    acc2 = torch.zeros(S, device="cuda")
+    lp = carve(S, torch.bfloat16, 1, fill=POISON16)
+    h_acc = np.zeros(S, np.float32)
+    for mb in range(3):
+        grads = make_grads(W, P, N, gdt, 2600 + 10 * mb + W)
+        if mb < 2:
+            F.fsdp_reduce_scatter_accumulate(lay, grads, r, pre, post, acc)
+        else:
+            F.fsdp_reduce_scatter_accumulate_adam_fused(lay, grads, r, pre, post, acc, p, m, v, 2, *hp, lp)
+        F.fsdp_reduce_scatter_accumulate(lay, grads, r, pre, post, acc2)
+        torch.cuda.synchronize()
+        h_acc = oracle.accumulate(h_acc, oracle.reduce_scatter([np_grad(g) for g in grads], r, pre, post))
+    F.fsdp_shard_adam_step(lay, p2, acc2, m2, v2, 2, *hp)
+    torch.cuda.synchronize()
+    assert same_bits(np_bits(acc), h_acc.view(np.uint32)), first_diff(np_bits(acc), h_acc.view(np.uint32))
+    assert same_bits(np_bits(acc), np_bits(acc2))
+    for a, b, name in ((p, p2, "p"), (m, m2, "m"), (v, v2, "v")):
+        assert same_bits(np_bits(a), np_bits(b)), f"{name}: {first_diff(np_bits(a), np_bits(b))}"
+    rp, rm, rv = oracle.adam_f32(h_p, h_acc, h_m, h_v, 2, *hp)
+    assert_adam_bits(np_f32(p), np_f32(m), np_f32(v), rp, rm, rv)
+    assert same_bits(np_bits(lp), oracle.cast_bf16(np_f32(p)))
+
+
 def test_accumulate_then_fused_adam_equals_oracle_chain(F):
     """Two accumulated micro-batches followed by the optimizer step at t = 2 from non-zero state."""
     unit = big_unit()
