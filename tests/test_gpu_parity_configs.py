@@ -294,27 +294,38 @@ def test_config_unit_variants_match_oracle(F, cfg, unit_index):
     torch.cuda.synchronize()
     grads[W // 2][k] = saved
     assert float(flag.item()) == 1.0, "a non-finite sum in the last element must set the flag"
-    del acc0, out, ref
-    print("[step] accumulate and unscale bit-exact", flush=True)
-
-    # ---- hybrid sharding: two sharded groups of F ranks (G * F <= 64); the second group holds the same
-    # buffers in reverse rank order, so the inner sums differ between the groups
-    Fs = W if 2 * W <= 64 else 32
-    lay_h = lay if Fs == W else F.fsdp_layout_init(unit.shapes, Fs)
-    Sh = lay_h.shard
-    hg = grads if Fs == W else [g[:lay_h.padded] for g in grads[:Fs]]
-    if lay_h.padded > P:                     # a different sharding factor may pad more than the buffers hold
-        hg = [torch.cat([g, torch.zeros(lay_h.padded - P, dtype=odt, device="cuda")]) for g in grads[:Fs]]
-    table = list(hg) + list(reversed(hg))
-    pre_h, post_h = F.fsdp_default_divide_factors(2 * Fs)
-    out = _poisoned(Sh, torch.float32)
-    F.fsdp_reduce_scatter_hybrid(lay_h, table, 2, r, pre_h, post_h, out)
+    # the last micro-batch of an accumulation: accumulate and step in one launch
+    acc1 = torch.from_numpy(h_acc0).cuda()
+    p4, m4, v4 = shards[r].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
+    F.fsdp_reduce_scatter_accumulate_adam_fused(lay, grads, r, pre, post, acc1, p4, m4, v4, 1, *hp, None)
     torch.cuda.synchronize()
-    sl = [(np_f32 if other == "f32" else np_bits)(g[r * Sh:(r + 1) * Sh]) for g in table]
-    ref = oracle.reduce_slices_hybrid(sl, 2, Fs, pre_h, post_h)
+    ref_acc = oracle.accumulate(h_acc0, ref_g)
+    assert same_bits(np_bits(acc1), ref_acc.view(np.uint32)), "accumulate + Adam: the accumulated gradient"
+    assert_adam_parity(np_f32(p4), np_f32(m4), np_f32(v4), h_shards[r], ref_acc, z, z, 1, hp, "accumulate + Adam")
+    del acc0, acc1, p4, m4, v4, out, ref, ref_acc
+    print("[step] accumulate (also fused with Adam) and unscale bit-exact", flush=True)
+
+    # ---- hybrid sharding: two sharded groups of W ranks (more than 64 ranks in all go out as one launch
+    # per group); the second group holds the same buffers in reverse rank order, so the inner sums differ
+    # between the groups
+    table = list(grads) + list(reversed(grads))
+    pre_h, post_h = F.fsdp_default_divide_factors(2 * W)
+    out = _poisoned(S, torch.float32)
+    F.fsdp_reduce_scatter_hybrid(lay, table, 2, r, pre_h, post_h, out)
+    torch.cuda.synchronize()
+    sl = h_slices + h_slices[::-1]
+    ref = oracle.reduce_slices_hybrid(sl, 2, W, pre_h, post_h)
     assert same_bits(np_bits(out), ref.view(np.uint32)), "hybrid: " + first_diff(np_bits(out), ref.view(np.uint32))
-    print(f"[step] hybrid reduce-scatter (2 groups of {Fs}) bit-exact", flush=True)
-    del grads, hg, table, sl, out, ref, shards, base, h_shards, h_slices
+    # the same reduction with the Adam step in the launch
+    p5, m5, v5 = shards[r].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
+    out2 = _poisoned(S, torch.float32)
+    F.fsdp_reduce_scatter_hybrid_adam_fused(lay, table, 2, r, pre_h, post_h, out2, p5, m5, v5, 1, *hp, None)
+    torch.cuda.synchronize()
+    assert same_bits(np_bits(out2), ref.view(np.uint32)), "hybrid + Adam: the reduced gradient"
+    assert_adam_parity(np_f32(p5), np_f32(m5), np_f32(v5), h_shards[r], ref, z, z, 1, hp, "hybrid + Adam")
+    print(f"[step] hybrid reduce-scatter (2 groups of {W}), alone and fused with Adam, bit-exact", flush=True)
+    del p5, m5, v5, out2
+    del grads, table, sl, out, ref, shards, base, h_shards, h_slices
     gc.collect()
     torch.cuda.empty_cache()
 
