@@ -208,6 +208,14 @@ static void validation_checks()
                   FSDP_ERR_INVALID_ARG);
         }
         CHECK(fsdp_reduce_scatter_hybrid(L, tab.data(), FSDP_F32, 0, 0, 1.0f, 1.0f, out, nullptr) == FSDP_ERR_INVALID_ARG);
+        CHECK(fsdp_reduce_scatter_hybrid_adam_fused(L, tab.data(), FSDP_F32, 0, 0, 1.0f, 1.0f, out, p, m, v, 1, 1e-3f, 0.9f,
+                                                    0.999f, 1e-8f, nullptr, nullptr) == FSDP_ERR_INVALID_ARG);
+        CHECK(fsdp_reduce_scatter_hybrid_adam_fused(L, tab.data(), FSDP_F32, 1, 0, 1.0f, 1.0f, out, p, nullptr, v, 1, 1e-3f,
+                                                    0.9f, 0.999f, 1e-8f, nullptr, nullptr) == FSDP_ERR_NULL_PTR);
+        CHECK(fsdp_reduce_scatter_accumulate_adam_fused(L, tab.data(), FSDP_F32, 0, 1.0f, 1.0f, nullptr, p, m, v, 1, 1e-3f,
+                                                        0.9f, 0.999f, 1e-8f, nullptr, nullptr) == FSDP_ERR_NULL_PTR);
+        CHECK(fsdp_reduce_scatter_accumulate_adam_fused(L, tab.data(), FSDP_F32, 0, 1.0f, 1.0f, out, p, m, v, 0, 1e-3f, 0.9f,
+                                                        0.999f, 1e-8f, nullptr, nullptr) == FSDP_ERR_INVALID_ARG);
         CHECK(fsdp_reduce_scatter_accumulate(L, bad.data(), FSDP_F32, 0, 1.0f, 1.0f, out, nullptr) == FSDP_ERR_NULL_PTR);
         CHECK(fsdp_grad_accumulate(L, nullptr, fake(9), FSDP_F32, nullptr) == FSDP_ERR_NULL_PTR);
         CHECK(fsdp_grad_accumulate(L, out, fake(9), static_cast<fsdp_dtype_t>(3), nullptr) == FSDP_ERR_BAD_DTYPE);
