@@ -100,7 +100,7 @@ def parse_args():
                     help="the rank whose share of the reduce-scatter and of the optimizer step is timed (default 0; "
                          "with a shard size that is not a multiple of 4, other ranks' gradient slices are not "
                          "16-byte aligned)")
-    ap.add_argument("--walk", choices=["auto", "wide", "deep"], default="auto",
+    ap.add_argument("--walk", choices=["auto", "wide", "deep", "half"], default="auto",
                     help="rank walk of the stand-alone reduce-scatter kernels (the layouts' fsdp_layout_init_ex hint)")
     ap.add_argument("--grad-sets", type=int, default=0,
                     help="cap the number of distinct sets of gradient buffers per unit shape (0 = as many as fit)")
@@ -216,7 +216,7 @@ def probe_mix(torch):
     st = torch.cuda.current_stream().cuda_stream
     out = torch.zeros(nbytes // 2, dtype=torch.float32, device="cuda")
     res = {}
-    for n in (2, 4, 8, 16):
+    for n in (1, 2, 4, 8, 16):
         bufs = [torch.zeros(nbytes // 2, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
         tab = (ctypes.c_void_p * n)(*[b.data_ptr() for b in bufs])
 
@@ -240,16 +240,18 @@ def probe_mix(torch):
             rc = lib.fsdp_probe_write(out.data_ptr(), 2 * nbytes, 0.0, st)
             assert rc == 0, rc
 
-        t_r, t_rw, t_w = timed(lambda: run(0)), timed(lambda: run(1)), timed(write_only)
+        t_r, t_rw, t_rw2, t_w = timed(lambda: run(0)), timed(lambda: run(1)), timed(lambda: run(2)), timed(write_only)
         res[f"{n}_streams"] = {
             "read_bytes": n * nbytes, "write_bytes": 2 * nbytes, "reads_only_us": round(t_r, 1),
-            "reads_and_write_us": round(t_rw, 1), "write_only_us": round(t_w, 1),
+            "reads_and_write_us": round(t_rw, 1), "reads_and_strided_write_us": round(t_rw2, 1),
+            "write_only_us": round(t_w, 1),
             "reads_only_GBps": round(n * nbytes / t_r / 1e3, 1),
             "mix_GBps": round((n + 2) * nbytes / t_rw / 1e3, 1),
             "half_duplex_model_us": round(t_r + t_w, 1),
         }
         log(f"[probe-mix] {n} streams: reads alone {t_r:.1f} us ({n * nbytes / t_r / 1e3:.0f} GB/s), with the write "
-            f"{t_rw:.1f} us ({(n + 2) * nbytes / t_rw / 1e3:.0f} GB/s), write alone {t_w:.1f} us")
+            f"{t_rw:.1f} us ({(n + 2) * nbytes / t_rw / 1e3:.0f} GB/s; stores of 32 bytes per lane: {t_rw2:.1f} us), "
+            f"write alone {t_w:.1f} us")
         del bufs
         torch.cuda.empty_cache()
     print(json.dumps({"probe": "read/write mix", "stream_bytes": nbytes, "results": res}), flush=True)
@@ -281,9 +283,14 @@ def probe_update(cfg, F, torch, workloads):
         tab = (ctypes.c_void_p * W)(*[g.data_ptr() for g in grads])          # rank 0's slices start at the buffers' bases
         sets.append((F.PtrArray(grads), state, tab))
 
-    def library(i):
-        tabs, (p, m, v), _ = sets[i % nsets]
-        F.fsdp_reduce_scatter_adam_fused(lay, tabs, 0, pre, post, None, p, m, v, 2, *hp, None)
+    walks = {"auto": F.FSDP_WALK_AUTO, "wide": F.FSDP_WALK_WIDE, "deep": F.FSDP_WALK_DEEP, "half": F.FSDP_WALK_HALF}
+    lays = {name: F.fsdp_layout_init(unit.shapes, W, reduce_walk=hint) for name, hint in walks.items()}
+
+    def library(name):
+        def fn(i):
+            tabs, (p, m, v), _ = sets[i % nsets]
+            F.fsdp_reduce_scatter_adam_fused(lays[name], tabs, 0, pre, post, None, p, m, v, 2, *hp, None)
+        return fn
 
     def plain(i):
         _, (p, m, v), tab = sets[i % nsets]
@@ -306,11 +313,12 @@ def probe_update(cfg, F, torch, workloads):
 
     rounds = []
     for _ in range(3):
-        t_lib, t_plain = timed(library), timed(plain)
-        rounds.append({"library_us": round(t_lib, 1), "plain_us": round(t_plain, 1)})
-        log(f"[probe-update] {wl.name}: library {t_lib:.1f} us ({touched / t_lib / 1e3:.0f} GB/s touched), plain kernel "
-            f"{t_plain:.1f} us ({touched / t_plain / 1e3:.0f} GB/s)")
-    print(json.dumps({"probe": "fused update against a plain kernel with the same traffic", "workload": wl.name,
+        r = {f"library_{name}_us": round(timed(library(name)), 1) for name in walks}
+        r["plain_us"] = round(timed(plain), 1)
+        rounds.append(r)
+        log(f"[probe-update] {wl.name}: " + ", ".join(f"{k[:-3]} {v:.1f} us ({touched / v / 1e3:.0f} GB/s)" for k, v in r.items()))
+    print(json.dumps({"probe": "fused update (the library's choice of rank walk and each walk forced) against a plain kernel "
+                               "with the same traffic", "workload": wl.name,
                       "unit": unit.name, "world_size": W, "touched_bytes": touched, "rotating_sets": nsets,
                       "rounds": rounds}), flush=True)
 
@@ -433,7 +441,7 @@ def make_states(F, wl, units, args, torch, workloads):
     states = []
     grad_budget = 160e9          # bytes of HBM given to the simulated ranks' gradient buffers
     used = 0.0
-    walk = {"auto": F.FSDP_WALK_AUTO, "wide": F.FSDP_WALK_WIDE, "deep": F.FSDP_WALK_DEEP}[args.walk]
+    walk = {"auto": F.FSDP_WALK_AUTO, "wide": F.FSDP_WALK_WIDE, "deep": F.FSDP_WALK_DEEP, "half": F.FSDP_WALK_HALF}[args.walk]
     for i, u in enumerate(units):
         share = None
         need = wl.world_size * sum(workloads.numel(s) for s in u.shapes) * (4 if wl.grad_dtype == "f32" else 2)

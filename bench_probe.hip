@@ -39,8 +39,9 @@ __global__ __launch_bounds__(256) void fsdp_probe_write_kernel(f32x4* __restrict
 // The rank walk's memory traffic with almost no arithmetic around it: every
 // lane reads 16 bytes (8 bf16) at the same offset of each of n streams, in
 // order, sums them in fp32, and (store != 0) writes its 8 sums as fp32, or
-// (store == 0) nothing.  bench.py --probe-mix times both forms: what the same
-// reads cost with and without the small write stream next to them.
+// (store == 0) nothing.  bench.py --probe-mix times the forms: what the same
+// reads cost with and without the small write stream next to them, and what the
+// shape of the stores does to it.
 struct ProbeStreams {
     const uint32_t* p[64];
 };
@@ -60,10 +61,18 @@ __global__ __launch_bounds__(256) void fsdp_probe_streams_kernel(ProbeStreams t,
         acc[4] += __uint_as_float(x.z << 16); acc[5] += __uint_as_float(x.z & 0xFFFF0000u);
         acc[6] += __uint_as_float(x.w << 16); acc[7] += __uint_as_float(x.w & 0xFFFF0000u);
     }
-    // without the store the sums are kept alive by a comparison that zero-filled streams never satisfy
+    // Without the store the sums are kept alive by a comparison that zero-filled streams never satisfy.
+    // store == 1: each of the two store instructions is contiguous across the wave (the lane's two vectors
+    // land 256 vectors apart inside the workgroup's 8 KiB of output; only the traffic matters here);
+    // store == 2: the lane's 32 bytes side by side, so that each store instruction covers every other 16
+    // bytes of its span: the pattern that nontemporal stores handle badly.
     if (store != 0 || acc[0] == 12345.678f) {
-        __builtin_nontemporal_store(f32x4{acc[0], acc[1], acc[2], acc[3]}, reinterpret_cast<f32x4*>(out + c * 8));
-        __builtin_nontemporal_store(f32x4{acc[4], acc[5], acc[6], acc[7]}, reinterpret_cast<f32x4*>(out + c * 8 + 4));
+        f32x4* o = reinterpret_cast<f32x4*>(out) + static_cast<int64_t>(blockIdx.x) * 512;
+        const bool side_by_side = store == 2 || (static_cast<int64_t>(blockIdx.x) + 1) * 256 > nvec;   // or a partial block
+        const int first = side_by_side ? 2 * threadIdx.x : threadIdx.x;
+        const int second = side_by_side ? 2 * threadIdx.x + 1 : 256 + threadIdx.x;
+        __builtin_nontemporal_store(f32x4{acc[0], acc[1], acc[2], acc[3]}, o + first);
+        __builtin_nontemporal_store(f32x4{acc[4], acc[5], acc[6], acc[7]}, o + second);
     }
 }
 

@@ -83,6 +83,10 @@ void fsdp_layout_destroy(fsdp_layout_t* layout);           /* NULL is a no-op */
  *   FSDP_WALK_WIDE: a lane owns one 16-byte chunk (and loads one to four ranks
  *                   at a time, by gradient dtype);
  *   FSDP_WALK_DEEP: a lane owns four chunks and loads one rank at a time;
+ *   FSDP_WALK_HALF: fused updates on 16-bit gradients only (others: as WIDE): a
+ *                   lane owns four elements (an 8-byte load per rank), so that
+ *                   its accesses to p, m, v are contiguous across the wave, in
+ *                   workgroups of 64 lanes;
  *   FSDP_WALK_AUTO (what fsdp_layout_init uses): the library's choice, from
  *                   measurements on MI355X: deep when the shard fills at
  *                   least 360 deep workgroups (1.5 M fp32 or 2.9 M 16-bit
@@ -92,7 +96,7 @@ void fsdp_layout_destroy(fsdp_layout_t* layout);           /* NULL is a no-op */
  * _adam_fused, _hybrid, _accumulate, _unscale, the two-launch form of
  * _prefetch_unshard and a batch's lone large update); kernels that share a grid
  * with an unshard always walk wide.  Any other value: FSDP_ERR_INVALID_ARG. */
-enum { FSDP_WALK_AUTO = 0, FSDP_WALK_WIDE = 1, FSDP_WALK_DEEP = 2 };
+enum { FSDP_WALK_AUTO = 0, FSDP_WALK_WIDE = 1, FSDP_WALK_DEEP = 2, FSDP_WALK_HALF = 3 };
 int fsdp_layout_init_ex(const int64_t* dims, const int32_t* ndims, int32_t num_params,
                         int32_t world_size, int32_t reduce_walk, fsdp_layout_t** out);
 
@@ -345,7 +349,8 @@ typedef enum {
     FSDP_KERNEL_REDUCE = 1,       /* reduce_kernel: one reduce-scatter (+ Adam) */
     FSDP_KERNEL_UNSHARD_LP = 2,   /* unshard_lp_kernel: cast + gather to bf16 / fp16 */
     FSDP_KERNEL_UNSHARD_F32 = 3,  /* unshard_f32_kernel: fp32 gather */
-    FSDP_KERNEL_GATHER_LP = 4     /* gather_lp_kernel: gather of 16-bit shards */
+    FSDP_KERNEL_GATHER_LP = 4,    /* gather_lp_kernel: gather of 16-bit shards */
+    FSDP_KERNEL_UNSHARD_LP_LIGHT = 5  /* unshard_lp_light_kernel: the cast + gather in single-wave workgroups */
 } fsdp_kernel_t;
 int  fsdp_batch_launch_count(const fsdp_batch_t* batch, int32_t* count);
 int  fsdp_batch_launch_info(const fsdp_batch_t* batch, int32_t i, int32_t* kernel, int32_t* n_updates,

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     FSDP_F32,
     FSDP_WALK_AUTO,
     FSDP_WALK_DEEP,
+    FSDP_WALK_HALF,
     FSDP_WALK_WIDE,
     FsdpError,
     Layout,

@@ -20,6 +20,7 @@ FSDP_F16 = 2
 FSDP_WALK_AUTO = 0
 FSDP_WALK_WIDE = 1
 FSDP_WALK_DEEP = 2
+FSDP_WALK_HALF = 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfsdp_flat.so")
@@ -244,7 +245,7 @@ class Layout:
 
 def fsdp_layout_init(shapes: Sequence[Sequence[int]], world_size: int, reduce_walk: Optional[int] = None) -> Layout:
     """fsdp_layout_init, or fsdp_layout_init_ex when a rank-walk hint
-    (FSDP_WALK_AUTO / _WIDE / _DEEP) is given."""
+    (FSDP_WALK_AUTO / _WIDE / _DEEP / _HALF) is given."""
     shapes = [tuple(int(d) for d in s) for s in shapes]
     flat = [d for s in shapes for d in s]
     dims = (_i64 * max(1, len(flat)))(*flat)

@@ -140,6 +140,23 @@ inline bool pairs_with_large_unshard(const fsdp_layout_t* L, int gt)
     return gt == kF32 && L->reduce_walk != FSDP_WALK_DEEP && L->S < kPairMaxShard;
 }
 
+// The half-chunk walk (fused updates on 16-bit gradients, plain launches only): workgroups of kHalfBlock lanes.
+constexpr int kHalfBlock = 64;
+constexpr int32_t kHalf16MaxRanks = 16;
+constexpr int64_t kHalf16MinShard = 1 << 20;
+constexpr int32_t kHalfF32MinRanks = 8;
+constexpr int64_t kHalfF32MinShard = 12 << 20;
+inline bool half_walk_pays(int gt, int32_t W, int64_t S)
+{
+    if (gt == kF32) return W >= kHalfF32MinRanks && S >= kHalfF32MinShard;
+    return W <= kHalf16MaxRanks && S >= kHalf16MinShard;
+}
+// does a plain fused stand-alone update take the half-chunk walk?
+inline bool takes_half(int32_t walk, int gt, int32_t W, int64_t S)
+{
+    return walk == FSDP_WALK_AUTO ? half_walk_pays(gt, W, S) : walk == FSDP_WALK_HALF;
+}
+
 // would a stand-alone reduce kernel of this unit take the deep walk (the layout's hint, else the library's choice)?
 inline bool wants_deep(const fsdp_layout_t* L, int gt)
 {
@@ -161,12 +178,21 @@ void launch_reduce(const PtrTable& tab, const RsArgs& a, int32_t walk, hipStream
 {
     constexpr int B = kReduceBlock;
     constexpr int E = WalkShape<GT, FUSED, false>::E;
+    const bool plain = a.group == 0 && !a.cont && !a.accum && !a.unscale;
+    if constexpr (FUSED) {
+        if (plain && takes_half(walk, GT, a.W, a.S)) {
+            const dim3 grid(static_cast<uint32_t>(ceil_div(a.S / 4 + 1, kHalfBlock * WalkShape<GT, true, false, true>::C)));
+            hipLaunchKernelGGL((reduce_kernel<GT, PRE, true, false, kHalfBlock, true, true>), grid, dim3(kHalfBlock), 0, st,
+                               tab, a);
+            return;
+        }
+    }
     const bool deep = walk == FSDP_WALK_AUTO ? deep_walk_pays(GT, a.W, a.S) : walk == FSDP_WALK_DEEP;
     const dim3 block(B);
     if (deep) {
         const dim3 grid(static_cast<uint32_t>(ceil_div(a.S / E + 1, B * WalkShape<GT, FUSED, true>::C)));
         if constexpr (FUSED) {
-            if (a.group == 0 && !a.cont && !a.accum && !a.unscale) {
+            if (plain) {
                 hipLaunchKernelGGL((reduce_kernel<GT, PRE, true, true, B, true>), grid, block, 0, st, tab, a);
                 return;
             }
@@ -184,6 +210,19 @@ void launch_reduce_pre(int pre_mode, const PtrTable& tab, const RsArgs& a, int32
     if (pre_mode == kPreNone) launch_reduce<GT, kPreNone, FUSED>(tab, a, walk, st);
     else if (pre_mode == kPreMul) launch_reduce<GT, kPreMul, FUSED>(tab, a, walk, st);
     else launch_reduce<GT, kPreDiv, FUSED>(tab, a, walk, st);
+}
+
+// Does the single-wave unshard read every shard with aligned 16-byte loads?  Shard w's loads start `head`
+// elements in, where head brings its slot of the flat buffer to a 128-byte boundary.
+bool light_unshard_fits(const float* const* shard_ptrs, int32_t W, int64_t S, const void* flat_out)
+{
+    if (S / 4 + 1 > 0x7FFFFFFFLL * kLightBlock) return false;       // tiles per shard must fit the grid's x dimension
+    for (int32_t w = 0; w < W; ++w) {
+        const uintptr_t dst = reinterpret_cast<uintptr_t>(flat_out) + static_cast<uintptr_t>(w) * static_cast<uintptr_t>(S) * 2;
+        const uintptr_t head = ((128 - (dst & 127)) & 127) >> 1;
+        if ((reinterpret_cast<uintptr_t>(shard_ptrs[w]) + 4 * head) & 15) return false;
+    }
+    return true;
 }
 
 inline bool valid_dtype(fsdp_dtype_t d) { return d == FSDP_F32 || d == FSDP_BF16 || d == FSDP_F16; }
@@ -365,10 +404,11 @@ int fsdp_unshard(const fsdp_layout_t* L, const float* const* shard_ptrs, void* f
     }
     const bool lp = out_dtype != FSDP_F32;
     if (misaligned(flat_out, lp ? 2 : 4)) return FSDP_ERR_INVALID_ARG;
-    // One destination vector per lane measured fastest on MI355X for the cast
-    // (more, shorter workgroups hide the ramp of small units better).
-    const int64_t vec = lp ? 8 : 4;
-    const int64_t tiles = ceil_div(S / vec + 1, kBlock);
+    // One destination vector per lane.  The cast takes single-wave workgroups
+    // with 8-byte vectors when every shard's 16-byte loads are aligned, else
+    // workgroups of kBlock lanes with 16-byte vectors and an LDS window.
+    const bool light = lp && light_unshard_fits(shard_ptrs, W, S, flat_out);
+    const int64_t tiles = light ? ceil_div(S / 4 + 1, kLightBlock) : ceil_div(S / (lp ? 8 : 4) + 1, kBlock);
     if (!grid_ok(tiles * kMaxRanks)) return FSDP_ERR_OVERFLOW;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
 
@@ -377,7 +417,14 @@ int fsdp_unshard(const fsdp_layout_t* L, const float* const* shard_ptrs, void* f
         PtrTable tab = {};
         for (int32_t j = 0; j < nw; ++j) tab.p[j] = shard_ptrs[w0 + j];
         const dim3 grid(static_cast<uint32_t>(tiles * nw));
-        if (lp) {
+        if (light) {
+            uint16_t* base = static_cast<uint16_t*>(flat_out) + static_cast<int64_t>(w0) * S;
+            const dim3 grid2(static_cast<uint32_t>(tiles), static_cast<uint32_t>(nw));
+            if (out_dtype == FSDP_F16)
+                hipLaunchKernelGGL(unshard_lp_light_kernel<kF16>, grid2, dim3(kLightBlock), 0, st, tab, S, base);
+            else
+                hipLaunchKernelGGL(unshard_lp_light_kernel<kBF16>, grid2, dim3(kLightBlock), 0, st, tab, S, base);
+        } else if (lp) {
             uint16_t* base = static_cast<uint16_t*>(flat_out) + static_cast<int64_t>(w0) * S;
             if (out_dtype == FSDP_F16)
                 hipLaunchKernelGGL(unshard_lp_kernel<kF16>, grid, dim3(kBlock), 0, st, tab, S, base,
@@ -658,17 +705,22 @@ int fsdp_cast_shard(const fsdp_layout_t* L, const float* shard, void* lp_shard_o
     if (!L || !shard || !lp_shard_out) return FSDP_ERR_NULL_PTR;
     if (lp_dtype != FSDP_BF16 && lp_dtype != FSDP_F16) return FSDP_ERR_BAD_DTYPE;
     if (misaligned(shard, 4) || misaligned(lp_shard_out, 2)) return FSDP_ERR_INVALID_ARG;
-    const int64_t tiles = ceil_div(L->S / 8 + 1, kBlock);
+    const bool light = light_unshard_fits(&shard, 1, L->S, lp_shard_out);
+    const int64_t tiles = light ? ceil_div(L->S / 4 + 1, kLightBlock) : ceil_div(L->S / 8 + 1, kBlock);
     if (!grid_ok(tiles)) return FSDP_ERR_OVERFLOW;
     PtrTable tab = {};
     tab.p[0] = shard;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (lp_dtype == FSDP_F16)
-        hipLaunchKernelGGL(unshard_lp_kernel<kF16>, dim3(static_cast<uint32_t>(tiles)), dim3(kBlock), 0, st, tab, L->S,
-                           static_cast<uint16_t*>(lp_shard_out), static_cast<int32_t>(tiles));
+    uint16_t* out = static_cast<uint16_t*>(lp_shard_out);
+    const dim3 grid(static_cast<uint32_t>(tiles));
+    if (light && lp_dtype == FSDP_F16)
+        hipLaunchKernelGGL(unshard_lp_light_kernel<kF16>, grid, dim3(kLightBlock), 0, st, tab, L->S, out);
+    else if (light)
+        hipLaunchKernelGGL(unshard_lp_light_kernel<kBF16>, grid, dim3(kLightBlock), 0, st, tab, L->S, out);
+    else if (lp_dtype == FSDP_F16)
+        hipLaunchKernelGGL(unshard_lp_kernel<kF16>, grid, dim3(kBlock), 0, st, tab, L->S, out, static_cast<int32_t>(tiles));
     else
-        hipLaunchKernelGGL(unshard_lp_kernel<kBF16>, dim3(static_cast<uint32_t>(tiles)), dim3(kBlock), 0, st, tab,
-                           L->S, static_cast<uint16_t*>(lp_shard_out), static_cast<int32_t>(tiles));
+        hipLaunchKernelGGL(unshard_lp_kernel<kBF16>, grid, dim3(kBlock), 0, st, tab, L->S, out, static_cast<int32_t>(tiles));
     return launch_status();
 }
 
@@ -841,6 +893,7 @@ struct fsdp_batch {
         BatchArgs args = {};                 // complete except for the members' Adam constants
         ReduceKind kind = {kF32, kPreNone};
         AdamHyper hyper[kBatchOps] = {};
+        const fsdp_layout_t* u_layout[kBatchOps] = {};   // layouts of the unshard members
         int32_t walk0 = FSDP_WALK_AUTO;      // rank-walk hint of the first reduce member's layout
         int32_t n_ptrs = 0;
         int large_r = 0, large_u = 0;
@@ -916,6 +969,7 @@ static int batch_add_unshard_impl(fsdp_batch_t* b, const fsdp_layout_t* L, const
             (is_large && (g->large_u > 0 || (g->large_r > 0 && !g->pairable))))
             g = b->new_grid();
         g->large_u += is_large ? 1 : 0;
+        g->u_layout[g->args.n_unshard] = L;
         BatchUnshardOp& o = g->args.u[g->args.n_unshard];
         o.ptr0 = g->n_ptrs;
         for (int32_t w = 0; w < W; ++w) g->args.ptrs[g->n_ptrs++] = shard_ptrs[w];
@@ -1039,6 +1093,9 @@ int fsdp_batch_add_reduce_scatter_adam(fsdp_batch_t* b, const fsdp_layout_t* L, 
 }
 
 namespace {
+// a grid whose only member is one unshard goes out through the stand-alone entry point
+inline bool lone_unshard(const fsdp_batch::Grid& g) { return g.args.n_reduce == 0 && g.args.n_unshard == 1; }
+
 // launches of one plan step: (kernel, updates, unshards, workgroups) of launch j of the step; returns the count
 int32_t step_launches(const fsdp_batch_t* b, const fsdp_batch::Step& s, int32_t j, int32_t* kernel, int32_t* n_upd,
                       int32_t* n_uns, int64_t* wgs)
@@ -1050,11 +1107,20 @@ int32_t step_launches(const fsdp_batch_t* b, const fsdp_batch::Step& s, int32_t 
         *n_upd = g.args.n_reduce;
         *n_uns = g.args.n_unshard;
         *wgs = static_cast<int64_t>(g.r_blocks) + g.u_blocks;
+        if (lone_unshard(g)) {   // issued through fsdp_unshard / fsdp_unshard_lp, which choose their own kernel and grid
+            const BatchUnshardOp& o = g.args.u[0];
+            const fsdp_layout_t* UL = g.u_layout[0];
+            const bool light = !o.lp && light_unshard_fits(reinterpret_cast<const float* const*>(g.args.ptrs + o.ptr0),
+                                                           UL->world_size, UL->S, o.out);
+            *kernel = o.lp ? FSDP_KERNEL_GATHER_LP : (light ? FSDP_KERNEL_UNSHARD_LP_LIGHT : FSDP_KERNEL_UNSHARD_LP);
+            *wgs = (light ? ceil_div(UL->S / 4 + 1, kLightBlock) : ceil_div(UL->S / 8 + 1, kBlock)) * UL->world_size;
+        }
         if (lone) {   // the stand-alone kernel sizes its own grid by the rank walk it takes
             const RsArgs& a = g.args.r[0].a;
             const int64_t E = g.kind.gt == kF32 ? 4 : 8;
             const bool deep = g.walk0 == FSDP_WALK_AUTO ? deep_walk_pays(g.kind.gt, a.W, a.S) : g.walk0 == FSDP_WALK_DEEP;
-            *wgs = ceil_div(a.S / E + 1, deep ? kReduceBlock * 4 : kReduceBlock);
+            *wgs = takes_half(g.walk0, g.kind.gt, a.W, a.S) ? ceil_div(a.S / 4 + 1, kHalfBlock * WalkShape<kBF16, true, false, true>::C)
+                                                           : ceil_div(a.S / E + 1, deep ? kReduceBlock * 4 : kReduceBlock);
         }
         return 1;
     }
@@ -1071,10 +1137,15 @@ int32_t step_launches(const fsdp_batch_t* b, const fsdp_batch::Step& s, int32_t 
     const fsdp_batch::UnshardRec& u = b->unshards[s.index];
     const int32_t n = static_cast<int32_t>(ceil_div(u.L->world_size, kMaxRanks));
     const int32_t nw = j + 1 < n ? kMaxRanks : u.L->world_size - j * kMaxRanks;
-    *kernel = u.lp ? FSDP_KERNEL_GATHER_LP : (u.dtype == FSDP_F32 ? FSDP_KERNEL_UNSHARD_F32 : FSDP_KERNEL_UNSHARD_LP);
+    const bool light = !u.lp && u.dtype != FSDP_F32 &&
+                       light_unshard_fits(reinterpret_cast<const float* const*>(u.shards.data()), u.L->world_size, u.L->S, u.out);
+    *kernel = u.lp ? FSDP_KERNEL_GATHER_LP
+                   : (u.dtype == FSDP_F32 ? FSDP_KERNEL_UNSHARD_F32
+                                          : (light ? FSDP_KERNEL_UNSHARD_LP_LIGHT : FSDP_KERNEL_UNSHARD_LP));
     *n_upd = 0;
     *n_uns = 1;
-    *wgs = ceil_div(u.L->S / (!u.lp && u.dtype == FSDP_F32 ? 4 : 8) + 1, kBlock) * nw;
+    *wgs = light ? ceil_div(u.L->S / 4 + 1, kLightBlock) * nw
+                 : ceil_div(u.L->S / (!u.lp && u.dtype == FSDP_F32 ? 4 : 8) + 1, kBlock) * nw;
     return n;
 }
 }  // namespace
@@ -1122,6 +1193,7 @@ const char* fsdp_kernel_name(int32_t kernel)
         case FSDP_KERNEL_UNSHARD_LP: return "unshard_lp_kernel";
         case FSDP_KERNEL_UNSHARD_F32: return "unshard_f32_kernel";
         case FSDP_KERNEL_GATHER_LP: return "gather_lp_kernel";
+        case FSDP_KERNEL_UNSHARD_LP_LIGHT: return "unshard_lp_light_kernel";
         default: return nullptr;
     }
 }
@@ -1158,6 +1230,15 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
                                      hip_stream);
         } else {
             const fsdp_batch::Grid& g = b->grids[s.index];
+            if (lone_unshard(g)) {
+                const BatchUnshardOp& o = g.args.u[0];
+                const fsdp_layout_t* UL = g.u_layout[0];
+                rc = o.lp ? fsdp_unshard_lp(UL, g.args.ptrs + o.ptr0, o.out, hip_stream)
+                          : fsdp_unshard(UL, reinterpret_cast<const float* const*>(g.args.ptrs + o.ptr0), o.out, FSDP_BF16,
+                                         hip_stream);
+                if (rc != FSDP_OK) return rc;
+                continue;
+            }
             BatchArgs a = g.args;
             for (int32_t i = 0; i < a.n_reduce; ++i) a.r[i].a.adam = consts_for(g.hyper[i]);
             if (a.n_reduce == 1 && a.n_unshard == 0 && g.large_r > 0) {

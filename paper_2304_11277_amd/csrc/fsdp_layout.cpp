@@ -53,7 +53,8 @@ int fsdp_layout_init_ex(const int64_t* dims, const int32_t* ndims, int32_t num_p
     *out = nullptr;
     if (!ndims) return FSDP_ERR_NULL_PTR;
     if (num_params <= 0 || world_size <= 0) return FSDP_ERR_INVALID_ARG;
-    if (reduce_walk != FSDP_WALK_AUTO && reduce_walk != FSDP_WALK_WIDE && reduce_walk != FSDP_WALK_DEEP)
+    if (reduce_walk != FSDP_WALK_AUTO && reduce_walk != FSDP_WALK_WIDE && reduce_walk != FSDP_WALK_DEEP &&
+        reduce_walk != FSDP_WALK_HALF)
         return FSDP_ERR_INVALID_ARG;
 
     fsdp_layout* L = new (std::nothrow) fsdp_layout;

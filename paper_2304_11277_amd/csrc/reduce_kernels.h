@@ -105,24 +105,43 @@ __device__ __forceinline__ float post_scale(float x, const RsArgs& a)
 // the last pointer, so loads never need a predicate; the padding's adds are
 // skipped.
 constexpr int kMaxWideRanks = 4;
-template <int GT, bool FUSED, bool DEEP>
+template <int GT, bool FUSED, bool DEEP, bool HALF = false>
 struct WalkShape {
-    static constexpr int E = GT != kF32 ? 8 : 4;
-    static constexpr int G = DEEP ? 1 : (GT == kF32 ? 1 : (FUSED ? kMaxWideRanks : 2));
+    static constexpr int E = (GT != kF32 && !HALF) ? 8 : 4;
+    static constexpr int G = (DEEP || HALF) ? 1 : (GT == kF32 ? 1 : (FUSED ? kMaxWideRanks : 2));
     static constexpr int C = DEEP ? 4 : 1;
     // fetch p, m, v (and the accumulated gradient) before the rank walk rather than after it
-    static constexpr bool kStateFirst = !DEEP && GT != kF32;
+    static constexpr bool kStateFirst = !DEEP && !HALF && GT != kF32;
+    // issue the next batch's loads before the current batch's adds wait for their data
+    static constexpr bool kLookahead = !HALF;
 };
 
-template <int GT, int G, int C>
+// what one rank's load of a chunk returns: 16 bytes, or 8 bytes for a half chunk of 16-bit gradients
+template <int GT, int E>
+struct GradVec {
+    using type = u32x4;
+};
+template <>
+struct GradVec<kBF16, 4> {
+    using type = u32x2;
+};
+template <>
+struct GradVec<kF16, 4> {
+    using type = u32x2;
+};
+
+template <int GT, int G, int C, int E>
 __device__ __forceinline__ void load_batch(const void* const* grads, int32_t w0, const int64_t (&k)[C],
-                                           u32x4 (&x)[G][C])
+                                           typename GradVec<GT, E>::type (&x)[G][C])
 {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
 #pragma unroll
         for (int j = 0; j < C; ++j) {
-            if constexpr (GT != kF32)
+            if constexpr (GT != kF32 && E == 4)
+                x[g][j] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x2_a2*>(static_cast<const uint16_t*>(grads[w0 + g]) + k[j]));
+            else if constexpr (GT != kF32)
                 x[g][j] = __builtin_nontemporal_load(
                     reinterpret_cast<const u32x4_a2*>(static_cast<const uint16_t*>(grads[w0 + g]) + k[j]));
             else
@@ -136,8 +155,8 @@ __device__ __forceinline__ void load_batch(const void* const* grads, int32_t w0,
 // sharding (Sec. 3.2.2): acc is the inner sum of the current sharded group;
 // after every `group` ranks it is folded into outer and restarted at -0.0f.
 template <int GT, int PRE, int G, int C, int E, bool HYBRID>
-__device__ __forceinline__ void add_batch(const u32x4 (&x)[G][C], int32_t n, float pre_c, int32_t group,
-                                          int32_t& cnt, float (&acc)[C][E], float (&outer)[C][E])
+__device__ __forceinline__ void add_batch(const typename GradVec<GT, E>::type (&x)[G][C], int32_t n, float pre_c,
+                                          int32_t group, int32_t& cnt, float (&acc)[C][E], float (&outer)[C][E])
 {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -145,7 +164,10 @@ __device__ __forceinline__ void add_batch(const u32x4 (&x)[G][C], int32_t n, flo
 #pragma unroll
             for (int j = 0; j < C; ++j) {
                 float t[E];
-                if constexpr (GT != kF32) {   // exact upcast of eight 16-bit gradients
+                if constexpr (GT != kF32 && E == 4) {   // exact upcast of four 16-bit gradients
+                    t[0] = up_lo<GT>(x[g][j].x); t[1] = up_hi<GT>(x[g][j].x);
+                    t[2] = up_lo<GT>(x[g][j].y); t[3] = up_hi<GT>(x[g][j].y);
+                } else if constexpr (GT != kF32) {   // exact upcast of eight 16-bit gradients
                     t[0] = up_lo<GT>(x[g][j].x); t[1] = up_hi<GT>(x[g][j].x);
                     t[2] = up_lo<GT>(x[g][j].y); t[3] = up_hi<GT>(x[g][j].y);
                     t[4] = up_lo<GT>(x[g][j].z); t[5] = up_hi<GT>(x[g][j].z);
@@ -181,10 +203,10 @@ __device__ __forceinline__ void add_batch(const u32x4 (&x)[G][C], int32_t n, flo
 // PLAIN instantiations serve the launches that use none of the variants (no
 // hybrid groups, no accumulation, no unscaling, no carried partial sum): the
 // second set of accumulators and the old gradient then take no registers.
-template <int GT, int PRE, bool FUSED, bool DEEP, int B, bool PLAIN>
+template <int GT, int PRE, bool FUSED, bool DEEP, int B, bool PLAIN, bool HALF = false>
 __device__ __forceinline__ void reduce_body(const void* const* grads, const RsArgs& a, uint32_t bid)
 {
-    using Shape = WalkShape<GT, FUSED, DEEP>;
+    using Shape = WalkShape<GT, FUSED, DEEP, HALF>;
     constexpr int E = Shape::E, G = Shape::G, C = Shape::C;
     constexpr int Q = E / 4;
     const int32_t group = PLAIN ? 0 : a.group;
@@ -249,15 +271,22 @@ __device__ __forceinline__ void reduce_body(const void* const* grads, const RsAr
             for (int j = 0; j < C; ++j) fetch_state(j);
         }
 
-        u32x4 xa[G][C], xb[G][C];
+        typename GradVec<GT, E>::type xa[G][C], xb[G][C];
         const int32_t nbatch = (W + G - 1) / G;
-        load_batch<GT, G, C>(grads, 0, k, xa);
+        if constexpr (!Shape::kLookahead) {   // one batch in flight per lane: the occupancy keeps the memory system busy
+            for (int32_t b = 0; b < nbatch; ++b) {
+                load_batch<GT, G, C, E>(grads, b * G, k, xa);
+                add_batch<GT, PRE, G, C, E, !PLAIN>(xa, W - b * G, a.pre_c, group, cnt, acc, outer);
+            }
+        } else {
+        load_batch<GT, G, C, E>(grads, 0, k, xa);
         for (int32_t b = 0; b < nbatch; b += 2) {
             const bool has_b = b + 1 < nbatch;
-            if (has_b) load_batch<GT, G, C>(grads, (b + 1) * G, k, xb);
+            if (has_b) load_batch<GT, G, C, E>(grads, (b + 1) * G, k, xb);
             add_batch<GT, PRE, G, C, E, !PLAIN>(xa, W - b * G, a.pre_c, group, cnt, acc, outer);
-            if (b + 2 < nbatch) load_batch<GT, G, C>(grads, (b + 2) * G, k, xa);
+            if (b + 2 < nbatch) load_batch<GT, G, C, E>(grads, (b + 2) * G, k, xa);
             if (has_b) add_batch<GT, PRE, G, C, E, !PLAIN>(xb, W - (b + 1) * G, a.pre_c, group, cnt, acc, outer);
+        }
         }
 
         if constexpr (!Shape::kStateFirst) fetch_state(0);
@@ -362,10 +391,10 @@ __device__ __forceinline__ void reduce_body(const void* const* grads, const RsAr
     }
 }
 
-template <int GT, int PRE, bool FUSED, bool DEEP, int B, bool PLAIN>
+template <int GT, int PRE, bool FUSED, bool DEEP, int B, bool PLAIN, bool HALF = false>
 __global__ __launch_bounds__(B) void reduce_kernel(PtrTable grads, RsArgs a)
 {
-    reduce_body<GT, PRE, FUSED, DEEP, B, PLAIN>(grads.p, a, blockIdx.x);
+    reduce_body<GT, PRE, FUSED, DEEP, B, PLAIN, HALF>(grads.p, a, blockIdx.x);
 }
 
 // Backward prefetching (Sec. 3.3.2) as one launch: the first n_reduce

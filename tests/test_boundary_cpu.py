@@ -332,11 +332,11 @@ def test_binding_rejects_host_tensors(L):
     assert L.lib().fsdp_status_string(-6) == b"rank or parameter index out of range"
 
 
-def test_layout_init_ex_takes_only_the_three_rank_walks(L):
-    for walk in (L.FSDP_WALK_AUTO, L.FSDP_WALK_WIDE, L.FSDP_WALK_DEEP):
+def test_layout_init_ex_takes_only_the_rank_walks_it_knows(L):
+    for walk in (L.FSDP_WALK_AUTO, L.FSDP_WALK_WIDE, L.FSDP_WALK_DEEP, L.FSDP_WALK_HALF):
         lay = L.fsdp_layout_init([(4, 3), (3,)], 16, reduce_walk=walk)
         assert (lay.numel, lay.shard, lay.padded, lay.pad) == (15, 1, 16, 1)
-    for bad in (-1, 3, 99):
+    for bad in (-1, 4, 99):
         with pytest.raises(L.FsdpError) as e:
             L.fsdp_layout_init([(4, 3)], 2, reduce_walk=bad)
         assert e.value.status == INVALID
@@ -463,14 +463,22 @@ def test_batches_are_planned_while_they_are_recorded(L):
     assert add_update(b, mid, 12) == OK and add_unshard(b, mid, 12) == OK
     assert [p[:3] for p in _plan(raw, b)] == [("batch_kernel", 1, 1)]
     raw.fsdp_batch_clear(b)
-    # the GPT-3-175B block, bf16 gradients: no pairing; the lone update takes the stand-alone kernel and its deep walk
+    # the GPT-3-175B block, bf16 gradients: no pairing; the lone update takes the stand-alone kernel and, with 16
+    # ranks, its half-chunk walk (single-wave workgroups of 256 elements); the lone unshard of aligned shards goes
+    # out as single-wave workgroups too
     rc, big = _init(raw, workloads.config(4).units[0].shapes, 16)
     S = 113256192
     assert add_update(b, big, 16, dt=1) == OK and add_unshard(b, big, 16) == OK
-    assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(S // 8 + 1) // 1024)), ("batch_kernel", 0, 1, 16 * (S // 8 // 256 + 1))]
+    assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(S // 4 + 1) // 64)),
+                             ("unshard_lp_light_kernel", 0, 1, 16 * (-(-(S // 4 + 1) // 64)))]
     raw.fsdp_batch_clear(b)
-    # the library's own choice of walk for a lone large update (measured rule): the Llama-7B block over 64 ranks
-    # takes the deep walk (386 workgroups of 1024 chunks), a 16 M-element shard over 8 ranks the wide one
+    # a lone unshard whose loads would not be 16-byte aligned keeps the kernel that realigns through LDS
+    assert raw.fsdp_batch_add_unshard(b, big, _table([0x9000004 + 0x1000 * j for j in range(16)]), ctypes.c_void_p(0x7000000), 1) == OK
+    assert _plan(raw, b) == [("unshard_lp_kernel", 0, 1, 16 * (S // 8 // 256 + 1))]
+    raw.fsdp_batch_clear(b)
+    # the library's own choice of walk for a lone large update (measured rules): the Llama-7B block over 64 ranks
+    # takes the deep walk (386 workgroups of 1024 chunks), a 16 M-element shard over 8 ranks with 16-bit gradients
+    # the half-chunk walk
     rc, llama = _init(raw, workloads.config(3).units[0].shapes, 64)
     S3 = 3162240
     assert add_update(b, llama, 64, dt=1) == OK
@@ -478,8 +486,13 @@ def test_batches_are_planned_while_they_are_recorded(L):
     raw.fsdp_batch_clear(b)
     rc, w8 = _init(raw, [(8 * 16000000,)], 8)
     assert add_update(b, w8, 8, dt=1) == OK
-    assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(16000000 // 8 + 1) // 256))]
+    assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(16000000 // 4 + 1) // 64))]
     raw.fsdp_batch_clear(b)
+    rc, w8s = _init(raw, [(8 * 8000000,)], 8)       # fp32 gradients, 8 M elements: below the fp32 rule's 12 Mi, wide walk
+    assert add_update(b, w8s, 8, dt=0) == OK
+    assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(8000000 // 4 + 1) // 256))]
+    raw.fsdp_batch_clear(b)
+    raw.fsdp_layout_destroy(w8s)
     raw.fsdp_layout_destroy(llama)
     raw.fsdp_layout_destroy(w8)
     # ... unless its layout asks for the wide walk
