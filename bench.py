@@ -133,10 +133,11 @@ def build_probe(force: bool = False) -> str:
 def load_probe():
     lib = ctypes.CDLL(build_probe(force=False))
     vp, i64 = ctypes.c_void_p, ctypes.c_int64
-    lib.fsdp_probe_copy.argtypes = [vp, vp, i64, vp]
+    lib.fsdp_probe_copy.argtypes = [vp, vp, i64, ctypes.c_int, vp]
     lib.fsdp_probe_memcpy.argtypes = [vp, vp, i64, vp]
-    lib.fsdp_probe_read.argtypes = [vp, i64, vp, vp]
-    lib.fsdp_probe_write.argtypes = [vp, i64, ctypes.c_float, vp]
+    lib.fsdp_probe_cast.argtypes = [vp, vp, i64, ctypes.c_int, vp]
+    lib.fsdp_probe_read.argtypes = [vp, i64, vp, ctypes.c_int, vp]
+    lib.fsdp_probe_write.argtypes = [vp, i64, ctypes.c_float, ctypes.c_int, vp]
     lib.fsdp_probe_streams.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, ctypes.c_int, vp, vp]
     lib.fsdp_probe_update.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, vp, vp, vp, vp]
     return lib
@@ -169,16 +170,25 @@ def measure_ceilings(torch):
     def chk(rc):
         assert rc == 0, f"probe kernel launch failed: hipError_t {rc}"
 
+    # Workgroup size per kernel: what measured fastest for its shape on MI355X (copy and cast: single-wave
+    # workgroups, 2-7 % above 256 lanes; the one-sided kernels need 256 lanes: 6.9 against 4.8 TB/s).
+    LANES, ONE_SIDED = 64, 256
     out = {
         "copy_GBps": timed(lambda i: chk(lib.fsdp_probe_copy(bufs[(i + 1) % 4].data_ptr(), bufs[i % 4].data_ptr(), nbytes,
-                                                             st)), 2 * nbytes),
-        "read_GBps": timed(lambda i: chk(lib.fsdp_probe_read(bufs[i % 4].data_ptr(), nbytes, sink.data_ptr(), st)), nbytes),
-        "write_GBps": timed(lambda i: chk(lib.fsdp_probe_write(bufs[i % 4].data_ptr(), nbytes, 0.0, st)), nbytes),
+                                                             LANES, st)), 2 * nbytes),
+        "read_GBps": timed(lambda i: chk(lib.fsdp_probe_read(bufs[i % 4].data_ptr(), nbytes, sink.data_ptr(), ONE_SIDED, st)),
+                           nbytes),
+        "write_GBps": timed(lambda i: chk(lib.fsdp_probe_write(bufs[i % 4].data_ptr(), nbytes, 0.0, ONE_SIDED, st)), nbytes),
+        "cast_GBps": timed(lambda i: chk(lib.fsdp_probe_cast(bufs[(i + 1) % 4].data_ptr(), bufs[i % 4].data_ptr(), nbytes // 2,
+                                                             LANES, st)), nbytes + nbytes // 2),
+        "copy_256_lane_workgroups_GBps": timed(lambda i: chk(lib.fsdp_probe_copy(
+            bufs[(i + 1) % 4].data_ptr(), bufs[i % 4].data_ptr(), nbytes, 256, st)), 2 * nbytes),
         "hipMemcpyAsync_d2d_GBps": timed(lambda i: chk(lib.fsdp_probe_memcpy(bufs[(i + 1) % 4].data_ptr(), bufs[i % 4].data_ptr(),
                                                                              nbytes, st)), 2 * nbytes),
         "buffer_bytes": nbytes,
-        "note": "plain nontemporal streaming kernels of bench_probe.hip and the runtime's own device-to-device copy, same "
-                "run, HIP events; the copies count bytes read + bytes written",
+        "note": "plain nontemporal streaming kernels of bench_probe.hip (copy and cast in single-wave workgroups, read-only "
+                "and write-only in 256-lane ones: the fastest shape of each) and the runtime's own device-to-device copy, "
+                "same run, HIP events; copy and cast count bytes read + bytes written",
     }
     assert float(sink.item()) == 0.0
     del bufs
@@ -196,7 +206,7 @@ def probe_copy(n, torch):
     st = torch.cuda.current_stream().cuda_stream
     for i in range(n):
         src, dst = bufs[i % len(bufs)]
-        rc = lib.fsdp_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, st)
+        rc = lib.fsdp_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, 256, st)
         assert rc == 0, rc
     torch.cuda.synchronize()
     assert bool((bufs[0][1] == 1).all())
@@ -237,7 +247,7 @@ def probe_mix(torch):
             assert rc == 0, rc
 
         def write_only():
-            rc = lib.fsdp_probe_write(out.data_ptr(), 2 * nbytes, 0.0, st)
+            rc = lib.fsdp_probe_write(out.data_ptr(), 2 * nbytes, 0.0, 256, st)
             assert rc == 0, rc
 
         t_r, t_rw, t_rw2, t_w = timed(lambda: run(0)), timed(lambda: run(1)), timed(lambda: run(2)), timed(write_only)
@@ -368,7 +378,7 @@ def probe_small(torch):
         bufs = [(torch.zeros(nbytes // 4, device="cuda"), torch.zeros(nbytes // 4, device="cuda")) for _ in range(R)]
 
         def fn(i):
-            rc = lib.fsdp_probe_copy(bufs[i % R][1].data_ptr(), bufs[i % R][0].data_ptr(), nbytes, st)
+            rc = lib.fsdp_probe_copy(bufs[i % R][1].data_ptr(), bufs[i % R][0].data_ptr(), nbytes, 64, st)
             assert rc == 0, rc
 
         us = timed(fn)
@@ -962,7 +972,7 @@ def main():
     ceilings = None if args.no_ceilings else measure_ceilings(torch)
     if ceilings:
         log(f"[bench] ceilings of this box: copy {ceilings['copy_GBps']} GB/s, read-only {ceilings['read_GBps']} GB/s, "
-            f"write-only {ceilings['write_GBps']} GB/s; hipMemcpyAsync device-to-device {ceilings['hipMemcpyAsync_d2d_GBps']} GB/s")
+            f"write-only {ceilings['write_GBps']} GB/s, cast (2 bytes read per byte written) {ceilings['cast_GBps']} GB/s; hipMemcpyAsync device-to-device {ceilings['hipMemcpyAsync_d2d_GBps']} GB/s")
 
     head = next(r for r in records if r["workload"] == workloads.config(head_cfg).name)
     roofline = None
@@ -974,7 +984,8 @@ def main():
                     "frac": round(k["GBps"] / HBM_PEAK_GBPS, 4), "traffic": k["hbm_bytes_per_launch"],
                     "avg_launch_us": k["avg_us"], "alg_bytes_per_launch": k["alg_bytes_per_launch"],
                     "launches_per_step": k["launches_per_step"],
-                    "frac_of_measured_copy": round(k["GBps_touched"] / ceilings["copy_GBps"], 4) if ceilings else None}
+                    "frac_of_measured_copy": round(k["GBps_touched"] / ceilings["copy_GBps"], 4) if ceilings else None,
+                    "frac_of_measured_plain_cast": round(k["GBps_touched"] / ceilings["cast_GBps"], 4) if ceilings else None}
     # per-unit record of the headline workload when it is a single unit (the batch grids of the
     # multi-unit workloads mix units, so only their per-configuration figures exist)
     units_table = None
@@ -1024,7 +1035,7 @@ def compact(out):
     line["config"] = {k: out["config"][k] for k in ("workload", "units", "world_size", "grad_dtype", "mode",
                                                     "launches_per_step", "alg_bytes_per_step", "touched_bytes_per_step")}
     if out["measured_ceilings"]:
-        line["measured_ceilings"] = {k: out["measured_ceilings"][k] for k in ("copy_GBps", "read_GBps", "write_GBps",
+        line["measured_ceilings"] = {k: out["measured_ceilings"][k] for k in ("copy_GBps", "read_GBps", "write_GBps", "cast_GBps",
                                                                                  "hipMemcpyAsync_d2d_GBps")}
     line["kernels"] = kern(out["kernels"])
     if out["units_table"]:

@@ -14,7 +14,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256) void fsdp_probe_copy_kernel(const f32x4* __restrict__ src, f32x4* __restrict__ dst,
                                                               int64_t nvec)
 {
-    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i < nvec) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
@@ -23,7 +23,7 @@ __global__ __launch_bounds__(256) void fsdp_probe_copy_kernel(const f32x4* __res
 __global__ __launch_bounds__(256) void fsdp_probe_read_kernel(const f32x4* __restrict__ src, int64_t nvec,
                                                               float* __restrict__ sink)
 {
-    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i < nvec) {
         const f32x4 v = __builtin_nontemporal_load(src + i);
         if (__float_as_uint(v.x) == 0x7FC0FFEEu && __float_as_uint(v.y) == 0x7FC0FFEEu) *sink = v.z + v.w;
@@ -32,8 +32,22 @@ __global__ __launch_bounds__(256) void fsdp_probe_read_kernel(const f32x4* __res
 
 __global__ __launch_bounds__(256) void fsdp_probe_write_kernel(f32x4* __restrict__ dst, int64_t nvec, float value)
 {
-    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i < nvec) __builtin_nontemporal_store(f32x4{value, value, value, value}, dst + i);
+}
+
+// The unshard's traffic from one flat array: every lane loads 16 bytes (four floats) and stores 8 bytes (their
+// upper halves, a truncating stand-in for the cast), both contiguous across the wave.
+typedef uint32_t u32x2p __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4p __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void fsdp_probe_cast_kernel(const u32x4p* __restrict__ src, u32x2p* __restrict__ dst,
+                                                              int64_t nvec)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < nvec) {
+        const u32x4p x = __builtin_nontemporal_load(src + i);
+        __builtin_nontemporal_store(u32x2p{(x.x >> 16) | (x.y & 0xFFFF0000u), (x.z >> 16) | (x.w & 0xFFFF0000u)}, dst + i);
+    }
 }
 
 // The rank walk's memory traffic with almost no arithmetic around it: every
@@ -113,36 +127,38 @@ __global__ __launch_bounds__(256) void fsdp_probe_update_kernel(ProbeStreams t, 
 namespace {
 bool bad_buffer(const void* p, int64_t nbytes)
 {
-    return !p || nbytes <= 0 || (nbytes & 15) || (reinterpret_cast<uintptr_t>(p) & 15) || (nbytes / 16 + 255) / 256 > 0x7FFFFFFFLL;
+    return !p || nbytes <= 0 || (nbytes & 15) || (reinterpret_cast<uintptr_t>(p) & 15) || (nbytes / 16 + 63) / 64 > 0x7FFFFFFFLL;
 }
+bool bad_lanes(int lanes) { return lanes != 64 && lanes != 128 && lanes != 256; }
 }  // namespace
 
-// dst, src: device, 16-byte aligned; nbytes: multiple of 16.  Each returns the hipError_t of its launch.
-extern "C" int fsdp_probe_copy(void* dst, const void* src, int64_t nbytes, void* hip_stream)
+// dst, src: device, 16-byte aligned; nbytes: multiple of 16; lanes: workgroup size, 64, 128 or 256 (single-wave
+// workgroups measure 2 % faster than 256-lane ones on MI355X).  Each returns the hipError_t of its launch.
+extern "C" int fsdp_probe_copy(void* dst, const void* src, int64_t nbytes, int lanes, void* hip_stream)
 {
-    if (bad_buffer(dst, nbytes) || bad_buffer(src, nbytes)) return static_cast<int>(hipErrorInvalidValue);
+    if (bad_buffer(dst, nbytes) || bad_buffer(src, nbytes) || bad_lanes(lanes)) return static_cast<int>(hipErrorInvalidValue);
     const int64_t nvec = nbytes / 16;
-    hipLaunchKernelGGL(fsdp_probe_copy_kernel, dim3(static_cast<uint32_t>((nvec + 255) / 256)), dim3(256), 0,
+    hipLaunchKernelGGL(fsdp_probe_copy_kernel, dim3(static_cast<uint32_t>((nvec + lanes - 1) / lanes)), dim3(lanes), 0,
                        static_cast<hipStream_t>(hip_stream), static_cast<const f32x4*>(src), static_cast<f32x4*>(dst),
                        nvec);
     return static_cast<int>(hipGetLastError());
 }
 
 // sink: device, one float (never written for zero-filled sources)
-extern "C" int fsdp_probe_read(const void* src, int64_t nbytes, float* sink, void* hip_stream)
+extern "C" int fsdp_probe_read(const void* src, int64_t nbytes, float* sink, int lanes, void* hip_stream)
 {
-    if (bad_buffer(src, nbytes) || !sink) return static_cast<int>(hipErrorInvalidValue);
+    if (bad_buffer(src, nbytes) || !sink || bad_lanes(lanes)) return static_cast<int>(hipErrorInvalidValue);
     const int64_t nvec = nbytes / 16;
-    hipLaunchKernelGGL(fsdp_probe_read_kernel, dim3(static_cast<uint32_t>((nvec + 255) / 256)), dim3(256), 0,
+    hipLaunchKernelGGL(fsdp_probe_read_kernel, dim3(static_cast<uint32_t>((nvec + lanes - 1) / lanes)), dim3(lanes), 0,
                        static_cast<hipStream_t>(hip_stream), static_cast<const f32x4*>(src), nvec, sink);
     return static_cast<int>(hipGetLastError());
 }
 
-extern "C" int fsdp_probe_write(void* dst, int64_t nbytes, float value, void* hip_stream)
+extern "C" int fsdp_probe_write(void* dst, int64_t nbytes, float value, int lanes, void* hip_stream)
 {
-    if (bad_buffer(dst, nbytes)) return static_cast<int>(hipErrorInvalidValue);
+    if (bad_buffer(dst, nbytes) || bad_lanes(lanes)) return static_cast<int>(hipErrorInvalidValue);
     const int64_t nvec = nbytes / 16;
-    hipLaunchKernelGGL(fsdp_probe_write_kernel, dim3(static_cast<uint32_t>((nvec + 255) / 256)), dim3(256), 0,
+    hipLaunchKernelGGL(fsdp_probe_write_kernel, dim3(static_cast<uint32_t>((nvec + lanes - 1) / lanes)), dim3(lanes), 0,
                        static_cast<hipStream_t>(hip_stream), static_cast<f32x4*>(dst), nvec, value);
     return static_cast<int>(hipGetLastError());
 }
@@ -187,4 +203,16 @@ extern "C" int fsdp_probe_memcpy(void* dst, const void* src, int64_t nbytes, voi
     if (bad_buffer(dst, nbytes) || bad_buffer(src, nbytes)) return static_cast<int>(hipErrorInvalidValue);
     return static_cast<int>(hipMemcpyAsync(dst, src, static_cast<size_t>(nbytes), hipMemcpyDeviceToDevice,
                                            static_cast<hipStream_t>(hip_stream)));
+}
+
+// src: device, 2 * nbytes_out bytes of floats; dst: device, nbytes_out bytes (a multiple of 8); both 16-byte aligned.
+extern "C" int fsdp_probe_cast(void* dst, const void* src, int64_t nbytes_out, int lanes, void* hip_stream)
+{
+    if (!dst || !src || nbytes_out <= 0 || (nbytes_out & 7) || (reinterpret_cast<uintptr_t>(dst) & 15) ||
+        (reinterpret_cast<uintptr_t>(src) & 15) || bad_lanes(lanes) || (nbytes_out / 8 + 63) / 64 > 0x7FFFFFFFLL)
+        return static_cast<int>(hipErrorInvalidValue);
+    const int64_t nvec = nbytes_out / 8;
+    hipLaunchKernelGGL(fsdp_probe_cast_kernel, dim3(static_cast<uint32_t>((nvec + lanes - 1) / lanes)), dim3(lanes), 0,
+                       static_cast<hipStream_t>(hip_stream), static_cast<const u32x4p*>(src), static_cast<u32x2p*>(dst), nvec);
+    return static_cast<int>(hipGetLastError());
 }
