@@ -83,15 +83,21 @@ void fsdp_layout_destroy(fsdp_layout_t* layout);           /* NULL is a no-op */
  *   FSDP_WALK_WIDE: a lane owns one 16-byte chunk (and loads one to four ranks
  *                   at a time, by gradient dtype);
  *   FSDP_WALK_DEEP: a lane owns four chunks and loads one rank at a time;
- *   FSDP_WALK_HALF: fused updates on 16-bit gradients only (others: as WIDE): a
- *                   lane owns four elements (an 8-byte load per rank), so that
- *                   its accesses to p, m, v are contiguous across the wave, in
- *                   workgroups of 64 lanes;
+ *   FSDP_WALK_HALF: fused updates without hybrid groups, accumulation or
+ *                   unscaling and with at most 64 ranks (others: as AUTO
+ *                   without it): a lane owns four elements (with 16-bit
+ *                   gradients an 8-byte load per rank), keeps one load in
+ *                   flight and reads and writes p, m, v contiguously across
+ *                   the wave, in workgroups of 64 lanes;
  *   FSDP_WALK_AUTO (what fsdp_layout_init uses): the library's choice, from
- *                   measurements on MI355X: deep when the shard fills at
- *                   least 360 deep workgroups (1.5 M fp32 or 2.9 M 16-bit
- *                   elements) and the unit has 16 ranks or more, or 8 to 15
- *                   ranks and fewer than 640 deep workgroups; else wide.
+ *                   measurements on MI355X.  Fused updates that use none of
+ *                   the variants: half with 16-bit gradients up to 16 ranks
+ *                   from 1 Mi elements per shard on, and with fp32 gradients
+ *                   from 8 ranks and 12 Mi elements on.  Otherwise deep when
+ *                   the shard fills at least 360 deep workgroups (1.5 M fp32
+ *                   or 2.9 M 16-bit elements) and the unit has 16 ranks or
+ *                   more, or 8 to 15 ranks and fewer than 640 deep
+ *                   workgroups; else wide.
  * The hint applies to the stand-alone reduce kernels (fsdp_reduce_scatter_local,
  * _adam_fused, _hybrid, _accumulate, _unscale, the two-launch form of
  * _prefetch_unshard and a batch's lone large update); kernels that share a grid

@@ -140,7 +140,12 @@ inline bool pairs_with_large_unshard(const fsdp_layout_t* L, int gt)
     return gt == kF32 && L->reduce_walk != FSDP_WALK_DEEP && L->S < kPairMaxShard;
 }
 
-// The half-chunk walk (fused updates on 16-bit gradients, plain launches only): workgroups of kHalfBlock lanes.
+// The half-chunk walk (plain fused updates only): single-wave workgroups, one load in flight per lane.  Measured
+// on MI355X against the better of the wide and the deep walk, cold buffers (ratio of times):
+//   16-bit gradients: 0.86-0.98 for 2 to 16 ranks at every shard size from 1 M to 113 M elements (the GPT-3-175B
+//     block over 16 ranks: 1052 against 1163 us on the same buffers), even at 24 ranks, 1.0-1.13 from 32 ranks on
+//     (the serial walk over the ranks is then too long a chain), and 1.1-1.4 below 1 M elements;
+//   fp32 gradients: 0.92-0.99 from 8 ranks and 16 M elements on, 1.0-1.07 below 8 M elements.
 constexpr int kHalfBlock = 64;
 constexpr int32_t kHalf16MaxRanks = 16;
 constexpr int64_t kHalf16MinShard = 1 << 20;
@@ -157,11 +162,14 @@ inline bool takes_half(int32_t walk, int gt, int32_t W, int64_t S)
     return walk == FSDP_WALK_AUTO ? half_walk_pays(gt, W, S) : walk == FSDP_WALK_HALF;
 }
 
-// would a stand-alone reduce kernel of this unit take the deep walk (the layout's hint, else the library's choice)?
-inline bool wants_deep(const fsdp_layout_t* L, int gt)
+// does a launch that does not take the half-chunk walk take the deep one?  (A hint for the half-chunk walk leaves
+// this choice to the library.)
+inline bool walks_deep(int32_t walk, int gt, int32_t W, int64_t S)
 {
-    return L->reduce_walk == FSDP_WALK_AUTO ? deep_walk_pays(gt, L->world_size, L->S) : L->reduce_walk == FSDP_WALK_DEEP;
+    return walk == FSDP_WALK_AUTO || walk == FSDP_WALK_HALF ? deep_walk_pays(gt, W, S) : walk == FSDP_WALK_DEEP;
 }
+// would a stand-alone reduce kernel of this unit take the deep walk (the layout's hint, else the library's choice)?
+inline bool wants_deep(const fsdp_layout_t* L, int gt) { return walks_deep(L->reduce_walk, gt, L->world_size, L->S); }
 
 // walk: the layout's hint (FSDP_WALK_*).  The fused deep kernels exist in a
 // plain instantiation as well, for launches that use no hybrid groups,
@@ -187,7 +195,7 @@ void launch_reduce(const PtrTable& tab, const RsArgs& a, int32_t walk, hipStream
             return;
         }
     }
-    const bool deep = walk == FSDP_WALK_AUTO ? deep_walk_pays(GT, a.W, a.S) : walk == FSDP_WALK_DEEP;
+    const bool deep = walks_deep(walk, GT, a.W, a.S);
     const dim3 block(B);
     if (deep) {
         const dim3 grid(static_cast<uint32_t>(ceil_div(a.S / E + 1, B * WalkShape<GT, FUSED, true>::C)));
@@ -1118,7 +1126,7 @@ int32_t step_launches(const fsdp_batch_t* b, const fsdp_batch::Step& s, int32_t 
         if (lone) {   // the stand-alone kernel sizes its own grid by the rank walk it takes
             const RsArgs& a = g.args.r[0].a;
             const int64_t E = g.kind.gt == kF32 ? 4 : 8;
-            const bool deep = g.walk0 == FSDP_WALK_AUTO ? deep_walk_pays(g.kind.gt, a.W, a.S) : g.walk0 == FSDP_WALK_DEEP;
+            const bool deep = walks_deep(g.walk0, g.kind.gt, a.W, a.S);
             *wgs = takes_half(g.walk0, g.kind.gt, a.W, a.S) ? ceil_div(a.S / 4 + 1, kHalfBlock * WalkShape<kBF16, true, false, true>::C)
                                                            : ceil_div(a.S / E + 1, deep ? kReduceBlock * 4 : kReduceBlock);
         }

@@ -101,6 +101,16 @@ __device__ __forceinline__ float post_scale(float x, const RsArgs& a)
 //         workgroup reads 16 KiB of a rank in one piece.  Taken from about 1.4
 //         such workgroups per compute unit on when there are many ranks (the
 //         host's rule and its measurements: deep_walk_pays).
+//   half  (C = 1, G = 1, E = 4 also for 16-bit gradients, which are then loaded 8
+//         bytes at a time; no load ahead): the lightest wave.  Its reads and
+//         writes of p, m, v are 16 bytes per lane, contiguous across the wave,
+//         where a lane that owns eight 16-bit gradients touches 32 bytes of each
+//         state array, so that each of its instructions covers only every other
+//         16 bytes of its span.  In single-wave workgroups, and with only one
+//         load in flight per lane, the occupancy (8 waves per SIMD at 48
+//         registers) is what keeps the memory busy: measured, fewer outstanding
+//         requests serve this mix of reads and read-modify-writes better than
+//         more (deep_walk_pays / half_walk_pays on the host carry the figures).
 // The host pads the pointer table to a multiple of kMaxWideRanks with copies of
 // the last pointer, so loads never need a predicate; the padding's adds are
 // skipped.

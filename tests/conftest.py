@@ -19,9 +19,9 @@ def golden_dir():
 
 
 # GPU tests whose names match run once per rank walk of the reduce-scatter
-# kernels: the library's own choice (wide at test sizes) and the deep walk
-# forced, so that the deep kernels see the ragged, misaligned, split-W, hybrid,
-# accumulate and unscale cases at small sizes too.
+# kernels: the library's own choice (wide at test sizes) and the deep and the
+# half-chunk walk forced, so that those kernels see the ragged, misaligned,
+# split-W, hybrid, accumulate and unscale cases at small sizes too.
 _WALK_TESTS = re.compile(r"reduce|fused|hybrid|accumul|unscale|scaler|whole_path|graph|prefetch|fig3")
 
 
@@ -30,19 +30,20 @@ def pytest_generate_tests(metafunc):
             m.name == "gpu" for m in getattr(metafunc.module, "pytestmark", []) or []):
         return
     if "_reduce_walk" in metafunc.fixturenames and _WALK_TESTS.search(metafunc.function.__name__):
-        metafunc.parametrize("_reduce_walk", ["auto", "deep"], indirect=True)
+        metafunc.parametrize("_reduce_walk", ["auto", "deep", "half"], indirect=True)
 
 
 @pytest.fixture(autouse=True)
 def _reduce_walk(request, monkeypatch):
     """The rank walk is a per-layout hint (fsdp_layout_init_ex): under the
-    "deep" parameter every layout the test creates through the package asks for
-    the deep walk.  Only this test's view of the binding is patched."""
+    "deep" and "half" parameters every layout the test creates through the
+    package asks for that walk.  Only this test's view of the binding is patched."""
     walk = getattr(request, "param", None)
-    if walk != "deep":
+    if walk not in ("deep", "half"):
         yield
         return
     import functools
     import paper_2304_11277_amd as F
-    monkeypatch.setattr(F, "fsdp_layout_init", functools.partial(F.binding.fsdp_layout_init, reduce_walk=F.FSDP_WALK_DEEP))
+    hint = F.FSDP_WALK_DEEP if walk == "deep" else F.FSDP_WALK_HALF
+    monkeypatch.setattr(F, "fsdp_layout_init", functools.partial(F.binding.fsdp_layout_init, reduce_walk=hint))
     yield

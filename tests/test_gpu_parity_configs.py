@@ -123,7 +123,7 @@ def test_config_unit_matches_oracle(F, cfg, unit_index):
         if r == BENCH_RANK:
             bench_ref = (rp.copy(), rm.copy(), rv.copy(), np_bits(p2).copy(), np_bits(m2).copy(), np_bits(v2).copy())
             # both rank walks forced through the layout (one of them is the library's own choice): same bits
-            for walk in (F.FSDP_WALK_WIDE, F.FSDP_WALK_DEEP):
+            for walk in (F.FSDP_WALK_WIDE, F.FSDP_WALK_DEEP, F.FSDP_WALK_HALF):
                 lay_w = F.fsdp_layout_init(unit.shapes, W, reduce_walk=walk)
                 p3, m3, v3 = shards[r].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
                 F.fsdp_reduce_scatter_adam_fused(lay_w, grads, r, pre, post, None, p3, m3, v3, 1, *hp, None)
@@ -234,7 +234,7 @@ def test_config_unit_variants_match_oracle(F, cfg, unit_index):
     z = np.zeros(S, np.float32)
     rp, _, _ = assert_adam_parity(np_f32(p), np_f32(m), np_f32(v), h_shards[r], ref_g, z, z, 1, hp, f"{other} gradients")
     assert same_bits(np_bits(lp_out), oracle.cast_bf16(rp)), "bf16 copy of the updated shard"
-    for walk in (F.FSDP_WALK_WIDE, F.FSDP_WALK_DEEP):
+    for walk in (F.FSDP_WALK_WIDE, F.FSDP_WALK_DEEP, F.FSDP_WALK_HALF):
         lay_w = F.fsdp_layout_init(unit.shapes, W, reduce_walk=walk)
         p3, m3, v3 = shards[r].clone(), torch.zeros(S, device="cuda"), torch.zeros(S, device="cuda")
         F.fsdp_reduce_scatter_adam_fused(lay_w, grads, r, pre, post, None, p3, m3, v3, 1, *hp, None)
