@@ -742,7 +742,7 @@ int fsdp_unshard_lp(const fsdp_layout_t* L, const void* const* lp_shard_ptrs, vo
         if (misaligned(lp_shard_ptrs[w], 2)) return FSDP_ERR_INVALID_ARG;
     }
     if (misaligned(flat_out, 2)) return FSDP_ERR_INVALID_ARG;
-    const int64_t tiles = ceil_div(S / 8 + 1, kBlock);
+    const int64_t tiles = ceil_div(S / 8 + 1, kLightBlock);
     if (!grid_ok(tiles * kMaxRanks)) return FSDP_ERR_OVERFLOW;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     for (int32_t w0 = 0; w0 < W; w0 += kMaxRanks) {
@@ -750,7 +750,7 @@ int fsdp_unshard_lp(const fsdp_layout_t* L, const void* const* lp_shard_ptrs, vo
         PtrTable tab = {};
         for (int32_t j = 0; j < nw; ++j) tab.p[j] = lp_shard_ptrs[w0 + j];
         uint16_t* base = static_cast<uint16_t*>(flat_out) + static_cast<int64_t>(w0) * S;
-        hipLaunchKernelGGL(gather_lp_kernel, dim3(static_cast<uint32_t>(tiles * nw)), dim3(kBlock), 0, st, tab, S,
+        hipLaunchKernelGGL(gather_lp_kernel, dim3(static_cast<uint32_t>(tiles * nw)), dim3(kLightBlock), 0, st, tab, S,
                            base, static_cast<int32_t>(tiles));
         const int rc = launch_status();
         if (rc != FSDP_OK) return rc;
@@ -1121,7 +1121,8 @@ int32_t step_launches(const fsdp_batch_t* b, const fsdp_batch::Step& s, int32_t 
             const bool light = !o.lp && light_unshard_fits(reinterpret_cast<const float* const*>(g.args.ptrs + o.ptr0),
                                                            UL->world_size, UL->S, o.out);
             *kernel = o.lp ? FSDP_KERNEL_GATHER_LP : (light ? FSDP_KERNEL_UNSHARD_LP_LIGHT : FSDP_KERNEL_UNSHARD_LP);
-            *wgs = (light ? ceil_div(UL->S / 4 + 1, kLightBlock) : ceil_div(UL->S / 8 + 1, kBlock)) * UL->world_size;
+            *wgs = (light ? ceil_div(UL->S / 4 + 1, kLightBlock)
+                          : ceil_div(UL->S / 8 + 1, o.lp ? kLightBlock : kBlock)) * UL->world_size;
         }
         if (lone) {   // the stand-alone kernel sizes its own grid by the rank walk it takes
             const RsArgs& a = g.args.r[0].a;
@@ -1153,7 +1154,7 @@ int32_t step_launches(const fsdp_batch_t* b, const fsdp_batch::Step& s, int32_t 
     *n_upd = 0;
     *n_uns = 1;
     *wgs = light ? ceil_div(u.L->S / 4 + 1, kLightBlock) * nw
-                 : ceil_div(u.L->S / (!u.lp && u.dtype == FSDP_F32 ? 4 : 8) + 1, kBlock) * nw;
+                 : ceil_div(u.L->S / (!u.lp && u.dtype == FSDP_F32 ? 4 : 8) + 1, u.lp ? kLightBlock : kBlock) * nw;
     return n;
 }
 }  // namespace

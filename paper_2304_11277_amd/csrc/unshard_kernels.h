@@ -151,6 +151,7 @@ __global__ __launch_bounds__(kBlock) void unshard_f32_kernel(PtrTable shards, in
 // flat_lp[w*S + k] = lp_shard_w[k]; 16-byte destination vectors, sources only
 // 2-byte aligned.  bid = index of the workgroup among the launch's gather
 // workgroups, as in unshard_lp_body.
+template <int B = kBlock>
 __device__ __forceinline__ void gather_lp_body(const void* const* shards, int64_t S, uint16_t* __restrict__ out_base,
                                                int32_t tiles_per_shard, uint32_t bid)
 {
@@ -161,7 +162,7 @@ __device__ __forceinline__ void gather_lp_body(const void* const* shards, int64_
 
     const int64_t head = head_elems(dst, 2, S);
     const int64_t nvec = (S - head) >> 3;
-    const int64_t c = static_cast<int64_t>(tile) * kBlock + threadIdx.x;
+    const int64_t c = static_cast<int64_t>(tile) * B + threadIdx.x;
     if (c < nvec) {
         const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a2*>(src + head + (c << 3)));
         __builtin_nontemporal_store(a, reinterpret_cast<u32x4*>(dst + head + (c << 3)));
@@ -171,15 +172,16 @@ __device__ __forceinline__ void gather_lp_body(const void* const* shards, int64_
         const int64_t ntail = S - tail0;
         const int t = threadIdx.x;
         if (t < head) dst[t] = src[t];
-        if (t >= 64 && t - 64 < ntail) dst[tail0 + t - 64] = src[tail0 + t - 64];
+        if (t >= 32 && t - 32 < ntail) dst[tail0 + t - 32] = src[tail0 + t - 32];
     }
 }
 
-__global__ __launch_bounds__(kBlock) void gather_lp_kernel(PtrTable shards, int64_t S,
-                                                            uint16_t* __restrict__ out_base,
-                                                            int32_t tiles_per_shard)
+// stand-alone: single-wave workgroups (a plain 16-byte copy measures 2 % faster in them than in 256-lane ones)
+__global__ __launch_bounds__(kLightBlock) void gather_lp_kernel(PtrTable shards, int64_t S,
+                                                                 uint16_t* __restrict__ out_base,
+                                                                 int32_t tiles_per_shard)
 {
-    gather_lp_body(shards.p, S, out_base, tiles_per_shard, blockIdx.x);
+    gather_lp_body<kLightBlock>(shards.p, S, out_base, tiles_per_shard, blockIdx.x);
 }
 
 }  // namespace
