@@ -321,7 +321,9 @@ int fsdp_grad_scaler_update(float* scale, int32_t* growth_tracker, const float* 
  * operation of the same kind above 128 MiB, an update above 128 MiB next to an
  * unshard above 128 MiB unless the gradients are fp32 and the shard has fewer
  * than 8.4 M elements, different gradient dtype or divide mode) are issued
- * through their own kernels, in order.  The grids are planned and their kernel
+ * through their own kernels, in order, and so is an operation left alone in its
+ * grid when the stand-alone kernel is the faster one (an unshard; an update
+ * above 128 MiB).  The grids are planned and their kernel
  * arguments written while the batch is recorded; a launch only fills in the
  * Adam constants that depend on the step count.
  * The batch copies the pointer tables; layouts and device buffers must stay
