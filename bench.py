@@ -540,7 +540,11 @@ def build_launches(F, states, flats, args, depth, rank, pre, post, hp):
         if mode == "lp":
             return ("gather_lp_kernel", (lambda t, s=s, buf=buf: F.fsdp_unshard_lp(s.lay, s.lp_tab, buf[:s.P])),
                     s.b_unshard, touched_unshard(s))
-        return ("unshard_lp_kernel", (lambda t, s=s, buf=buf: F.fsdp_unshard(s.lay, s.shard_tab, buf[:s.P])),
+        probe = F.Batch()          # a one-member batch goes out through the same entry point: its plan names the kernel
+        probe.add_unshard(s.lay, s.shard_tab, buf[:s.P])
+        name = probe.launches()[0]["kernel"]
+        probe.close()
+        return (name, (lambda t, s=s, buf=buf: F.fsdp_unshard(s.lay, s.shard_tab, buf[:s.P])),
                 s.b_unshard, touched_unshard(s))
 
     assert all(s.W <= 64 for s in states), "these modes name one kernel per entry point, which holds up to 64 ranks"
