@@ -108,9 +108,9 @@ __device__ __forceinline__ float post_scale(float x, const RsArgs& a)
 //         state array, so that each of its instructions covers only every other
 //         16 bytes of its span.  In single-wave workgroups, and with only one
 //         load in flight per lane, the occupancy (8 waves per SIMD at 48
-//         registers) is what keeps the memory busy: measured, fewer outstanding
-//         requests serve this mix of reads and read-modify-writes better than
-//         more (deep_walk_pays / half_walk_pays on the host carry the figures).
+//         registers) is what keeps the memory busy: measured, this mix of reads
+//         and read-modify-writes moves faster when each wave asks for little at a
+//         time (deep_walk_pays / half_walk_pays on the host carry the figures).
 // The host pads the pointer table to a multiple of kMaxWideRanks with copies of
 // the last pointer, so loads never need a predicate; the padding's adds are
 // skipped.
