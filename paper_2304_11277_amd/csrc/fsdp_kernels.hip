@@ -1103,6 +1103,14 @@ int fsdp_batch_add_reduce_scatter_adam(fsdp_batch_t* b, const fsdp_layout_t* L, 
 namespace {
 // a grid whose only member is one unshard goes out through the stand-alone entry point
 inline bool lone_unshard(const fsdp_batch::Grid& g) { return g.args.n_reduce == 0 && g.args.n_unshard == 1; }
+// a grid whose only member is one update goes out through the stand-alone kernel when that one is the better:
+// above kOneLaunchMaxBytes (it may take the deep walk), or when it takes the half-chunk walk
+inline bool lone_update(const fsdp_batch::Grid& g)
+{
+    if (g.args.n_reduce != 1 || g.args.n_unshard != 0) return false;
+    const RsArgs& a = g.args.r[0].a;
+    return g.large_r > 0 || takes_half(g.walk0, g.kind.gt, a.W, a.S);
+}
 
 // launches of one plan step: (kernel, updates, unshards, workgroups) of launch j of the step; returns the count
 int32_t step_launches(const fsdp_batch_t* b, const fsdp_batch::Step& s, int32_t j, int32_t* kernel, int32_t* n_upd,
@@ -1110,7 +1118,7 @@ int32_t step_launches(const fsdp_batch_t* b, const fsdp_batch::Step& s, int32_t 
 {
     if (s.kind == fsdp_batch::Step::kGrid) {
         const fsdp_batch::Grid& g = b->grids[s.index];
-        const bool lone = g.args.n_reduce == 1 && g.args.n_unshard == 0 && g.large_r > 0;
+        const bool lone = lone_update(g);
         *kernel = lone ? FSDP_KERNEL_REDUCE : FSDP_KERNEL_BATCH;
         *n_upd = g.args.n_reduce;
         *n_uns = g.args.n_unshard;
@@ -1250,9 +1258,8 @@ int fsdp_batch_launch(const fsdp_batch_t* b, int64_t step, void* hip_stream)
             }
             BatchArgs a = g.args;
             for (int32_t i = 0; i < a.n_reduce; ++i) a.r[i].a.adam = consts_for(g.hyper[i]);
-            if (a.n_reduce == 1 && a.n_unshard == 0 && g.large_r > 0) {
-                // the lone update of a unit too large to share a grid goes through the stand-alone kernel,
-                // which may take the deep rank walk
+            if (lone_update(g)) {
+                // the stand-alone kernel, which may take the deep or the half-chunk rank walk
                 PtrTable tab = {};
                 const int32_t W_padded = (a.r[0].a.W + kMaxWideRanks - 1) / kMaxWideRanks * kMaxWideRanks;
                 for (int32_t w = 0; w < W_padded; ++w) tab.p[w] = a.ptrs[a.r[0].ptr0 + w];

@@ -488,6 +488,14 @@ def test_batches_are_planned_while_they_are_recorded(L):
     assert add_update(b, w8, 8, dt=1) == OK
     assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(16000000 // 4 + 1) // 64))]
     raw.fsdp_batch_clear(b)
+    rc, w8m = _init(raw, [(8 * 2000000,)], 8)       # 80 MB of update, 16-bit gradients: alone in its grid it takes the
+    assert add_update(b, w8m, 8, dt=1) == OK        # stand-alone kernel for the half-chunk walk; with fp32 ones it stays
+    assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(2000000 // 4 + 1) // 64))]
+    raw.fsdp_batch_clear(b)
+    assert add_update(b, w8m, 8, dt=0) == OK
+    assert _plan(raw, b) == [("batch_kernel", 1, 0, 2000000 // 4 // 256 + 1)]
+    raw.fsdp_batch_clear(b)
+    raw.fsdp_layout_destroy(w8m)
     rc, w8s = _init(raw, [(8 * 8000000,)], 8)       # fp32 gradients, 8 M elements: below the fp32 rule's 12 Mi, wide walk
     assert add_update(b, w8s, 8, dt=0) == OK
     assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(8000000 // 4 + 1) // 256))]
