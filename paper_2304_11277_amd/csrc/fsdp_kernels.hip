@@ -1103,14 +1103,9 @@ int fsdp_batch_add_reduce_scatter_adam(fsdp_batch_t* b, const fsdp_layout_t* L, 
 namespace {
 // a grid whose only member is one unshard goes out through the stand-alone entry point
 inline bool lone_unshard(const fsdp_batch::Grid& g) { return g.args.n_reduce == 0 && g.args.n_unshard == 1; }
-// a grid whose only member is one update goes out through the stand-alone kernel when that one is the better:
-// above kOneLaunchMaxBytes (it may take the deep walk), or when it takes the half-chunk walk
-inline bool lone_update(const fsdp_batch::Grid& g)
-{
-    if (g.args.n_reduce != 1 || g.args.n_unshard != 0) return false;
-    const RsArgs& a = g.args.r[0].a;
-    return g.large_r > 0 || takes_half(g.walk0, g.kind.gt, a.W, a.S);
-}
+// ... and so does a grid whose only member is one update: the stand-alone kernel may take the deep or the half-chunk
+// walk, and for a small update its few kernel arguments save half a microsecond against the shared kernel's 4 KiB
+inline bool lone_update(const fsdp_batch::Grid& g) { return g.args.n_reduce == 1 && g.args.n_unshard == 0; }
 
 // launches of one plan step: (kernel, updates, unshards, workgroups) of launch j of the step; returns the count
 int32_t step_launches(const fsdp_batch_t* b, const fsdp_batch::Step& s, int32_t j, int32_t* kernel, int32_t* n_upd,

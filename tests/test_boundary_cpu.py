@@ -441,11 +441,11 @@ def test_batches_are_planned_while_they_are_recorded(L):
         assert add_update(b, small, 8) == OK and add_unshard(b, small, 8) == OK
     assert _plan(raw, b) == [("batch_kernel", 6, 6, 6 * (S // 4 // 256 + 1) + 6 * 8 * (S // 8 // 256 + 1))]
     assert add_update(b, small, 8) == OK
-    assert [p[:3] for p in _plan(raw, b)] == [("batch_kernel", 6, 6), ("batch_kernel", 1, 0)]
+    assert [p[:3] for p in _plan(raw, b)] == [("batch_kernel", 6, 6), ("reduce_kernel", 1, 0)]    # alone in its grid
     # another gradient dtype cannot join the open grid; an fp32 unshard goes through its own kernel
     assert add_update(b, small, 8, dt=1) == OK
     assert add_unshard(b, small, 8, dt=0) == OK
-    assert [p[:3] for p in _plan(raw, b)][2:] == [("batch_kernel", 1, 0), ("unshard_f32_kernel", 0, 1)]
+    assert [p[:3] for p in _plan(raw, b)][2:] == [("reduce_kernel", 1, 0), ("unshard_f32_kernel", 0, 1)]
     assert raw.fsdp_batch_clear(b) == OK and _plan(raw, b) == []
     # 65 ranks: each operation is split over two launches of its own kernel
     rc, wide = _init(raw, [(100000,)], 65)
@@ -488,12 +488,12 @@ def test_batches_are_planned_while_they_are_recorded(L):
     assert add_update(b, w8, 8, dt=1) == OK
     assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(16000000 // 4 + 1) // 64))]
     raw.fsdp_batch_clear(b)
-    rc, w8m = _init(raw, [(8 * 2000000,)], 8)       # 80 MB of update, 16-bit gradients: alone in its grid it takes the
-    assert add_update(b, w8m, 8, dt=1) == OK        # stand-alone kernel for the half-chunk walk; with fp32 ones it stays
+    rc, w8m = _init(raw, [(8 * 2000000,)], 8)       # 80 MB of update, alone in its grid: the stand-alone kernel, in the
+    assert add_update(b, w8m, 8, dt=1) == OK        # half-chunk walk with 16-bit gradients, in the deep one with fp32 ones
     assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(2000000 // 4 + 1) // 64))]
     raw.fsdp_batch_clear(b)
     assert add_update(b, w8m, 8, dt=0) == OK
-    assert _plan(raw, b) == [("batch_kernel", 1, 0, 2000000 // 4 // 256 + 1)]
+    assert _plan(raw, b) == [("reduce_kernel", 1, 0, -(-(2000000 // 4 + 1) // 1024))]     # 489 deep workgroups, 8 ranks
     raw.fsdp_batch_clear(b)
     raw.fsdp_layout_destroy(w8m)
     rc, w8s = _init(raw, [(8 * 8000000,)], 8)       # fp32 gradients, 8 M elements: below the fp32 rule's 12 Mi, wide walk
