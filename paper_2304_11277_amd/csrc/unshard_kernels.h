@@ -88,8 +88,10 @@ __global__ __launch_bounds__(kBlock) void unshard_lp_kernel(PtrTable shards, int
 // the form above; the same lane work in workgroups of 128 or 256 lanes stays at
 // 6.5-6.6 TB/s, so this form only exists as a stand-alone kernel.  The host
 // takes it when every shard's loads are 16-byte aligned: with loads that are
-// only 4-byte aligned this form drops to 6.4 TB/s, below the form above, which
-// realigns through LDS at no cost.
+// only 4-byte aligned this form drops to 6.4 TB/s, and realigning through LDS
+// inside a single-wave workgroup to 4.7 TB/s (the round trip through LDS
+// lengthens the life of waves that have nothing else in flight), both below
+// the form above, which realigns through LDS at no cost.
 constexpr int kLightBlock = 64;
 // grid = (tiles per shard, shards): the shard's pointer is fetched together with the other arguments, a wave's
 // whole life being two memory round trips
